@@ -1,0 +1,416 @@
+"""numpy front end of the CPU oracle (test infrastructure, not product).
+
+Loads ``libep_oracle.so`` (built from ``ep_oracle.c`` by ``build_oracle``) and
+adds the command-stream side of the oracle, which is small enough for plain
+Python: the multiset of transfer commands a dispatch must emit (Section 3.1,
+"Types of TransferCmd"), a replay of a drained command log onto the oracle's
+own receive buffer, and a checker for the receiver-side completion fence of
+the low-latency mode (Section 3.3, "partial completion fence").
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this module.  It imports nothing from the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from collections import Counter
+from typing import Dict, Iterable, List, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ep_oracle.c")
+_LIB = os.path.join(_HERE, "libep_oracle.so")
+_lib = None
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the C oracle with gcc.  -ffp-contract=off: no multiply-add is
+    fused unless the source says fmaf."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=gnu11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+               "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build_oracle()
+        L = C.CDLL(_LIB)
+        i32p, u16p, u8p, f32p, f64p = (C.POINTER(C.c_int32), C.POINTER(C.c_uint16), C.POINTER(C.c_uint8),
+                                       C.POINTER(C.c_float), C.POINTER(C.c_double))
+        L.oracle_layout.argtypes = [i32p] + [C.c_int] * 5 + [i32p] * 8
+        L.oracle_layout.restype = C.c_int
+        L.oracle_dispatch_bf16.argtypes = [u16p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           u16p, C.c_long, u8p]
+        L.oracle_dispatch_bf16.restype = C.c_int
+        L.oracle_dispatch_fp8.argtypes = [u16p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                          u8p, f32p, C.c_long, u8p]
+        L.oracle_dispatch_fp8.restype = C.c_int
+        L.oracle_e4m3_decode.argtypes = [C.c_uint8]
+        L.oracle_e4m3_decode.restype = C.c_float
+        L.oracle_e4m3_encode.argtypes = [C.c_float]
+        L.oracle_e4m3_encode.restype = C.c_uint8
+        L.oracle_quant_block.argtypes = [u16p, C.c_int, u8p, f32p]
+        L.oracle_quant_block.restype = None
+        L.oracle_quant_rows.argtypes = [u16p, C.c_int, C.c_int, u8p, f32p]
+        L.oracle_quant_rows.restype = None
+        L.oracle_dequant_rows.argtypes = [u8p, f32p, C.c_long, C.c_int, u16p]
+        L.oracle_dequant_rows.restype = None
+        L.oracle_combine.argtypes = [u16p, f32p, i32p, C.c_int, C.c_int, C.c_int, C.c_long, u16p]
+        L.oracle_combine.restype = C.c_int
+        L.oracle_combine_f64.argtypes = [u16p, f32p, i32p, C.c_int, C.c_int, C.c_int, C.c_long, f64p, f64p]
+        L.oracle_combine_f64.restype = C.c_int
+        L.oracle_f32_to_bf16.argtypes = [C.c_float]
+        L.oracle_f32_to_bf16.restype = C.c_uint16
+        L.oracle_bf16_to_f32.argtypes = [C.c_uint16]
+        L.oracle_bf16_to_f32.restype = C.c_float
+        L.oracle_set_threads.argtypes = [C.c_int]
+        L.oracle_max_threads.restype = C.c_int
+        L.oracle_get_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def _c(a, dt) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def set_threads(n: int) -> None:
+    _load().oracle_set_threads(int(n))
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def get_threads() -> int:
+    return int(_load().oracle_get_threads())
+
+
+# ------------------------------------------------------------------ layout
+def layout(idx: np.ndarray, E: int, R: int) -> Dict[str, np.ndarray]:
+    """idx int32 [S,T,K] (or [T,K]) -> counts, scans, slots (see ep_oracle.c)."""
+    idx = _c(idx, np.int32)
+    if idx.ndim == 2:
+        idx = idx[None]
+    S, T, K = idx.shape
+    o = dict(count=np.zeros((S, E), np.int32), expert_total=np.zeros(E, np.int32),
+             rank_total=np.zeros(R, np.int32), base=np.zeros((S, E), np.int32),
+             expert_offset=np.zeros(E + 1, np.int32), rank_offset=np.zeros(R + 1, np.int32),
+             slot=np.zeros((S, T, K), np.int32), dst_row=np.zeros((S, T, K), np.int32))
+    rc = _load().oracle_layout(_p(idx, C.c_int32), S, T, K, E, R,
+                               *[_p(o[n], C.c_int32) for n in ("count", "expert_total", "rank_total", "base",
+                                                               "expert_offset", "rank_offset", "slot", "dst_row")])
+    if rc != 0:
+        raise ValueError(f"oracle_layout rejected its input (rc={rc})")
+    return o
+
+
+# ---------------------------------------------------------------- dispatch
+def dispatch_bf16(x, idx, dst_row, E_loc: int, recv_rows: int, rank_filter: int = -1,
+                  recv: Optional[np.ndarray] = None, fill: int = 0xA5A5):
+    """x uint16 [T,H]; idx/dst_row int32 [T,K] -> (recv uint16 [recv_rows,H], write_count uint8)."""
+    x = _c(x, np.uint16); idx = _c(idx, np.int32); dst_row = _c(dst_row, np.int32)
+    T, H = x.shape
+    K = idx.shape[1]
+    if recv is None:
+        recv = np.full((recv_rows, H), fill, np.uint16)
+    wc = np.zeros(recv_rows, np.uint8)
+    rc = _load().oracle_dispatch_bf16(_p(x, C.c_uint16), _p(idx, C.c_int32), _p(dst_row, C.c_int32),
+                                      T, K, H, E_loc, rank_filter, _p(recv, C.c_uint16), recv_rows,
+                                      _p(wc, C.c_uint8))
+    if rc != 0:
+        raise ValueError(f"oracle_dispatch_bf16: destination row out of range (rc={rc})")
+    return recv, wc
+
+
+def dispatch_fp8(x, idx, dst_row, E_loc: int, recv_rows: int, rank_filter: int = -1,
+                 recv_q: Optional[np.ndarray] = None, recv_scale: Optional[np.ndarray] = None,
+                 fill: int = 0xA5):
+    x = _c(x, np.uint16); idx = _c(idx, np.int32); dst_row = _c(dst_row, np.int32)
+    T, H = x.shape
+    K = idx.shape[1]
+    if recv_q is None:
+        recv_q = np.full((recv_rows, H), fill, np.uint8)
+    if recv_scale is None:
+        recv_scale = np.full((recv_rows, H // 128), -1.0, np.float32)
+    wc = np.zeros(recv_rows, np.uint8)
+    rc = _load().oracle_dispatch_fp8(_p(x, C.c_uint16), _p(idx, C.c_int32), _p(dst_row, C.c_int32),
+                                     T, K, H, E_loc, rank_filter, _p(recv_q, C.c_uint8),
+                                     _p(recv_scale, C.c_float), recv_rows, _p(wc, C.c_uint8))
+    if rc != 0:
+        raise ValueError(f"oracle_dispatch_fp8: destination row out of range (rc={rc})")
+    return recv_q, recv_scale, wc
+
+
+def e4m3_decode(code: int) -> float:
+    return float(_load().oracle_e4m3_decode(int(code)))
+
+
+def e4m3_encode(y: float) -> int:
+    return int(_load().oracle_e4m3_encode(C.c_float(y)))
+
+
+def e4m3_encode_array(y: np.ndarray) -> np.ndarray:
+    """Encode via quant-free path: element-wise oracle_e4m3_encode."""
+    y = _c(y, np.float32).ravel()
+    L = _load()
+    return np.fromiter((L.oracle_e4m3_encode(C.c_float(v)) for v in y), dtype=np.uint8, count=y.size)
+
+
+def quant_block(v_bits: np.ndarray) -> Tuple[np.ndarray, float]:
+    v = _c(v_bits, np.uint16).ravel()
+    q = np.zeros(v.size, np.uint8)
+    s = C.c_float(0)
+    _load().oracle_quant_block(_p(v, C.c_uint16), v.size, _p(q, C.c_uint8), C.byref(s))
+    return q, float(s.value)
+
+
+def quant_rows(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    x = _c(x, np.uint16)
+    T, H = x.shape
+    q = np.zeros((T, H), np.uint8)
+    s = np.zeros((T, H // 128), np.float32)
+    _load().oracle_quant_rows(_p(x, C.c_uint16), T, H, _p(q, C.c_uint8), _p(s, C.c_float))
+    return q, s
+
+
+def dequant_rows(q: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    q = _c(q, np.uint8); scale = _c(scale, np.float32)
+    rows, H = q.shape
+    y = np.zeros((rows, H), np.uint16)
+    _load().oracle_dequant_rows(_p(q, C.c_uint8), _p(scale, C.c_float), rows, H, _p(y, C.c_uint16))
+    return y
+
+
+# ----------------------------------------------------------------- combine
+def combine(y, w, dst_row) -> np.ndarray:
+    """y uint16 [rows,H]; w float32 [T,K]; dst_row int32 [T,K] -> out uint16 [T,H]."""
+    y = _c(y, np.uint16); w = _c(w, np.float32); dst_row = _c(dst_row, np.int32)
+    rows, H = y.shape
+    T, K = dst_row.shape
+    out = np.zeros((T, H), np.uint16)
+    rc = _load().oracle_combine(_p(y, C.c_uint16), _p(w, C.c_float), _p(dst_row, C.c_int32), T, K, H, rows,
+                                _p(out, C.c_uint16))
+    if rc != 0:
+        raise ValueError("oracle_combine: row out of range")
+    return out
+
+
+def combine_f64(y, w, dst_row) -> Tuple[np.ndarray, np.ndarray]:
+    """Plain fp64 weighted sum and the sum of |terms| (for the error bound)."""
+    y = _c(y, np.uint16); w = _c(w, np.float32); dst_row = _c(dst_row, np.int32)
+    rows, H = y.shape
+    T, K = dst_row.shape
+    out = np.zeros((T, H), np.float64)
+    mag = np.zeros((T, H), np.float64)
+    rc = _load().oracle_combine_f64(_p(y, C.c_uint16), _p(w, C.c_float), _p(dst_row, C.c_int32), T, K, H, rows,
+                                    _p(out, C.c_double), _p(mag, C.c_double))
+    if rc != 0:
+        raise ValueError("oracle_combine_f64: row out of range")
+    return out, mag
+
+
+def f32_to_bf16(a: np.ndarray) -> np.ndarray:
+    a = _c(a, np.float32)
+    L = _load()
+    return np.fromiter((L.oracle_f32_to_bf16(C.c_float(v)) for v in a.ravel()), dtype=np.uint16,
+                       count=a.size).reshape(a.shape)
+
+
+def bf16_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.asarray(b, np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def bf16_ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
+    """Distance in units of representable bf16 values between two bit patterns
+    (sign-magnitude order mapped to a line; +0 and -0 coincide)."""
+    def line(b):
+        b = np.asarray(b, np.uint16).astype(np.int32)
+        mag = b & 0x7FFF
+        return np.where(b & 0x8000, -mag, mag)
+    return np.abs(line(a_bits) - line(b_bits))
+
+
+# ------------------------------------------------------- command stream
+# TransferCmd = four 32-bit words (16 bytes, Section 3.1 "FIFO channels").
+# The paper names the fields (destination peer, offsets, length, sequence)
+# but not their widths; this is the reading the build uses:
+#   w0: [31] lap parity  [30:28] op  [27:20] source (connection) rank
+#       [19:12] destination rank  [11:0] expert index local to the destination
+#   w1: Write: bytes to move;  Atomic: value;  Drain: channel index to drain to
+#   w2: Write: source offset / 16
+#   w3: [31] lap parity  [30:0] Write: destination offset / 16;
+#                               Atomic: counter index src * E_loc + local expert
+OP_WRITE, OP_ATOMIC, OP_DRAIN, OP_BARRIER = 1, 2, 3, 4
+CHUNK_ROWS = 32
+
+
+def row_bytes(H: int, payload: str) -> int:
+    """Bytes one token occupies in a message: bf16 row, or FP8 codes plus one
+    fp32 scale per 128 channels, padded to the 16-byte offset granule."""
+    if payload == "bf16":
+        return 2 * H
+    return (H + H // 32 + 15) // 16 * 16
+
+
+def decode_cmd(words: Iterable[int]) -> Dict[str, int]:
+    w0, w1, w2, w3 = (int(v) & 0xFFFFFFFF for v in words)
+    return dict(gen=w0 >> 31, gen_hi=w3 >> 31, op=(w0 >> 28) & 7, src=(w0 >> 20) & 0xFF,
+                dst_rank=(w0 >> 12) & 0xFF, local_expert=w0 & 0xFFF, w1=w1, src_off=w2 << 4,
+                dst_off=(w3 & 0x7FFFFFFF) << 4, counter=w3 & 0x7FFFFFFF)
+
+
+def expected_cmds(idx_s: np.ndarray, lay: Dict[str, np.ndarray], s: int, E_loc: int, H: int,
+                  payload: str, mode: str, rank_filter: int = -1) -> Counter:
+    """Multiset of commands one dispatch of source rank s must push.
+
+    per_token: one Write per valid (t,k).  chunk32: per expert one Write per
+    run of <= 32 consecutive slots.  Both: one Atomic per destination expert
+    carrying count[s][e] (also when it is 0), the doorbell the receiver holds
+    back until that many writes arrived.  Keys are tuples
+    (op, src, dst_rank, local_expert, w1, src_off, dst_off_or_counter).
+    """
+    rb = row_bytes(H, payload)
+    E = lay["count"].shape[1]
+    out: Counter = Counter()
+    T, K = idx_s.shape
+    passes = lambda e: rank_filter < 0 or e // E_loc == rank_filter
+    if mode == "per_token":
+        for t in range(T):
+            for k in range(K):
+                e = int(idx_s[t, k])
+                if e < 0 or not passes(e):
+                    continue
+                row = int(lay["dst_row"][s, t, k])
+                out[(OP_WRITE, s, e // E_loc, e % E_loc, rb, t * rb, row * rb)] += 1
+    elif mode == "chunk32":
+        for e in range(E):
+            if not passes(e):
+                continue
+            c = int(lay["count"][s, e]); b = int(lay["base"][s, e])
+            for j in range(0, c, CHUNK_ROWS):
+                n = min(CHUNK_ROWS, c - j)
+                out[(OP_WRITE, s, e // E_loc, e % E_loc, n * rb, (b + j) * rb, (b + j) * rb)] += 1
+    elif mode != "none":
+        raise ValueError(mode)
+    if mode != "none":
+        for e in range(E):
+            if passes(e):
+                out[(OP_ATOMIC, s, e // E_loc, e % E_loc, int(lay["count"][s, e]), 0,
+                     s * E_loc + e % E_loc)] += 1
+    return out
+
+
+def cmd_multiset(log_words: np.ndarray, ops=(OP_WRITE, OP_ATOMIC)) -> Counter:
+    """Multiset (same key shape as expected_cmds) of a drained command log uint32 [n,4]."""
+    out: Counter = Counter()
+    for w in np.asarray(log_words, np.uint32).reshape(-1, 4):
+        d = decode_cmd(w)
+        if d["op"] not in ops:
+            continue
+        if d["op"] == OP_WRITE:
+            out[(OP_WRITE, d["src"], d["dst_rank"], d["local_expert"], d["w1"], d["src_off"], d["dst_off"])] += 1
+        else:
+            out[(OP_ATOMIC, d["src"], d["dst_rank"], d["local_expert"], d["w1"], 0, d["counter"])] += 1
+    return out
+
+
+def replay_writes_per_token(log_words: np.ndarray, x_rows: np.ndarray, recv_rows: int,
+                            fill_byte: int = 0xA5) -> Tuple[np.ndarray, np.ndarray]:
+    """Apply the Write commands of a per-token log to a fresh receive buffer:
+    each command moves `len` bytes from offset src_off of the packed send rows
+    (x_rows: uint8 [T, row_bytes]) to offset dst_off of the receive heap.
+    Shows the commands alone determine the receive buffer."""
+    rb = x_rows.shape[1]
+    heap = np.full(recv_rows * rb, fill_byte, np.uint8)
+    hits = np.zeros(recv_rows, np.int32)
+    src = np.ascontiguousarray(x_rows).reshape(-1)
+    for w in np.asarray(log_words, np.uint32).reshape(-1, 4):
+        d = decode_cmd(w)
+        if d["op"] != OP_WRITE:
+            continue
+        n, so, do = d["w1"], d["src_off"], d["dst_off"]
+        if so + n > src.size or do + n > heap.size or n % rb or do % rb:
+            raise ValueError(f"command outside the registered regions: {d}")
+        heap[do:do + n] = src[so:so + n]
+        hits[do // rb:(do + n) // rb] += 1
+    return heap.reshape(recv_rows, rb), hits
+
+
+def check_chunk_cover(log_words: np.ndarray, lay: Dict[str, np.ndarray], s: int, E_loc: int, rb: int) -> None:
+    """chunk32 logs: the Writes of source s must tile exactly the rows
+    [base[s][e], base[s][e]+count[s][e]) of every destination expert, each chunk
+    inside one expert, none longer than 32 rows."""
+    E = lay["count"].shape[1]
+    covered = np.zeros(int(lay["expert_offset"][E]), np.int32)
+    for w in np.asarray(log_words, np.uint32).reshape(-1, 4):
+        d = decode_cmd(w)
+        if d["op"] != OP_WRITE or d["src"] != s:
+            continue
+        e = d["dst_rank"] * E_loc + d["local_expert"]
+        r0, n = d["dst_off"] // rb, d["w1"] // rb
+        assert d["dst_off"] % rb == 0 and d["w1"] % rb == 0 and 1 <= n <= CHUNK_ROWS, d
+        b, c = int(lay["base"][s, e]), int(lay["count"][s, e])
+        assert b <= r0 and r0 + n <= b + c and (r0 - b) % CHUNK_ROWS == 0, (d, b, c)
+        covered[r0:r0 + n] += 1
+    want = np.zeros_like(covered)
+    for e in range(E):
+        b, c = int(lay["base"][s, e]), int(lay["count"][s, e])
+        want[b:b + c] = 1
+    assert np.array_equal(covered, want), "chunk writes do not tile the destination rows exactly once"
+
+
+# Receiver-side event log (one record = 4 x uint32):
+#   [0] kind | thread << 8   kind 1: Write delivered (value = rows it carried)
+#                            kind 2: Atomic delivered (value = X)
+#                            kind 3: Atomic applied   (value = X)
+#   [1] source rank   [2] global expert   [3] value
+EV_WRITE, EV_ATOMIC_IN, EV_ATOMIC_APPLIED = 1, 2, 3
+
+
+def check_fence_trace(events: np.ndarray, count: np.ndarray) -> Dict[str, int]:
+    """Completion-fence check (Section 3.3): within the receiving thread's own
+    order, an Atomic(src, e, X) may only be applied once at least X rows for
+    (src, e) were delivered; rows for other experts do not count; every
+    delivered atomic is applied exactly once; the final counters equal count.
+    Returns how many atomics had to wait."""
+    ev = np.asarray(events, np.uint32).reshape(-1, 4)
+    seen: Dict[Tuple[int, int], int] = {}
+    pending: Dict[Tuple[int, int], List[int]] = {}
+    owner: Dict[Tuple[int, int], int] = {}
+    applied: Dict[Tuple[int, int], int] = {}
+    waited = 0
+    for kind_thr, src, e, val in ev.tolist():
+        kind, thr = kind_thr & 0xFF, kind_thr >> 8
+        key = (src, e)
+        assert owner.setdefault(key, thr) == thr, f"(src,expert) {key} handled by two threads"
+        if kind == EV_WRITE:
+            seen[key] = seen.get(key, 0) + val
+        elif kind == EV_ATOMIC_IN:
+            pending.setdefault(key, []).append(val)
+            if seen.get(key, 0) < val:
+                waited += 1
+        elif kind == EV_ATOMIC_APPLIED:
+            assert key in pending and val in pending[key], f"atomic applied but never delivered: {key} {val}"
+            pending[key].remove(val)
+            assert seen.get(key, 0) >= val, (
+                f"fence violated: atomic X={val} for {key} applied after only {seen.get(key, 0)} rows")
+            applied[key] = val
+        else:
+            raise AssertionError(f"unknown event kind {kind}")
+    left = {k: v for k, v in pending.items() if v}
+    assert not left, f"atomics delivered but never applied: {left}"
+    S, E = count.shape
+    for (src, e), val in applied.items():
+        assert int(count[src, e]) == val, f"counter ({src},{e}) = {val}, layout says {int(count[src, e])}"
+    return dict(waited=waited, applied=len(applied))

@@ -1,0 +1,126 @@
+"""Pins for the command-stream side of the oracle (CPU only): the multiset of
+transfer commands a dispatch must emit, the replay of a command log, and the
+completion-fence checker.  Mistakes are planted on the CPU, in hand-built logs."""
+import numpy as np
+import pytest
+
+import ep_inputs as g
+
+
+def _encode(op, src, dst_rank, local, w1, src_off, dst_or_counter, gen=1):
+    """Build the four words by hand from the documented bit layout."""
+    w0 = (gen << 31) | (op << 28) | (src << 20) | (dst_rank << 12) | local
+    w3 = (gen << 31) | (dst_or_counter >> 4 if op == 1 else dst_or_counter)
+    return [w0, w1, src_off >> 4, w3]
+
+
+def _log_from(ms):
+    rows = []
+    for key, n in ms.items():
+        rows += [_encode(*key)] * n
+    return np.array(rows, np.uint32).reshape(-1, 4)
+
+
+@pytest.mark.parametrize("payload", ["bf16", "fp8"])
+def test_expected_per_token_commands_replay_to_the_dispatch_result(oracle, payload):
+    cfg = g.config(1)
+    idx, _ = g.routing(cfg)
+    idx = g.mask_random(idx, 0.2, seed=2)
+    x = g.activations(cfg)
+    lay = oracle.layout(idx, cfg.E, cfg.R)
+    rows = int((idx >= 0).sum())
+    ms = oracle.expected_cmds(idx, lay, 0, cfg.E_loc, cfg.H, payload, "per_token")
+    nW = sum(n for k, n in ms.items() if k[0] == oracle.OP_WRITE)
+    nA = sum(n for k, n in ms.items() if k[0] == oracle.OP_ATOMIC)
+    assert nW == rows and nA == cfg.E
+    rb = oracle.row_bytes(cfg.H, payload)
+    assert sum(k[4] * n for k, n in ms.items() if k[0] == oracle.OP_WRITE) == rows * rb
+    assert sum(k[4] * n for k, n in ms.items() if k[0] == oracle.OP_ATOMIC) == rows
+    log = _log_from(ms)
+    assert oracle.cmd_multiset(log) == ms                       # decode is the inverse of the layout
+    if payload == "bf16":
+        send = x.view(np.uint8).reshape(cfg.T, rb)
+        want, _ = oracle.dispatch_bf16(x, idx, lay["dst_row"][0], cfg.E_loc, rows, fill=0xA5A5)
+        want = want.view(np.uint8).reshape(rows, rb)
+    else:
+        q, s = oracle.quant_rows(x)
+        send = np.zeros((cfg.T, rb), np.uint8)
+        send[:, :cfg.H] = q
+        send[:, cfg.H:cfg.H + cfg.H // 32] = s.view(np.uint8).reshape(cfg.T, -1)
+        rq, rs, _ = oracle.dispatch_fp8(x, idx, lay["dst_row"][0], cfg.E_loc, rows)
+        want = np.zeros((rows, rb), np.uint8)
+        want[:, :cfg.H] = rq
+        want[:, cfg.H:cfg.H + cfg.H // 32] = rs.view(np.uint8).reshape(rows, -1)
+    heap, hits = oracle.replay_writes_per_token(log, send, rows)
+    assert (hits == 1).all()
+    assert np.array_equal(heap[:, :want.shape[1]], want)
+
+
+def test_row_bytes(oracle):
+    assert oracle.row_bytes(7168, "bf16") == 14336
+    assert oracle.row_bytes(7168, "fp8") == 7168 + 224          # the paper's "7 KB" token
+    assert oracle.row_bytes(128, "fp8") == 144                  # 132 padded to the 16-byte granule
+
+
+def test_expected_chunk_commands_tile_every_expert(oracle):
+    cfg = g.config(4)
+    idx, _ = g.routing(cfg, 0, 300)
+    lay = oracle.layout(idx, cfg.E, cfg.R)
+    ms = oracle.expected_cmds(idx, lay, 0, cfg.E_loc, cfg.H, "bf16", "chunk32")
+    nW = sum(n for k, n in ms.items() if k[0] == oracle.OP_WRITE)
+    assert nW == int(np.ceil(lay["count"][0] / 32).sum())
+    log = _log_from(ms)
+    oracle.check_chunk_cover(log, lay, 0, cfg.E_loc, oracle.row_bytes(cfg.H, "bf16"))
+    # planted mistakes: a dropped chunk, a chunk that crosses into the next expert
+    writes = [i for i, w in enumerate(log) if oracle.decode_cmd(w)["op"] == oracle.OP_WRITE]
+    with pytest.raises(AssertionError):
+        oracle.check_chunk_cover(np.delete(log, writes[3], axis=0), lay, 0, cfg.E_loc, 14336)
+    bad = log.copy()
+    bad[writes[0], 1] += 14336
+    with pytest.raises(AssertionError):
+        oracle.check_chunk_cover(bad, lay, 0, cfg.E_loc, 14336)
+    # filter keeps only one rank's experts
+    ms2 = oracle.expected_cmds(idx, lay, 0, cfg.E_loc, cfg.H, "bf16", "chunk32", rank_filter=3)
+    assert all(k[2] == 3 for k in ms2)
+    assert sum(n for k, n in ms2.items() if k[0] == oracle.OP_ATOMIC) == cfg.E_loc
+
+
+def test_replay_rejects_out_of_region_commands(oracle):
+    send = np.zeros((4, 64), np.uint8)
+    ok = np.array([_encode(1, 0, 0, 0, 64, 64, 128)], np.uint32)
+    oracle.replay_writes_per_token(ok, send, 3)
+    for bad in (_encode(1, 0, 0, 0, 64, 64 * 4, 0), _encode(1, 0, 0, 0, 64, 0, 64 * 3),
+                _encode(1, 0, 0, 0, 48, 0, 0)):
+        with pytest.raises(ValueError):
+            oracle.replay_writes_per_token(np.array([bad], np.uint32), send, 3)
+
+
+def _ev(kind, src, e, val, thr=0):
+    return [kind | (thr << 8), src, e, val]
+
+
+def test_fence_checker_accepts_valid_and_catches_planted_violations(oracle):
+    count = np.array([[2, 1, 0]], np.int32)
+    W, A, AP = oracle.EV_WRITE, oracle.EV_ATOMIC_IN, oracle.EV_ATOMIC_APPLIED
+    good = [_ev(A, 0, 0, 2), _ev(W, 0, 0, 1), _ev(W, 0, 1, 1), _ev(A, 0, 1, 1), _ev(AP, 0, 1, 1),
+            _ev(W, 0, 0, 1), _ev(AP, 0, 0, 2), _ev(A, 0, 2, 0), _ev(AP, 0, 2, 0)]
+    r = oracle.check_fence_trace(np.array(good, np.uint32), count)
+    assert r == dict(waited=1, applied=3)
+    # applied before its writes arrived (writes to another expert must not count)
+    early = [_ev(A, 0, 0, 2), _ev(W, 0, 0, 1), _ev(W, 0, 1, 1), _ev(AP, 0, 0, 2), _ev(W, 0, 0, 1)]
+    with pytest.raises(AssertionError, match="fence violated"):
+        oracle.check_fence_trace(np.array(early, np.uint32), count)
+    # never applied
+    with pytest.raises(AssertionError, match="never applied"):
+        oracle.check_fence_trace(np.array(good[:6], np.uint32), count)
+    # applied without having been delivered
+    with pytest.raises(AssertionError, match="never delivered"):
+        oracle.check_fence_trace(np.array([_ev(W, 0, 1, 1), _ev(AP, 0, 1, 1)], np.uint32), count)
+    # wrong final value
+    wrong = [_ev(W, 0, 1, 1), _ev(A, 0, 1, 1), _ev(AP, 0, 1, 1)]
+    with pytest.raises(AssertionError, match="layout says"):
+        oracle.check_fence_trace(np.array(wrong, np.uint32), np.array([[0, 2, 0]], np.int32))
+    # one (src, expert) handled by two threads breaks the share-nothing rule
+    two = [_ev(W, 0, 1, 1, thr=0), _ev(A, 0, 1, 1, thr=1)]
+    with pytest.raises(AssertionError, match="two threads"):
+        oracle.check_fence_trace(np.array(two, np.uint32), count)
