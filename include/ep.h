@@ -1,0 +1,236 @@
+/*
+ * ep.h - C ABI of the MI355X expert-parallel dispatch/combine library (libep.so).
+ *
+ * One GPU runs its share of an expert-parallel (EP) group; the other EP ranks
+ * are partitions of this GPU's HBM.  The calls follow the paper's statement of
+ * the problem: tokens are dispatched to the ranks hosting their selected
+ * experts and expert outputs are combined back in the original token order
+ * (Section 2.1); transfers are initiated by the GPU as 16-byte commands pushed
+ * into FIFO channels that a multithreaded CPU proxy drains (Section 3.1, 3.2);
+ * the proxy enforces the receiver-side completion fence of the low-latency
+ * mode with 32-bit immediate data and posts completion counters in pinned
+ * host memory (Section 3.3, Section 4.1).
+ *
+ * Conventions
+ *  - Every function returns 0 (EP_OK) or a negative ep_status; nothing is thrown.
+ *  - Pointers named d_* are DEVICE pointers owned by the caller, 16-byte
+ *    aligned, valid until the stream work that uses them has finished.
+ *    All other pointers are HOST pointers.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *    ep_layout / ep_dispatch / ep_combine only enqueue work on it and never
+ *    synchronise the device.  Calls on one handle must be ordered on one
+ *    stream (or otherwise serialised): they share the handle's scratch.
+ *  - Argument errors found on the host return EP_EINVAL before anything is
+ *    launched.  Errors found on the device (a destination row outside the
+ *    receive buffer, an expert id outside [-1, E), a ring wait that timed out)
+ *    skip the offending element, set a sticky error word and are reported by
+ *    ep_wait / ep_stats as EP_EBOUNDS / EP_ETIMEOUT.
+ *  - The library never falls back to the CPU: without a usable HIP device the
+ *    compute entry points return EP_EHIP.
+ *
+ * Notation: R ranks, E experts (expert e lives on rank e / (E/R)), K = top-k,
+ * T tokens of one source rank, H hidden size, S source ranks whose routing is
+ * given.  bf16 data is raw 16-bit patterns.
+ */
+#ifndef EP_H_
+#define EP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ep_handle ep_handle; /* opaque, owned by the library */
+
+enum ep_status {
+  EP_OK = 0,
+  EP_EINVAL = -1,   /* bad argument or configuration                       */
+  EP_ENOMEM = -2,   /* host or device allocation failed                    */
+  EP_ESTATE = -3,   /* call not valid for this handle (e.g. host-only)     */
+  EP_EHIP = -4,     /* a HIP runtime call failed / no device               */
+  EP_ETIMEOUT = -5, /* a bounded wait (GPU ring push, ep_wait) expired     */
+  EP_EBOUNDS = -6   /* an offset, row or expert id was out of range        */
+};
+
+/* Dispatch payload (Section 2.1: a token is ~7 KB in FP8 at hidden 7168). */
+enum ep_payload {
+  EP_BF16 = 0,     /* rows of H bf16                                               */
+  EP_FP8_E4M3 = 1  /* rows of H OCP-E4M3 codes + one fp32 scale per 128 channels   */
+};
+
+/* How the dispatch kernel drives the control channel (Section 3.3: the
+ * low-latency mode sends every token on its own; the high-throughput mode
+ * moves chunks of typically 32 tokens). */
+enum ep_cmd_mode {
+  EP_CMD_PER_TOKEN = 0,       /* one Write command per (token, expert)                 */
+  EP_CMD_CHUNK32 = 1,         /* one Write per run of <= 32 consecutive rows of an expert */
+  EP_CMD_NONE = 2,            /* ring off: payload placement only                      */
+  EP_CMD_MODE_MASK = 0xFF,
+  EP_CMD_ATOMICS_FIRST = 0x100, /* push every count Atomic before any Write (forces the fence path) */
+  EP_CMD_DRAIN = 0x200          /* last wave pushes Drain on every channel and blocks on Check-completion */
+};
+
+enum ep_flags {
+  EP_FLAG_LOG_CMDS = 1,   /* proxy keeps every polled command (ep_cmd_log)          */
+  EP_FLAG_LOG_EVENTS = 2, /* proxy keeps the receiver-side event trace (ep_event_log) */
+  EP_FLAG_HOST_ONLY = 4   /* no device: ring + proxy only, producer is ep_host_push  */
+};
+
+typedef struct ep_config {
+  int32_t num_ranks;         /* R, 1..256                                              */
+  int32_t num_experts;       /* E, multiple of R, <= 1024                              */
+  int32_t top_k;             /* K, 1..64                                               */
+  int32_t hidden;            /* H, multiple of 128, <= 65536                           */
+  int32_t max_tokens;        /* capacity in tokens per source rank, < 2^19             */
+  int32_t num_src;           /* S >= 1, <= 256                                         */
+  int32_t self_rank;         /* this GPU's rank, informational                         */
+  int32_t num_channels;      /* FIFO channels C, 1..64 (the paper runs 8)              */
+  int32_t ring_entries;      /* slots per channel = the paper's kMaxInflight; power of two >= 2 */
+  int32_t num_proxy_threads; /* 0..16 (the paper runs 4); channel c belongs to thread c mod N   */
+  int32_t reorder_window;    /* test hook: receiver sees up to this many immediates out of order; 0 = in order */
+  int32_t spin_timeout_ms;   /* bound of every GPU-side and host-side wait; 0 = 5000   */
+  uint64_t reorder_seed;
+  int64_t heap_rows;         /* rows of the registered receive heap; 0 = S * max_tokens * K */
+  int32_t flags;             /* ep_flags                                               */
+  int32_t reserved;
+} ep_config;
+
+typedef struct ep_stats_t {
+  uint64_t cmds;             /* commands polled by all proxy threads                   */
+  uint64_t writes, atomics, drains;
+  uint64_t write_bytes;      /* sum of Write lengths                                   */
+  uint64_t write_rows;       /* sum of rows carried by Writes                          */
+  uint64_t atomics_applied;
+  uint64_t atomics_deferred; /* atomics that had to wait in the control buffer         */
+  uint64_t rejected;         /* commands that failed offset translation / bounds check */
+  uint64_t gpu_ring_full;    /* times a GPU push found its channel full                */
+  uint64_t first_poll_ns;    /* CLOCK_MONOTONIC of the first command seen since ep_reset_stats */
+  uint64_t last_apply_ns;    /* ... and of the last atomic applied                     */
+  uint64_t per_thread_cmds[16];
+  int32_t device_error;      /* sticky ep_status set by a kernel, 0 if none            */
+  int32_t proxy_error;       /* sticky ep_status set by the proxy, 0 if none           */
+} ep_stats_t;
+
+/* ep_proxy_start - create a handle: validates *cfg, allocates the pinned-host
+ * command rings, head indices and completion counters (Section 3.1: head on the
+ * CPU, tail and a cached copy of the head on the GPU), device scratch, and
+ * starts num_proxy_threads proxy threads that share no state (Section 3.2).
+ * *out receives the handle.  EP_EINVAL / EP_ENOMEM / EP_EHIP on failure. */
+int ep_proxy_start(const ep_config *cfg, ep_handle **out);
+
+/* ep_proxy_stop - waits for enqueued device work of the handle, stops and
+ * joins the proxy threads, frees everything.  The handle is dead afterwards. */
+int ep_proxy_stop(ep_handle *h);
+
+/* ep_layout - "dynamically size and route messages every step" (Section 2.1,
+ * Irregular communication): from the router's top-k expert ids compute
+ *   count[s][e]      tokens of source s that chose expert e
+ *   expert_total[e], rank_total[r]
+ *   base[s][e]       first receive row of (s, e): rows are expert-major,
+ *                    source-minor; expert_offset[E+1], rank_offset[R+1] are
+ *                    the exclusive scans with end sentinels
+ *   slot[s,t,k]      number of earlier tokens of s that chose the same expert
+ *   dst_row[s,t,k]   base + slot
+ * d_topk_idx is int32 [S,T,K], -1 = masked entry (slot = dst_row = -1); the
+ * unmasked experts of one token must be distinct.  T <= max_tokens.  All
+ * outputs are int32 device arrays of the shapes named above. */
+int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T,
+              int32_t *d_count, int32_t *d_expert_total, int32_t *d_rank_total,
+              int32_t *d_base, int32_t *d_expert_offset, int32_t *d_rank_offset,
+              int32_t *d_slot, int32_t *d_dst_row, void *stream);
+
+/* ep_dispatch - the dispatch phase (Section 2.1) for the T tokens of source
+ * rank src_rank: every valid (t,k) whose expert lives on dst_rank_filter (or on
+ * any rank if -1) gets x[t,:] written to receive row dst_row[t,k]:
+ *   EP_BF16      d_recv is bf16 [recv_rows, H]; d_recv_scale must be NULL
+ *   EP_FP8_E4M3  d_recv is uint8 [recv_rows, H], d_recv_scale fp32 [recv_rows, H/128]
+ *                per 128-channel block: scale = amax/448 (1 if amax < 2^-100),
+ *                code = e4m3_rne_sat(x * (448/amax)).
+ * d_x bf16 [T,H]; d_topk_idx, d_dst_row int32 [T,K]; d_count, d_base int32 [E]
+ * are row src_rank of ep_layout's outputs.  Rows not addressed keep their
+ * contents.  Unless cmd_mode is EP_CMD_NONE the kernel also pushes the
+ * transfer commands of Section 3.1 into the handle's FIFO channels (channel =
+ * destination rank mod C): Writes at the granularity cmd_mode selects, after
+ * the rows they describe are stored, and per destination expert one Atomic
+ * carrying count[e] (also when 0).  A full channel blocks the pushing wave
+ * until the proxy pops (bounded by spin_timeout_ms). */
+int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
+                const int32_t *d_dst_row, const int32_t *d_count, const int32_t *d_base,
+                int32_t T, int32_t src_rank, int32_t dst_rank_filter,
+                int32_t payload, int32_t cmd_mode,
+                void *d_recv, float *d_recv_scale, int64_t recv_rows, void *stream);
+
+/* ep_combine - the combine phase (Section 2.1, 2.2: a weighted-sum reduce in
+ * the original token order):
+ *   out[t,:] = bf16( sum_k w[t,k] * y[dst_row[t,k], :] )
+ * fp32 accumulator starting at +0, k ascending, fused multiply-add, one final
+ * round-to-nearest-even; k with dst_row == -1 are skipped.  d_y bf16
+ * [y_rows,H]; d_topk_w fp32 [T,K]; d_dst_row int32 [T,K]; d_out bf16 [T,H]. */
+int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w,
+               const int32_t *d_dst_row, int32_t T, int64_t y_rows,
+               void *d_out, void *stream);
+
+/* ep_wait - host-blocks until the proxy has applied the count Atomic of every
+ * destination expert of every dispatch enqueued so far (the data of those
+ * dispatches is then in place and its counters are posted), or returns the
+ * sticky device/proxy error, or EP_ETIMEOUT after spin_timeout_ms. */
+int ep_wait(ep_handle *h);
+
+/* ep_counters - *recv_count points at the pinned-host completion counters,
+ * int32 [S, E] ([source][global expert]), written by the proxy when it applies
+ * an Atomic (Section 4.1: host-allocated counters the GPU may also read).
+ * *d_recv_count (may be NULL) receives the same memory's device address. */
+int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv_count);
+
+/* ep_stats / ep_reset_stats - proxy and ring statistics.  Reset also zeroes
+ * the completion counters; call it only when ep_wait has returned. */
+int ep_stats(ep_handle *h, ep_stats_t *out);
+int ep_reset_stats(ep_handle *h);
+
+/* ep_cmd_log - copies up to cap commands (16 bytes each, as polled, thread by
+ * thread, in-channel order preserved) into buf; *n = number available.
+ * Needs EP_FLAG_LOG_CMDS; call after ep_wait.
+ * ep_event_log - same for the receiver-side trace (4 x uint32 per record:
+ * kind | thread << 8, source rank, global expert, value; kind 1 = Write
+ * delivered (value = rows), 2 = Atomic delivered, 3 = Atomic applied). */
+int ep_cmd_log(ep_handle *h, void *buf, size_t cap, size_t *n);
+int ep_event_log(ep_handle *h, void *buf, size_t cap, size_t *n);
+
+/* Host-side producer for the same ring protocol, for handles made with
+ * EP_FLAG_HOST_ONLY (tests and diagnostics of the proxy without a GPU; the
+ * device-side Push lives in the kernels).  ep_host_push implements Push: it
+ * blocks while channel is full (bounded by spin_timeout_ms), writes the four
+ * words (lap-parity bits are set by the call) and returns the command's Idx.
+ * ep_host_check_completion implements Check-completion(Idx): 1 if the proxy
+ * has popped command idx of that channel, else 0. */
+int ep_host_push(ep_handle *h, int32_t channel, uint32_t w0, uint32_t w1, uint32_t w2,
+                 uint32_t w3, uint64_t *idx);
+int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx);
+/* Tells the proxy how many count Atomics ep_wait should expect in addition
+ * (ep_dispatch does this itself for its own). */
+int ep_host_expect_atomics(ep_handle *h, int32_t n);
+
+/* ep_last_error - text describing the most recent failed HIP runtime call made
+ * by the library on the calling thread ("" if none).  Static storage. */
+const char *ep_last_error(void);
+
+/* TransferCmd, 128 bits = four 32-bit words (Section 3.1 names the fields,
+ * not their widths; this is the layout of this library):
+ *   w0 [31] lap parity  [30:28] op  [27:20] source (connection) rank
+ *      [19:12] destination rank  [11:0] expert index local to the destination
+ *   w1 Write : [31:26] rows carried - 1, [25:0] length / 16
+ *      Atomic: value      Drain: unused
+ *   w2 Write : source offset / 16
+ *   w3 [31] lap parity  [30:0] Write: destination offset / 16
+ *                              Atomic: counter index = source * (E/R) + local expert
+ * The lap parity of slot Idx is ((Idx / ring_entries) & 1) ^ 1; a slot is
+ * ready when both parity bits match the lap the consumer is on.  The sequence
+ * number of a command is its Idx (order inside one channel is kept). */
+enum ep_cmd_op { EP_OP_WRITE = 1, EP_OP_ATOMIC = 2, EP_OP_DRAIN = 3, EP_OP_BARRIER = 4 };
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EP_H_ */

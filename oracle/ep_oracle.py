@@ -247,7 +247,7 @@ def bf16_ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
 # but not their widths; this is the reading the build uses:
 #   w0: [31] lap parity  [30:28] op  [27:20] source (connection) rank
 #       [19:12] destination rank  [11:0] expert index local to the destination
-#   w1: Write: bytes to move;  Atomic: value;  Drain: channel index to drain to
+#   w1: Write: [31:26] rows carried - 1, [25:0] bytes to move / 16;  Atomic: value
 #   w2: Write: source offset / 16
 #   w3: [31] lap parity  [30:0] Write: destination offset / 16;
 #                               Atomic: counter index src * E_loc + local expert
@@ -266,7 +266,8 @@ def row_bytes(H: int, payload: str) -> int:
 def decode_cmd(words: Iterable[int]) -> Dict[str, int]:
     w0, w1, w2, w3 = (int(v) & 0xFFFFFFFF for v in words)
     return dict(gen=w0 >> 31, gen_hi=w3 >> 31, op=(w0 >> 28) & 7, src=(w0 >> 20) & 0xFF,
-                dst_rank=(w0 >> 12) & 0xFF, local_expert=w0 & 0xFFF, w1=w1, src_off=w2 << 4,
+                dst_rank=(w0 >> 12) & 0xFF, local_expert=w0 & 0xFFF, w1=w1,
+                nbytes=(w1 & 0x3FFFFFF) << 4, rows=(w1 >> 26) + 1, src_off=w2 << 4,
                 dst_off=(w3 & 0x7FFFFFFF) << 4, counter=w3 & 0x7FFFFFFF)
 
 
@@ -278,7 +279,7 @@ def expected_cmds(idx_s: np.ndarray, lay: Dict[str, np.ndarray], s: int, E_loc: 
     run of <= 32 consecutive slots.  Both: one Atomic per destination expert
     carrying count[s][e] (also when it is 0), the doorbell the receiver holds
     back until that many writes arrived.  Keys are tuples
-    (op, src, dst_rank, local_expert, w1, src_off, dst_off_or_counter).
+    (op, src, dst_rank, local_expert, bytes_or_value, src_off, dst_off_or_counter).
     """
     rb = row_bytes(H, payload)
     E = lay["count"].shape[1]
@@ -319,7 +320,7 @@ def cmd_multiset(log_words: np.ndarray, ops=(OP_WRITE, OP_ATOMIC)) -> Counter:
         if d["op"] not in ops:
             continue
         if d["op"] == OP_WRITE:
-            out[(OP_WRITE, d["src"], d["dst_rank"], d["local_expert"], d["w1"], d["src_off"], d["dst_off"])] += 1
+            out[(OP_WRITE, d["src"], d["dst_rank"], d["local_expert"], d["nbytes"], d["src_off"], d["dst_off"])] += 1
         else:
             out[(OP_ATOMIC, d["src"], d["dst_rank"], d["local_expert"], d["w1"], 0, d["counter"])] += 1
     return out
@@ -339,8 +340,8 @@ def replay_writes_per_token(log_words: np.ndarray, x_rows: np.ndarray, recv_rows
         d = decode_cmd(w)
         if d["op"] != OP_WRITE:
             continue
-        n, so, do = d["w1"], d["src_off"], d["dst_off"]
-        if so + n > src.size or do + n > heap.size or n % rb or do % rb:
+        n, so, do = d["nbytes"], d["src_off"], d["dst_off"]
+        if so + n > src.size or do + n > heap.size or n % rb or do % rb or d["rows"] != n // rb:
             raise ValueError(f"command outside the registered regions: {d}")
         heap[do:do + n] = src[so:so + n]
         hits[do // rb:(do + n) // rb] += 1
@@ -358,8 +359,8 @@ def check_chunk_cover(log_words: np.ndarray, lay: Dict[str, np.ndarray], s: int,
         if d["op"] != OP_WRITE or d["src"] != s:
             continue
         e = d["dst_rank"] * E_loc + d["local_expert"]
-        r0, n = d["dst_off"] // rb, d["w1"] // rb
-        assert d["dst_off"] % rb == 0 and d["w1"] % rb == 0 and 1 <= n <= CHUNK_ROWS, d
+        r0, n = d["dst_off"] // rb, d["nbytes"] // rb
+        assert d["dst_off"] % rb == 0 and d["nbytes"] % rb == 0 and 1 <= n <= CHUNK_ROWS and d["rows"] == n, d
         b, c = int(lay["base"][s, e]), int(lay["count"][s, e])
         assert b <= r0 and r0 + n <= b + c and (r0 - b) % CHUNK_ROWS == 0, (d, b, c)
         covered[r0:r0 + n] += 1

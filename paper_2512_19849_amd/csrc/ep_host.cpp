@@ -1,0 +1,732 @@
+// Host side of libep.so: the handle, the pinned-host FIFO channels, the
+// multithreaded CPU proxy (sender half + receiver half in one process, since
+// the peer ranks are partitions of this GPU's memory) and the C ABI.
+#include <hip/hip_runtime_api.h>
+#include <immintrin.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <time.h>
+
+#include <atomic>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "ep_internal.h"
+
+namespace ep {
+namespace {
+
+// Text of the most recent failure on this thread (ep_last_error).
+thread_local char g_last_error[256] = "";
+
+bool hip_ok(hipError_t e, const char *what) {
+  if (e == hipSuccess) return true;
+  snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+  return false;
+}
+#define HIP_OK(call) hip_ok((call), #call)
+
+inline uint64_t now_ns() {
+  timespec ts;
+  clock_gettime(CLOCK_MONOTONIC, &ts);
+  return (uint64_t)ts.tv_sec * 1000000000ull + (uint64_t)ts.tv_nsec;
+}
+
+// splitmix64: the proxy's own generator for the delivery-reordering test hook.
+inline uint64_t mix64(uint64_t &state) {
+  uint64_t z = (state += 0x9E3779B97F4A7C15ull);
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// What travels from the sender half to the receiver half: the 32-bit immediate
+// (Section 3.3) plus what the receiver knows from the connection it arrived on.
+//   Write : [31]=0 [30:19] local expert [18:13] rows-1 [12:0] low bits of dst_off/16
+//   Atomic: [31]=1 [30:19] local expert [18:0]  value
+struct WireEvent {
+  uint32_t imm;
+  uint16_t src;       // connection = source rank
+  uint16_t dst_rank;  // the receiving rank (whose proxy this event reaches)
+};
+
+struct alignas(64) ProxyThread {
+  int tid = 0;
+  std::thread th;
+  std::vector<int> channels;
+  std::vector<uint64_t> head;  // consumer index per owned channel (private copy)
+  // receiver half: rows seen and parked atomics per (source, global expert)
+  std::vector<int32_t> seen;
+  std::vector<std::deque<int32_t>> parked;  // the control buffer
+  std::vector<WireEvent> window;            // in-flight immediates (reordering hook)
+  uint64_t rng = 0;
+  // statistics (written by the owner thread only, read racy-but-atomically)
+  std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
+      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0};
+  std::mutex log_mu;
+  std::vector<uint32_t> cmd_log, event_log;
+};
+
+}  // namespace
+}  // namespace ep
+
+using namespace ep;
+
+struct ep_handle {
+  ep_config cfg{};
+  bool host_only = false;
+  int E_loc = 0;
+  uint64_t heap_bytes = 0;
+  uint32_t entries = 0, log2_entries = 0;
+  // pinned host (or plain host memory when host_only)
+  uint64_t *slots = nullptr;  // 2 x uint64 per command
+  uint64_t *head = nullptr;   // [C * kHeadStride]
+  int32_t *recv_count = nullptr;
+  int *dev_error = nullptr;
+  void *d_recv_count = nullptr;
+  // device state
+  RingDev ring{};
+  int32_t *tile_hist = nullptr, *tile_base = nullptr, *chunk_cnt = nullptr, *expert_done = nullptr;
+  unsigned *ticket = nullptr, *waves_done = nullptr;
+  int ntiles_cap = 0, chunks_per_expert = 0;
+  // host-only producer state
+  std::atomic<uint64_t> host_tail[kMaxChannels];
+  std::atomic<uint64_t> host_stalls{0};
+  // proxy
+  std::atomic<bool> stop{false};
+  std::atomic<int64_t> expected_atomics{0};
+  std::atomic<int> proxy_error{0};
+  int nthreads = 0;
+  ProxyThread *threads = nullptr;
+  uint64_t timeout_ns = 0;
+};
+
+namespace {
+
+inline int dev_err(const ep_handle *h) {
+  return h->dev_error ? __atomic_load_n(h->dev_error, __ATOMIC_RELAXED) : 0;
+}
+
+void log_event(ep_handle *h, ProxyThread &P, uint32_t kind, uint32_t src, uint32_t e, uint32_t val) {
+  if (!(h->cfg.flags & EP_FLAG_LOG_EVENTS)) return;
+  std::lock_guard<std::mutex> g(P.log_mu);
+  P.event_log.insert(P.event_log.end(), {kind | ((uint32_t)P.tid << 8), src, e, val});
+}
+
+void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_t value) {
+  const size_t key = (size_t)src * h->cfg.num_experts + e;
+  P.seen[key] -= value;
+  // completion counter in pinned host memory, visible to the GPU (Section 4.1)
+  __atomic_store_n(&h->recv_count[key], value, __ATOMIC_RELEASE);
+  log_event(h, P, 3, src, e, (uint32_t)value);
+  P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
+  P.applied.fetch_add(1, std::memory_order_release);
+}
+
+// Receiver half: interpret one immediate.  Writes have already landed; they
+// only advance the per-(source, expert) arrival count.  An Atomic is applied
+// only when that count has reached its value, otherwise it waits in the
+// control buffer; arrivals for other experts never release it (Section 3.3,
+// "partial completion fence").
+void deliver(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  const uint32_t le = (ev.imm >> 19) & 0xFFFu;
+  const uint32_t e = (uint32_t)ev.dst_rank * h->E_loc + le;
+  const size_t key = (size_t)ev.src * h->cfg.num_experts + e;
+  if (!(ev.imm >> 31)) {
+    const int32_t rows = (int32_t)((ev.imm >> 13) & 0x3Fu) + 1;
+    P.seen[key] += rows;
+    log_event(h, P, 1, ev.src, e, (uint32_t)rows);
+    std::deque<int32_t> &q = P.parked[key];
+    while (!q.empty() && P.seen[key] >= q.front()) {
+      const int32_t v = q.front();
+      q.pop_front();
+      apply_atomic(h, P, ev.src, e, v);
+    }
+  } else {
+    const int32_t value = (int32_t)(ev.imm & 0x7FFFFu);
+    log_event(h, P, 2, ev.src, e, (uint32_t)value);
+    std::deque<int32_t> &q = P.parked[key];
+    if (q.empty() && P.seen[key] >= value) {
+      apply_atomic(h, P, ev.src, e, value);
+    } else {
+      q.push_back(value);
+      P.deferred.fetch_add(1, std::memory_order_relaxed);
+    }
+  }
+}
+
+// The "network" between the two halves.  With reorder_window == 0 immediates
+// arrive in the order they were sent; otherwise up to reorder_window of them
+// are in flight and a seeded draw decides which arrives next (an unordered
+// transport such as the one Section 2.4 describes).
+void transmit(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  const int W = h->cfg.reorder_window;
+  if (W <= 0) {
+    deliver(h, P, ev);
+    return;
+  }
+  P.window.push_back(ev);
+  if ((int)P.window.size() > W) {
+    const size_t i = (size_t)(mix64(P.rng) % P.window.size());
+    const WireEvent out = P.window[i];
+    P.window[i] = P.window.back();
+    P.window.pop_back();
+    deliver(h, P, out);
+  }
+}
+
+void flush_window(ep_handle *h, ProxyThread &P) {
+  while (!P.window.empty()) {
+    const size_t i = (size_t)(mix64(P.rng) % P.window.size());
+    const WireEvent out = P.window[i];
+    P.window[i] = P.window.back();
+    P.window.pop_back();
+    deliver(h, P, out);
+  }
+}
+
+void reject(ep_handle *h, ProxyThread &P) {
+  P.rejected.fetch_add(1, std::memory_order_relaxed);
+  int zero = 0;
+  h->proxy_error.compare_exchange_strong(zero, EP_EBOUNDS);
+}
+
+// Sender half: one polled command.  Offsets are relative to the registered
+// heap; the proxy translates and bounds-checks them before acting
+// (Section 3.2, "Symmetric memory").
+void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) {
+  const ep_config &c = h->cfg;
+  const uint32_t op = (w0 >> 28) & 7u, src = (w0 >> 20) & 0xFFu, dr = (w0 >> 12) & 0xFFu, le = w0 & 0xFFFu;
+  P.cmds.fetch_add(1, std::memory_order_relaxed);
+  if (P.first_poll_ns.load(std::memory_order_relaxed) == 0)
+    P.first_poll_ns.store(now_ns(), std::memory_order_relaxed);
+  if (c.flags & EP_FLAG_LOG_CMDS) {
+    std::lock_guard<std::mutex> g(P.log_mu);
+    P.cmd_log.insert(P.cmd_log.end(), {w0, w1, w2, w3});
+  }
+  switch (op) {
+    case EP_OP_WRITE: {
+      const uint64_t len = (uint64_t)(w1 & 0x3FFFFFFu) << 4;
+      const uint32_t rows = (w1 >> 26) + 1;
+      const uint64_t so = (uint64_t)w2 << 4, dof = (uint64_t)(w3 & 0x7FFFFFFFu) << 4;
+      if ((int)src >= c.num_src || (int)dr >= c.num_ranks || (int)le >= h->E_loc || len == 0 ||
+          so + len > h->heap_bytes || dof + len > h->heap_bytes) {
+        reject(h, P);
+        return;
+      }
+      P.writes.fetch_add(1, std::memory_order_relaxed);
+      P.write_bytes.fetch_add(len, std::memory_order_relaxed);
+      P.write_rows.fetch_add(rows, std::memory_order_relaxed);
+      // The payload already sits in the destination partition (the kernel stored it);
+      // what remains of the peer write is its arrival notice.
+      transmit(h, P, WireEvent{(le << 19) | ((rows - 1) << 13) | (uint32_t)((dof >> 4) & 0x1FFFu), (uint16_t)src,
+                               (uint16_t)dr});
+      break;
+    }
+    case EP_OP_ATOMIC: {
+      const uint32_t counter = w3 & 0x7FFFFFFFu;
+      if ((int)src >= c.num_src || (int)dr >= c.num_ranks || (int)le >= h->E_loc || w1 > 0x7FFFFu ||
+          counter != src * (uint32_t)h->E_loc + le) {
+        reject(h, P);
+        return;
+      }
+      P.atomics.fetch_add(1, std::memory_order_relaxed);
+      transmit(h, P, WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint16_t)dr});
+      break;
+    }
+    case EP_OP_DRAIN:
+      // everything this thread handed to the transport must have completed
+      P.drains.fetch_add(1, std::memory_order_relaxed);
+      flush_window(h, P);
+      break;
+    default:  // Barrier needs peer processes; not part of this single-GPU build
+      reject(h, P);
+      break;
+  }
+}
+
+void proxy_main(ep_handle *h, ProxyThread *Pp) {
+  ProxyThread &P = *Pp;
+  const uint32_t mask = h->entries - 1;
+  uint64_t idle = 0;
+  uint64_t idle_since = 0;
+  while (!h->stop.load(std::memory_order_acquire)) {
+    bool any = false;
+    for (size_t ci = 0; ci < P.channels.size(); ++ci) {
+      const int ch = P.channels[ci];
+      uint64_t hd = P.head[ci];
+      int n = 0;
+      while (n < 256) {
+        // Poll: a slot is ready when both lap-parity bits match the lap we are on.
+        const uint64_t *slot = h->slots + ((size_t)ch * h->entries + (hd & mask)) * 2;
+        const uint64_t lo = __atomic_load_n(slot, __ATOMIC_ACQUIRE);
+        const uint64_t hi = __atomic_load_n(slot + 1, __ATOMIC_ACQUIRE);
+        const uint32_t gen = (((uint32_t)(hd >> h->log2_entries)) & 1u) ^ 1u;
+        const uint32_t w0 = (uint32_t)lo, w3 = (uint32_t)(hi >> 32);
+        if ((w0 >> 31) != gen || (w3 >> 31) != gen) break;
+        process_cmd(h, P, w0 & 0x7FFFFFFFu, (uint32_t)(lo >> 32), (uint32_t)hi, w3 & 0x7FFFFFFFu);
+        ++hd;
+        ++n;
+      }
+      if (n) {
+        // Pop: publish the new head where the GPU can read it
+        P.head[ci] = hd;
+        __atomic_store_n(&h->head[(size_t)ch * kHeadStride], hd, __ATOMIC_RELEASE);
+        any = true;
+      }
+    }
+    if (any) {
+      idle = 0;
+      continue;
+    }
+    if (!P.window.empty()) flush_window(h, P);  // nothing new: let in-flight immediates land
+    if (++idle < 4096) {
+      _mm_pause();
+    } else if (idle == 4096) {
+      idle_since = now_ns();
+      std::this_thread::yield();
+    } else if (now_ns() - idle_since < 20000000ull) {
+      std::this_thread::yield();
+    } else {
+      timespec ts{0, 50000};
+      nanosleep(&ts, nullptr);
+    }
+  }
+}
+
+bool is_pow2(uint32_t v) { return v && !(v & (v - 1)); }
+
+int validate(const ep_config &c) {
+  if (c.num_ranks < 1 || c.num_ranks > 256) return EP_EINVAL;
+  if (c.num_experts < 1 || c.num_experts > kMaxExperts || c.num_experts % c.num_ranks) return EP_EINVAL;
+  if (c.top_k < 1 || c.top_k > 64) return EP_EINVAL;
+  if (c.hidden < 128 || c.hidden % 128 || c.hidden > 65536) return EP_EINVAL;
+  if (c.max_tokens < 1 || c.max_tokens >= (1 << 19)) return EP_EINVAL;
+  if (c.num_src < 1 || c.num_src > 256) return EP_EINVAL;
+  if (c.self_rank < 0 || c.self_rank >= c.num_ranks) return EP_EINVAL;
+  if (c.num_channels < 1 || c.num_channels > kMaxChannels) return EP_EINVAL;
+  if (c.ring_entries < 2 || c.ring_entries > (1 << 20) || !is_pow2((uint32_t)c.ring_entries)) return EP_EINVAL;
+  if (c.num_proxy_threads < 0 || c.num_proxy_threads > kMaxThreads) return EP_EINVAL;
+  if (c.reorder_window < 0 || c.reorder_window > 65536) return EP_EINVAL;
+  if (c.spin_timeout_ms < 0 || c.spin_timeout_ms > 60000) return EP_EINVAL;
+  if (c.heap_rows < 0) return EP_EINVAL;
+  return EP_OK;
+}
+
+void free_all(ep_handle *h) {
+  if (!h) return;
+  if (h->host_only) {
+    free(h->slots);
+    free(h->head);
+    free(h->recv_count);
+    free(h->dev_error);
+  } else {
+    if (h->slots) (void)hipHostFree(h->slots);
+    if (h->head) (void)hipHostFree(h->head);
+    if (h->recv_count) (void)hipHostFree(h->recv_count);
+    if (h->dev_error) (void)hipHostFree(h->dev_error);
+    void *dev[] = {h->ring.tail, h->ring.cached_head, h->ring.stalls, h->tile_hist, h->tile_base,
+                   h->chunk_cnt, h->expert_done, h->ticket, h->waves_done};
+    for (void *p : dev)
+      if (p) (void)hipFree(p);
+  }
+  delete[] h->threads;
+  delete h;
+}
+
+template <class T>
+int pinned_alloc(bool host_only, T **p, size_t bytes) {
+  if (host_only) {
+    *p = (T *)aligned_alloc(64, (bytes + 63) / 64 * 64);
+    if (!*p) return EP_ENOMEM;
+  } else {
+    void *q = nullptr;
+    if (!HIP_OK(hipHostMalloc(&q, bytes, hipHostMallocMapped | hipHostMallocCoherent))) return EP_ENOMEM;
+    *p = (T *)q;
+  }
+  memset(*p, 0, bytes);
+  return EP_OK;
+}
+
+template <class T>
+int dev_alloc_zero(T **p, size_t bytes) {
+  void *q = nullptr;
+  if (!HIP_OK(hipMalloc(&q, bytes))) return EP_ENOMEM;
+  if (!HIP_OK(hipMemset(q, 0, bytes))) return EP_EHIP;
+  *p = (T *)q;
+  return EP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
+  if (!cfg || !out) return EP_EINVAL;
+  *out = nullptr;
+  int rc = validate(*cfg);
+  if (rc) return rc;
+  ep_handle *h = new (std::nothrow) ep_handle();
+  if (!h) return EP_ENOMEM;
+  h->cfg = *cfg;
+  h->host_only = (cfg->flags & EP_FLAG_HOST_ONLY) != 0;
+  h->E_loc = cfg->num_experts / cfg->num_ranks;
+  if (h->cfg.heap_rows == 0) h->cfg.heap_rows = (int64_t)cfg->num_src * cfg->max_tokens * cfg->top_k;
+  h->heap_bytes = (uint64_t)h->cfg.heap_rows * 2ull * (uint64_t)cfg->hidden;
+  if ((h->heap_bytes >> 4) >= (1ull << 31)) {
+    delete h;
+    return EP_EINVAL;  // destination offsets are 31 bits of 16-byte units
+  }
+  h->entries = (uint32_t)cfg->ring_entries;
+  while ((1u << h->log2_entries) < h->entries) ++h->log2_entries;
+  const int ms = cfg->spin_timeout_ms ? cfg->spin_timeout_ms : 5000;
+  h->timeout_ns = (uint64_t)ms * 1000000ull;
+  for (auto &t : h->host_tail) t.store(0);
+  const int C = cfg->num_channels, S = cfg->num_src, E = cfg->num_experts;
+
+  if (!h->host_only) {
+    int ndev = 0;
+    if (!HIP_OK(hipGetDeviceCount(&ndev)) || ndev < 1) {
+      delete h;
+      return EP_EHIP;
+    }
+  }
+  rc = pinned_alloc(h->host_only, &h->slots, (size_t)C * h->entries * 16);
+  if (!rc) rc = pinned_alloc(h->host_only, &h->head, (size_t)C * kHeadStride * 8);
+  if (!rc) rc = pinned_alloc(h->host_only, &h->recv_count, (size_t)S * E * 4);
+  if (!rc) rc = pinned_alloc(h->host_only, &h->dev_error, 64);
+  if (!rc && !h->host_only) {
+    h->ntiles_cap = (cfg->max_tokens + kLayoutTile - 1) / kLayoutTile;
+    h->chunks_per_expert = (cfg->max_tokens + kChunkRows - 1) / kChunkRows;
+    const size_t hist = (size_t)S * h->ntiles_cap * E * 4;
+    rc = dev_alloc_zero(&h->ring.tail, (size_t)C * 8);
+    if (!rc) rc = dev_alloc_zero(&h->ring.cached_head, (size_t)C * 8);
+    if (!rc) rc = dev_alloc_zero(&h->ring.stalls, 8);
+    if (!rc) rc = dev_alloc_zero(&h->tile_hist, hist);
+    if (!rc) rc = dev_alloc_zero(&h->tile_base, hist);
+    if (!rc) rc = dev_alloc_zero(&h->chunk_cnt, (size_t)E * h->chunks_per_expert * 4);
+    if (!rc) rc = dev_alloc_zero(&h->expert_done, (size_t)E * 4);
+    if (!rc) rc = dev_alloc_zero(&h->ticket, 4);
+    if (!rc) rc = dev_alloc_zero(&h->waves_done, 4);
+    void *dp = nullptr;
+    if (!rc && !HIP_OK(hipHostGetDevicePointer(&dp, h->slots, 0))) rc = EP_EHIP;
+    h->ring.slots = dp;
+    if (!rc && !HIP_OK(hipHostGetDevicePointer(&dp, h->head, 0))) rc = EP_EHIP;
+    h->ring.head = (const unsigned long long *)dp;
+    if (!rc && !HIP_OK(hipHostGetDevicePointer(&dp, h->dev_error, 0))) rc = EP_EHIP;
+    h->ring.error = (int *)dp;
+    if (!rc && !HIP_OK(hipHostGetDevicePointer(&h->d_recv_count, h->recv_count, 0))) rc = EP_EHIP;
+    h->ring.entries = h->entries;
+    h->ring.log2_entries = h->log2_entries;
+    h->ring.channels = (unsigned)C;
+    h->ring.timeout_ticks = (unsigned long long)ms * 100000ull;  // wall_clock64 runs at 100 MHz
+    if (!rc && !HIP_OK(hipDeviceSynchronize())) rc = EP_EHIP;
+  }
+  if (rc) {
+    free_all(h);
+    return rc;
+  }
+
+  h->nthreads = cfg->num_proxy_threads;
+  h->threads = new (std::nothrow) ProxyThread[h->nthreads > 0 ? h->nthreads : 1];
+  if (!h->threads) {
+    free_all(h);
+    return EP_ENOMEM;
+  }
+  for (int i = 0; i < h->nthreads; ++i) {
+    ProxyThread &P = h->threads[i];
+    P.tid = i;
+    for (int c = i; c < C; c += h->nthreads) {
+      P.channels.push_back(c);
+      P.head.push_back(0);
+    }
+    P.seen.assign((size_t)S * E, 0);
+    P.parked.resize((size_t)S * E);
+    P.rng = cfg->reorder_seed * 0x9E3779B97F4A7C15ull + (uint64_t)i;
+  }
+  for (int i = 0; i < h->nthreads; ++i) h->threads[i].th = std::thread(proxy_main, h, &h->threads[i]);
+  *out = h;
+  return EP_OK;
+}
+
+int ep_proxy_stop(ep_handle *h) {
+  if (!h) return EP_EINVAL;
+  int rc = EP_OK;
+  if (!h->host_only && !HIP_OK(hipDeviceSynchronize())) rc = EP_EHIP;
+  h->stop.store(true, std::memory_order_release);
+  for (int i = 0; i < h->nthreads; ++i)
+    if (h->threads[i].th.joinable()) h->threads[i].th.join();
+  free_all(h);
+  return rc;
+}
+
+int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t *d_count, int32_t *d_expert_total,
+              int32_t *d_rank_total, int32_t *d_base, int32_t *d_expert_offset, int32_t *d_rank_offset,
+              int32_t *d_slot, int32_t *d_dst_row, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (T < 0 || T > h->cfg.max_tokens) return EP_EINVAL;
+  if (!d_count || !d_expert_total || !d_rank_total || !d_base || !d_expert_offset || !d_rank_offset) return EP_EINVAL;
+  if (T > 0 && (!d_topk_idx || !d_slot || !d_dst_row)) return EP_EINVAL;
+  LayoutArgs a{};
+  a.idx = d_topk_idx;
+  a.S = h->cfg.num_src;
+  a.T = T;
+  a.K = h->cfg.top_k;
+  a.E = h->cfg.num_experts;
+  a.R = h->cfg.num_ranks;
+  a.E_loc = h->E_loc;
+  a.ntiles = (T + kLayoutTile - 1) / kLayoutTile;
+  a.tile_hist = h->tile_hist;
+  a.tile_base = h->tile_base;
+  a.ticket = h->ticket;
+  a.count = d_count;
+  a.expert_total = d_expert_total;
+  a.rank_total = d_rank_total;
+  a.base = d_base;
+  a.expert_offset = d_expert_offset;
+  a.rank_offset = d_rank_offset;
+  a.slot = d_slot;
+  a.dst_row = d_dst_row;
+  a.error = h->ring.error;
+  return HIP_OK((hipError_t)launch_layout(a, stream)) ? EP_OK : EP_EHIP;
+}
+
+static uint32_t row_bytes_of(int H, int payload) {
+  return payload == EP_BF16 ? 2u * (uint32_t)H : ((uint32_t)H + (uint32_t)H / 32u + 15u) / 16u * 16u;
+}
+
+int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const int32_t *d_dst_row,
+                const int32_t *d_count, const int32_t *d_base, int32_t T, int32_t src_rank,
+                int32_t dst_rank_filter, int32_t payload, int32_t cmd_mode, void *d_recv, float *d_recv_scale,
+                int64_t recv_rows, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  const ep_config &c = h->cfg;
+  const int mode = cmd_mode & EP_CMD_MODE_MASK;
+  if (T < 0 || T > c.max_tokens || src_rank < 0 || src_rank >= c.num_src) return EP_EINVAL;
+  if (dst_rank_filter < -1 || dst_rank_filter >= c.num_ranks) return EP_EINVAL;
+  if (payload != EP_BF16 && payload != EP_FP8_E4M3) return EP_EINVAL;
+  if (mode != EP_CMD_PER_TOKEN && mode != EP_CMD_CHUNK32 && mode != EP_CMD_NONE) return EP_EINVAL;
+  if (cmd_mode & ~(EP_CMD_MODE_MASK | EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN)) return EP_EINVAL;
+  if (recv_rows < 0 || recv_rows > c.heap_rows) return EP_EINVAL;
+  if (T > 0 && (!d_x || !d_topk_idx || !d_dst_row || !d_recv)) return EP_EINVAL;
+  if ((payload == EP_FP8_E4M3) != (d_recv_scale != nullptr)) return EP_EINVAL;
+  if (mode != EP_CMD_NONE) {
+    if (h->nthreads < 1 || !d_count || !d_base) return EP_EINVAL;
+    if (mode == EP_CMD_NONE && (cmd_mode & (EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN))) return EP_EINVAL;
+  } else if (cmd_mode & (EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN)) {
+    return EP_EINVAL;
+  }
+  if (((uintptr_t)d_x | (uintptr_t)d_recv) & 15) return EP_EINVAL;
+  if (int e = dev_err(h)) return e;
+
+  DispatchArgs a{};
+  a.x = d_x;
+  a.idx = d_topk_idx;
+  a.dst_row = d_dst_row;
+  a.count = d_count;
+  a.base = d_base;
+  a.recv = d_recv;
+  a.recv_scale = d_recv_scale;
+  a.recv_rows = recv_rows;
+  a.T = T;
+  a.K = c.top_k;
+  a.H = c.hidden;
+  a.E = c.num_experts;
+  a.E_loc = h->E_loc;
+  a.src = src_rank;
+  a.filter = dst_rank_filter;
+  a.cmd_mode = cmd_mode;
+  a.row_bytes = row_bytes_of(c.hidden, payload);
+  a.chunks_per_expert = h->chunks_per_expert;
+  a.chunk_cnt = h->chunk_cnt;
+  a.expert_done = h->expert_done;
+  a.waves_done = h->waves_done;
+  a.ring = h->ring;
+  if (mode != EP_CMD_NONE) {
+    if (((uint64_t)T * a.row_bytes) >> 4 > 0xFFFFFFFFull) return EP_EINVAL;
+    if (T > 0)
+      h->expected_atomics.fetch_add(dst_rank_filter < 0 ? c.num_experts : h->E_loc, std::memory_order_relaxed);
+  }
+  if (T == 0) {
+    // nothing to launch; a ring-on dispatch of zero tokens still owes its (all zero) count atomics,
+    // which only a kernel can push: run it with one idle workgroup
+    if (mode == EP_CMD_NONE) return EP_OK;
+    a.T = 0;
+  }
+  return HIP_OK((hipError_t)launch_dispatch(a, payload, stream)) ? EP_OK : EP_EHIP;
+}
+
+int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32_t *d_dst_row, int32_t T,
+               int64_t y_rows, void *d_out, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (T < 0 || T > h->cfg.max_tokens || y_rows < 0) return EP_EINVAL;
+  if (T == 0) return EP_OK;
+  if (!d_topk_w || !d_dst_row || !d_out || (y_rows > 0 && !d_y)) return EP_EINVAL;
+  if (((uintptr_t)d_y | (uintptr_t)d_out) & 15) return EP_EINVAL;
+  CombineArgs a{};
+  a.y = d_y;
+  a.w = d_topk_w;
+  a.dst_row = d_dst_row;
+  a.out = d_out;
+  a.y_rows = y_rows;
+  a.T = T;
+  a.K = h->cfg.top_k;
+  a.H = h->cfg.hidden;
+  a.error = h->ring.error;
+  return HIP_OK((hipError_t)launch_combine(a, stream)) ? EP_OK : EP_EHIP;
+}
+
+int ep_wait(ep_handle *h) {
+  if (!h) return EP_EINVAL;
+  const uint64_t t0 = now_ns();
+  uint64_t spins = 0;
+  for (;;) {
+    if (int e = dev_err(h)) return e;
+    if (int e = h->proxy_error.load(std::memory_order_relaxed)) return e;
+    int64_t applied = 0;
+    for (int i = 0; i < h->nthreads; ++i) applied += (int64_t)h->threads[i].applied.load(std::memory_order_acquire);
+    if (applied >= h->expected_atomics.load(std::memory_order_relaxed)) return EP_OK;
+    if ((++spins & 1023) == 0) {
+      if (now_ns() - t0 > h->timeout_ns) return EP_ETIMEOUT;
+      std::this_thread::yield();
+    } else {
+      _mm_pause();
+    }
+  }
+}
+
+int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv_count) {
+  if (!h || !recv_count) return EP_EINVAL;
+  *recv_count = h->recv_count;
+  if (d_recv_count) *d_recv_count = (const int32_t *)h->d_recv_count;
+  return EP_OK;
+}
+
+int ep_stats(ep_handle *h, ep_stats_t *out) {
+  if (!h || !out) return EP_EINVAL;
+  memset(out, 0, sizeof(*out));
+  for (int i = 0; i < h->nthreads; ++i) {
+    ProxyThread &P = h->threads[i];
+    const uint64_t n = P.cmds.load();
+    out->cmds += n;
+    if (i < 16) out->per_thread_cmds[i] = n;
+    out->writes += P.writes.load();
+    out->atomics += P.atomics.load();
+    out->drains += P.drains.load();
+    out->write_bytes += P.write_bytes.load();
+    out->write_rows += P.write_rows.load();
+    out->atomics_applied += P.applied.load();
+    out->atomics_deferred += P.deferred.load();
+    out->rejected += P.rejected.load();
+    const uint64_t f = P.first_poll_ns.load(), l = P.last_apply_ns.load();
+    if (f && (!out->first_poll_ns || f < out->first_poll_ns)) out->first_poll_ns = f;
+    if (l > out->last_apply_ns) out->last_apply_ns = l;
+  }
+  if (h->host_only) {
+    out->gpu_ring_full = h->host_stalls.load();
+  } else {
+    unsigned long long st = 0;
+    if (!HIP_OK(hipMemcpy(&st, h->ring.stalls, 8, hipMemcpyDeviceToHost))) return EP_EHIP;
+    out->gpu_ring_full = st;
+  }
+  out->device_error = dev_err(h);
+  out->proxy_error = h->proxy_error.load();
+  return EP_OK;
+}
+
+int ep_reset_stats(ep_handle *h) {
+  if (!h) return EP_EINVAL;
+  int64_t applied = 0;
+  for (int i = 0; i < h->nthreads; ++i) applied += (int64_t)h->threads[i].applied.load();
+  if (applied != h->expected_atomics.load()) return EP_ESTATE;  // work in flight
+  for (int i = 0; i < h->nthreads; ++i) {
+    ProxyThread &P = h->threads[i];
+    for (auto *a : {&P.cmds, &P.writes, &P.atomics, &P.drains, &P.write_bytes, &P.write_rows, &P.applied,
+                    &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns})
+      a->store(0);
+    std::lock_guard<std::mutex> g(P.log_mu);
+    P.cmd_log.clear();
+    P.event_log.clear();
+  }
+  h->expected_atomics.store(0);
+  memset(h->recv_count, 0, (size_t)h->cfg.num_src * h->cfg.num_experts * 4);
+  if (h->host_only) {
+    h->host_stalls.store(0);
+  } else if (!HIP_OK(hipMemset(h->ring.stalls, 0, 8))) {
+    return EP_EHIP;
+  }
+  return EP_OK;
+}
+
+static int copy_log(ep_handle *h, bool events, void *buf, size_t cap, size_t *n) {
+  if (!h || !n) return EP_EINVAL;
+  if (!(h->cfg.flags & (events ? EP_FLAG_LOG_EVENTS : EP_FLAG_LOG_CMDS))) return EP_ESTATE;
+  size_t total = 0;
+  uint32_t *dst = (uint32_t *)buf;
+  for (int i = 0; i < h->nthreads; ++i) {
+    ProxyThread &P = h->threads[i];
+    std::lock_guard<std::mutex> g(P.log_mu);
+    const std::vector<uint32_t> &v = events ? P.event_log : P.cmd_log;
+    const size_t recs = v.size() / 4;
+    for (size_t r = 0; r < recs; ++r, ++total)
+      if (dst && total < cap) memcpy(dst + total * 4, v.data() + r * 4, 16);
+  }
+  *n = total;
+  return EP_OK;
+}
+
+int ep_cmd_log(ep_handle *h, void *buf, size_t cap, size_t *n) { return copy_log(h, false, buf, cap, n); }
+int ep_event_log(ep_handle *h, void *buf, size_t cap, size_t *n) { return copy_log(h, true, buf, cap, n); }
+
+int ep_host_push(ep_handle *h, int32_t channel, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, uint64_t *idx) {
+  if (!h || channel < 0 || channel >= h->cfg.num_channels) return EP_EINVAL;
+  if (!h->host_only) return EP_ESTATE;
+  const uint64_t i = h->host_tail[channel].fetch_add(1, std::memory_order_relaxed);
+  const uint64_t *hp = &h->head[(size_t)channel * kHeadStride];
+  if (i - __atomic_load_n(hp, __ATOMIC_ACQUIRE) >= h->entries) {
+    h->host_stalls.fetch_add(1, std::memory_order_relaxed);
+    const uint64_t t0 = now_ns();
+    uint64_t spins = 0;
+    while (i - __atomic_load_n(hp, __ATOMIC_ACQUIRE) >= h->entries) {
+      if ((++spins & 255) == 0) {
+        if (now_ns() - t0 > h->timeout_ns) {
+          __atomic_store_n(h->dev_error, (int)EP_ETIMEOUT, __ATOMIC_RELAXED);
+          return EP_ETIMEOUT;
+        }
+        std::this_thread::yield();
+      } else {
+        _mm_pause();
+      }
+    }
+  }
+  const uint32_t gen = (((uint32_t)(i >> h->log2_entries)) & 1u) ^ 1u;
+  uint64_t *slot = h->slots + ((size_t)channel * h->entries + (i & (h->entries - 1))) * 2;
+  const uint64_t lo = (uint64_t)((w0 & 0x7FFFFFFFu) | (gen << 31)) | ((uint64_t)w1 << 32);
+  const uint64_t hi = (uint64_t)w2 | ((uint64_t)((w3 & 0x7FFFFFFFu) | (gen << 31)) << 32);
+  __atomic_store_n(slot, lo, __ATOMIC_RELEASE);
+  __atomic_store_n(slot + 1, hi, __ATOMIC_RELEASE);
+  if (idx) *idx = i;
+  return EP_OK;
+}
+
+int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx) {
+  if (!h || channel < 0 || channel >= h->cfg.num_channels) return EP_EINVAL;
+  return __atomic_load_n(&h->head[(size_t)channel * kHeadStride], __ATOMIC_ACQUIRE) > idx ? 1 : 0;
+}
+
+const char *ep_last_error(void) { return g_last_error; }
+
+int ep_host_expect_atomics(ep_handle *h, int32_t n) {
+  if (!h || n < 0) return EP_EINVAL;
+  h->expected_atomics.fetch_add(n, std::memory_order_relaxed);
+  return EP_OK;
+}
+
+}  // extern "C"

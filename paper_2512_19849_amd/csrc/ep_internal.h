@@ -1,0 +1,96 @@
+// Internal declarations shared by the host side (handle, proxy threads) and the
+// HIP kernels of libep.so.  Not part of the C ABI.
+#pragma once
+
+#include <stdint.h>
+
+#include "../../include/ep.h"
+
+namespace ep {
+
+// One head index per channel sits alone in a 64-byte line of pinned host memory,
+// so proxy threads that own different channels never share a line.
+constexpr int kHeadStride = 8;  // in uint64 units
+constexpr int kChunkRows = 32;  // rows per Write in EP_CMD_CHUNK32 (Section 3.3: "typically 32 tokens")
+constexpr int kMaxChannels = 64;
+constexpr int kMaxThreads = 16;
+constexpr int kLayoutTile = 64;        // tokens per layout tile = one wavefront
+constexpr int kLayoutWaves = 4;        // tiles per layout workgroup
+constexpr int kMaxExperts = 1024;
+
+// TransferCmd fields (layout documented in include/ep.h).
+inline
+#ifdef __HIPCC__
+    __host__ __device__
+#endif
+    uint32_t
+    cmd_w0(uint32_t op, uint32_t src, uint32_t dst_rank, uint32_t local_expert) {
+  return (op << 28) | (src << 20) | (dst_rank << 12) | local_expert;
+}
+
+// Device-visible state of the FIFO channels (Section 3.1): slots and head live
+// in pinned host memory, tail and the cached head in device memory.
+struct RingDev {
+  void *slots;                       // uint32x4 [channels * entries], pinned host
+  const unsigned long long *head;    // [channels * kHeadStride], pinned host, written by the proxy
+  unsigned long long *tail;          // [channels], device: next Idx to hand out
+  unsigned long long *cached_head;   // [channels], device: last head value fetched over PCIe
+  int *error;                        // pinned host sticky error word
+  unsigned long long *stalls;        // device: times a push found the channel full
+  unsigned entries, log2_entries, channels;
+  unsigned long long timeout_ticks;  // wall_clock64 ticks (100 MHz)
+};
+
+struct LayoutArgs {
+  const int32_t *idx;  // [S,T,K]
+  int32_t S, T, K, E, R, E_loc, ntiles;
+  int32_t *tile_hist;  // scratch [S, ntiles, E]: tile histograms
+  int32_t *tile_base;  // scratch [S, ntiles, E]: exclusive scan over the tiles of one source
+  unsigned *ticket;    // scratch: workgroups finished (self-resetting)
+  int32_t *count, *expert_total, *rank_total, *base, *expert_offset, *rank_offset;
+  int32_t *slot, *dst_row;
+  int *error;
+};
+
+struct DispatchArgs {
+  const void *x;           // bf16 [T,H]
+  const int32_t *idx;      // [T,K]
+  const int32_t *dst_row;  // [T,K]
+  const int32_t *count;    // [E] of this source
+  const int32_t *base;     // [E] of this source
+  void *recv;              // bf16 [rows,H] or u8 [rows,H]
+  float *recv_scale;       // [rows, H/128] (FP8)
+  long long recv_rows;
+  int32_t T, K, H, E, E_loc, src, filter;
+  int32_t cmd_mode;        // ep_cmd_mode incl. flag bits
+  uint32_t row_bytes;      // bytes of one token in a message
+  int32_t parts;           // wavefronts per token
+  int32_t tokens_per_block;
+  int32_t chunks_per_expert;
+  int32_t *chunk_cnt;      // scratch [E * chunks_per_expert], zero between calls
+  int32_t *expert_done;    // scratch [E], zero between calls
+  unsigned *waves_done;    // scratch, zero between calls
+  RingDev ring;
+};
+
+struct CombineArgs {
+  const void *y;           // bf16 [rows,H]
+  const float *w;          // [T,K]
+  const int32_t *dst_row;  // [T,K]
+  void *out;               // bf16 [T,H]
+  long long y_rows;
+  int32_t T, K, H, parts;
+  int *error;
+};
+
+// Launchers implemented in ep_kernels.hip.  All return a hipError_t as int.
+int launch_layout(const LayoutArgs &a, void *stream);
+int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
+int launch_combine(const CombineArgs &a, void *stream);
+int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
+
+// Tunables (read once from the environment, for sweeps): vectors per lane.
+int tuned_dispatch_vpl(int H);
+int tuned_combine_vpl(int H);
+
+}  // namespace ep

@@ -1,0 +1,686 @@
+// HIP kernels for gfx950 (MI355X): layout, dispatch (bf16 / FP8 E4M3), combine,
+// and the device side of the GPU->CPU FIFO channels.
+//
+// None of the work here is a dense contraction, so there is no MFMA: dispatch
+// and combine are HBM-bound row copies / gathers done with 16-byte vector
+// accesses, one wavefront (64 lanes) per token or per slice of a token; the
+// layout is an integer counting sort built from LDS bit masks and popcounts.
+#include <hip/hip_runtime.h>
+#include <stdlib.h>
+
+#include "ep_internal.h"
+
+namespace ep {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+#define EP_DEV __device__ __forceinline__
+
+// ---------------------------------------------------------------- utilities
+EP_DEV void dev_set_error(int *err, int code) {
+  // Sticky error word in pinned host memory; any failing lane may write it.
+  __hip_atomic_store(err, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+EP_DEV int lane_id() { return threadIdx.x & 63; }
+
+// ------------------------------------------------- FIFO channel, GPU side
+// Push (Section 3.1, "Channel APIs"): reserve the next Idx of the channel with
+// one device-scope atomic on the tail (which lives in device memory), wait for
+// room using the device-resident cached copy of the head and re-reading the
+// host copy over PCIe only when that cache says "full", then publish the
+// 16-byte command with a single store.  Returns Idx, or ~0 after a timeout.
+EP_DEV unsigned long long ring_push(const RingDev &r, unsigned c, unsigned w0, unsigned w1,
+                                    unsigned w2, unsigned w3) {
+  unsigned long long idx =
+      __hip_atomic_fetch_add(&r.tail[c], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  unsigned long long head =
+      __hip_atomic_load(&r.cached_head[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (idx - head >= r.entries) {
+    __hip_atomic_fetch_add(r.stalls, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long t0 = wall_clock64();
+    for (;;) {
+      head = __hip_atomic_load(&r.head[c * kHeadStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (idx - head < r.entries) break;
+      if (wall_clock64() - t0 > r.timeout_ticks) {
+        dev_set_error(r.error, EP_ETIMEOUT);
+        return ~0ull;
+      }
+      __builtin_amdgcn_s_sleep(32);
+    }
+    __hip_atomic_fetch_max(&r.cached_head[c], head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  const unsigned gen = (((unsigned)(idx >> r.log2_entries)) & 1u) ^ 1u;
+  u32x4 v = {w0 | (gen << 31), w1, w2, w3 | (gen << 31)};
+  u32x4 *slot = (u32x4 *)r.slots + (size_t)c * r.entries + (size_t)(idx & (r.entries - 1));
+  *(volatile u32x4 *)slot = v;  // one 16-byte store straight to host memory (system scope)
+  return idx;
+}
+
+// Check-completion(Idx): has the proxy popped command idx of channel c?
+// Blocks (bounded) until it has; used after a Drain.
+EP_DEV bool ring_wait_completion(const RingDev &r, unsigned c, unsigned long long idx) {
+  const unsigned long long t0 = wall_clock64();
+  for (;;) {
+    unsigned long long head =
+        __hip_atomic_load(&r.head[c * kHeadStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (head > idx) return true;
+    if (wall_clock64() - t0 > r.timeout_ticks) {
+      dev_set_error(r.error, EP_ETIMEOUT);
+      return false;
+    }
+    __builtin_amdgcn_s_sleep(32);
+  }
+}
+
+// ------------------------------------------------------------------ layout
+// Kernel 1: one wavefront per tile of 64 tokens of one source rank.  Every
+// lane owns a token and sets its bit in a 64-bit LDS mask per expert it chose
+// (a token's experts are distinct, so one bit per (token, expert)).  The
+// in-tile stable rank of an entry is the popcount of the mask below its lane;
+// the tile histogram is the popcount of the whole mask.  The last workgroup
+// to finish scans the tile histograms (per source and expert, over tiles),
+// the expert totals (over experts) and writes every per-expert output.
+__global__ __launch_bounds__(kLayoutWaves * 64) void layout_count_kernel(LayoutArgs a) {
+  extern __shared__ unsigned long long s_mask[];  // [kLayoutWaves][E]
+  __shared__ int s_off[kMaxExperts + 1];
+  __shared__ int s_last;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nblk = max(1, (a.ntiles + kLayoutWaves - 1) / kLayoutWaves);
+  const int s = blockIdx.x / nblk;
+  const int tile = (blockIdx.x % nblk) * kLayoutWaves + wave;
+  const int E = a.E, K = a.K;
+
+  for (int i = tid; i < kLayoutWaves * E; i += kLayoutWaves * 64) s_mask[i] = 0ull;
+  __syncthreads();
+
+  unsigned long long *m = s_mask + (size_t)wave * E;
+  const int t = tile * kLayoutTile + lane;
+  const bool active = tile < a.ntiles && t < a.T;
+  const size_t ebase = ((size_t)s * a.T + (active ? t : 0)) * K;
+  if (active) {
+    for (int k = 0; k < K; ++k) {
+      const int e = a.idx[ebase + k];
+      if (e >= 0 && e < E)
+        atomicOr(&m[e], 1ull << lane);
+      else if (e != -1)
+        dev_set_error(a.error, EP_EBOUNDS);
+    }
+  }
+  __syncthreads();
+  if (active) {
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int k = 0; k < K; ++k) {
+      const int e = a.idx[ebase + k];
+      a.slot[ebase + k] = (e >= 0 && e < E) ? __popcll(m[e] & below) : -1;
+    }
+  }
+  if (tile < a.ntiles) {
+    int32_t *hist = a.tile_hist + ((size_t)s * a.ntiles + tile) * E;
+    for (int e = lane; e < E; e += 64) hist[e] = __popcll(m[e]);
+  }
+
+  // ---- last workgroup to arrive does the scans
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned ticket = atomicAdd(a.ticket, 1u);
+    s_last = (ticket == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  if (tid == 0) *a.ticket = 0u;
+
+  const int S = a.S, nt = a.ntiles;
+  for (int e = tid; e < E; e += kLayoutWaves * 64) {
+    int tot = 0;
+    for (int ss = 0; ss < S; ++ss) {
+      const int32_t *__restrict__ h = a.tile_hist + (size_t)ss * nt * E + e;
+      int32_t *__restrict__ b = a.tile_base + (size_t)ss * nt * E + e;
+      int run = 0;
+#pragma unroll 8
+      for (int tl = 0; tl < nt; ++tl) {
+        const int v = h[(size_t)tl * E];
+        b[(size_t)tl * E] = run;
+        run += v;
+      }
+      a.count[ss * E + e] = run;
+      tot += run;
+    }
+    a.expert_total[e] = tot;
+    s_off[e] = tot;
+  }
+  __syncthreads();
+  if (wave == 0) {  // exclusive scan over experts: 64 lanes x contiguous runs
+    const int per = (E + 63) / 64;
+    const int lo = min(E, lane * per), hi = min(E, lo + per);
+    int sum = 0;
+    for (int i = lo; i < hi; ++i) sum += s_off[i];
+    int incl = sum;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int v = __shfl_up(incl, d);
+      if (lane >= d) incl += v;
+    }
+    int run = incl - sum;
+    for (int i = lo; i < hi; ++i) {
+      const int v = s_off[i];
+      s_off[i] = run;
+      a.expert_offset[i] = run;
+      run += v;
+    }
+    if (lane == 63) {
+      s_off[E] = incl;
+      a.expert_offset[E] = incl;
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < E; e += kLayoutWaves * 64) {
+    int b = s_off[e];
+    for (int ss = 0; ss < S; ++ss) {
+      a.base[ss * E + e] = b;
+      b += a.count[ss * E + e];
+    }
+  }
+  for (int r = tid; r <= a.R; r += kLayoutWaves * 64) {
+    const int o = s_off[r * a.E_loc];  // r == R reads the end sentinel s_off[E]
+    a.rank_offset[r] = o;
+    if (r < a.R) a.rank_total[r] = s_off[(r + 1) * a.E_loc] - o;
+  }
+}
+
+// Kernel 2: slot = in-tile rank + tiles before it; dst_row = base + slot.
+__global__ __launch_bounds__(256) void layout_finish_kernel(LayoutArgs a) {
+  const long long n = (long long)a.S * a.T * a.K;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int e = a.idx[i];
+  if (e < 0 || e >= a.E) {
+    a.slot[i] = -1;
+    a.dst_row[i] = -1;
+    return;
+  }
+  const long long tk = (long long)a.T * a.K;
+  const int s = (int)(i / tk);
+  const int t = (int)((i - (long long)s * tk) / a.K);
+  const int tile = t / kLayoutTile;
+  const int r = a.slot[i] + a.tile_base[((size_t)s * a.ntiles + tile) * a.E + e];
+  a.slot[i] = r;
+  a.dst_row[i] = a.base[s * a.E + e] + r;
+}
+
+int launch_layout(const LayoutArgs &a, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int nblk = (a.ntiles + kLayoutWaves - 1) / kLayoutWaves;
+  const int grid1 = a.S * (nblk > 0 ? nblk : 1);
+  const size_t lds = (size_t)kLayoutWaves * a.E * sizeof(unsigned long long);
+  hipLaunchKernelGGL(layout_count_kernel, dim3(grid1), dim3(kLayoutWaves * 64), lds, st, a);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return (int)err;
+  const long long n = (long long)a.S * a.T * a.K;
+  if (n > 0) {
+    hipLaunchKernelGGL(layout_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+    err = hipGetLastError();
+  }
+  return (int)err;
+}
+
+// ------------------------------------------------- dispatch: command emission
+struct TokenMeta {
+  int e;       // expert of this lane's k (lane < K), -1 otherwise
+  int row;     // destination row
+  bool valid;  // this (t, k) is dispatched by this call
+};
+
+EP_DEV TokenMeta load_meta(const DispatchArgs &a, int t, int lane) {
+  TokenMeta m{-1, -1, false};
+  if (t < a.T && lane < a.K) {
+    m.e = a.idx[(size_t)t * a.K + lane];
+    m.row = a.dst_row[(size_t)t * a.K + lane];
+    if (m.e >= 0) {
+      if (m.e >= a.E || m.row < 0 || m.row >= a.recv_rows)
+        dev_set_error(a.ring.error, EP_EBOUNDS);
+      else if (a.filter < 0 || m.e / a.E_loc == a.filter)
+        m.valid = true;
+    } else if (m.e != -1) {
+      dev_set_error(a.ring.error, EP_EBOUNDS);
+    }
+  }
+  return m;
+}
+
+EP_DEV void push_count_atomic(const DispatchArgs &a, int e, int value) {
+  const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
+  ring_push(a.ring, dr % a.ring.channels, cmd_w0(EP_OP_ATOMIC, a.src, dr, le), (unsigned)value, 0u,
+            (unsigned)(a.src * a.E_loc) + le);
+}
+
+// Kernel prologue (workgroup 0, wavefront 0): the count Atomics that no row
+// completion will trigger - experts with count 0, or all of them when the
+// caller wants the atomics ahead of the writes.
+EP_DEV void emit_leading_atomics(const DispatchArgs &a, int lane) {
+  const bool first = (a.cmd_mode & EP_CMD_ATOMICS_FIRST) != 0;
+  for (int e = lane; e < a.E; e += 64) {
+    if (a.filter >= 0 && e / a.E_loc != a.filter) continue;
+    const int c = a.count[e];
+    if (first || c == 0) push_count_atomic(a, e, c);
+  }
+}
+
+// Called by the lanes holding a dispatched (t,k) after the token's rows are
+// stored and released at device scope.  LL granularity: one Write per row.
+// Chunk granularity: the lane that completes a run of <= 32 consecutive rows of
+// an expert pushes the Write for the run.  Whoever completes the expert pushes
+// its count Atomic (Section 3.3: the receiver holds it until that many rows
+// arrived).  The scratch counters return to zero by themselves.
+EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
+  const int e = m.e;
+  const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
+  const unsigned ch = dr % a.ring.channels;
+  const int c = a.count[e];
+  const int mode = a.cmd_mode & EP_CMD_MODE_MASK;
+  int finished_rows = 0;
+  if (mode == EP_CMD_PER_TOKEN) {
+    const unsigned long long so = (unsigned long long)t * a.row_bytes;
+    const unsigned long long dof = (unsigned long long)m.row * a.row_bytes;
+    ring_push(a.ring, ch, cmd_w0(EP_OP_WRITE, a.src, dr, le), a.row_bytes >> 4, (unsigned)(so >> 4),
+              (unsigned)(dof >> 4));
+    finished_rows = 1;
+  } else {
+    const int slot = m.row - a.base[e];
+    const int j = slot >> 5;
+    if (slot < 0 || j >= a.chunks_per_expert || slot >= c) {
+      dev_set_error(a.ring.error, EP_EBOUNDS);
+      return;
+    }
+    const int csize = min(kChunkRows, c - (j << 5));
+    int *cnt = a.chunk_cnt + (size_t)e * a.chunks_per_expert + j;
+    const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1 == csize) {
+      __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned long long off = (unsigned long long)(a.base[e] + (j << 5)) * a.row_bytes;
+      const unsigned len = (unsigned)csize * a.row_bytes;
+      ring_push(a.ring, ch, cmd_w0(EP_OP_WRITE, a.src, dr, le), ((unsigned)(csize - 1) << 26) | (len >> 4),
+                (unsigned)(off >> 4), (unsigned)(off >> 4));
+      finished_rows = csize;
+    }
+  }
+  if (finished_rows) {
+    const int done = __hip_atomic_fetch_add(a.expert_done + e, finished_rows, __ATOMIC_ACQ_REL,
+                                            __HIP_MEMORY_SCOPE_AGENT) + finished_rows;
+    if (done == c) {
+      __hip_atomic_store(a.expert_done + e, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (!(a.cmd_mode & EP_CMD_ATOMICS_FIRST)) push_count_atomic(a, e, c);
+    }
+  }
+}
+
+// Kernel epilogue with EP_CMD_DRAIN: the last wavefront of the grid pushes a
+// Drain on every channel and blocks on Check-completion for each (Section 3.1:
+// Drain and Barrier are blocking on the GPU side).
+EP_DEV void emit_drain(const DispatchArgs &a, int lane) {
+  const unsigned total = gridDim.x * (blockDim.x >> 6);
+  unsigned done = 0;
+  if (lane == 0)
+    done = __hip_atomic_fetch_add(a.waves_done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+  done = __builtin_amdgcn_readfirstlane(done);
+  if (done != total) return;
+  if (lane == 0) __hip_atomic_store(a.waves_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (unsigned c = lane; c < a.ring.channels; c += 64) {
+    const unsigned long long idx = ring_push(a.ring, c, cmd_w0(EP_OP_DRAIN, a.src, 0, 0), 0u, 0u, 0u);
+    if (idx != ~0ull) ring_wait_completion(a.ring, c, idx);
+  }
+}
+
+// ------------------------------------------------------------ dispatch bf16
+// A token's row is H/8 16-byte vectors.  Wavefront (token, part) reads its
+// slice of the row ONCE into registers (VPL vectors per lane) and stores it to
+// every destination row; destination rows are wave-uniform and come from the
+// lanes that hold the token's (expert, row) pairs.
+template <int VPL>
+__global__ void dispatch_bf16_kernel(DispatchArgs a) {
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int part = wave % a.parts;
+  const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
+  const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
+  if (ring_on && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
+
+  const TokenMeta m = load_meta(a, t, lane);
+  unsigned long long vmask = __ballot(m.valid);
+  const int nvec = a.H >> 3;
+  const int v0 = part * VPL * 64 + lane;
+  if (vmask) {
+    const u32x4 *src = (const u32x4 *)a.x + (size_t)t * nvec;
+    u32x4 v[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (v0 + i * 64 < nvec) v[i] = __builtin_nontemporal_load(src + v0 + i * 64);
+    unsigned long long mm = vmask;
+    while (mm) {
+      const int k = __builtin_ctzll(mm);
+      mm &= mm - 1;
+      const int row = __builtin_amdgcn_readlane(m.row, k);
+      u32x4 *dst = (u32x4 *)a.recv + (size_t)row * nvec;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+        if (v0 + i * 64 < nvec) __builtin_nontemporal_store(v[i], dst + v0 + i * 64);
+    }
+  }
+  if (!ring_on) return;
+  // rows must be visible device-wide before a command announces them
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  if (a.parts > 1) __syncthreads();
+  if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  if (a.cmd_mode & EP_CMD_DRAIN) emit_drain(a, lane);
+}
+
+// ------------------------------------------------------------- dispatch FP8
+EP_DEV float bf16_lo(unsigned d) { return __uint_as_float(d << 16); }
+EP_DEV float bf16_hi(unsigned d) { return __uint_as_float(d & 0xFFFF0000u); }
+
+// Two floats -> two E4M3 codes (round to nearest even, saturate to +-448)
+// in the low or high half of a dword.  The clamp is exact, so the hardware
+// conversion never sees a value beyond the largest finite code.
+template <bool HI>
+EP_DEV unsigned cvt2_e4m3(float x, float y, unsigned old) {
+  x = __builtin_amdgcn_fmed3f(x, 448.0f, -448.0f);
+  y = __builtin_amdgcn_fmed3f(y, 448.0f, -448.0f);
+  return (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(x, y, (int)old, HI);
+}
+
+// A lane owns 16 consecutive channels (two 16-byte loads, one 16-byte store of
+// codes); 8 adjacent lanes own one 128-channel block and share its amax through
+// three xor-shuffles.  scale = amax/448 and inv = 448/amax are IEEE divisions.
+template <int VPL>
+__global__ void dispatch_fp8_kernel(DispatchArgs a) {
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int part = wave % a.parts;
+  const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
+  const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
+  if (ring_on && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
+
+  const TokenMeta m = load_meta(a, t, lane);
+  unsigned long long vmask = __ballot(m.valid);
+  const int npair = a.H >> 4;  // 16-channel groups per row
+  const int nblk = a.H >> 7;   // 128-channel blocks per row
+  const int p0 = part * VPL * 64 + lane;
+  if (vmask) {
+    const u32x4 *src = (const u32x4 *)a.x + (size_t)t * npair * 2;
+    u32x4 lo[VPL], hi[VPL], q[VPL];
+    float sc[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (p0 + i * 64 < npair) {
+        lo[i] = __builtin_nontemporal_load(src + 2 * (p0 + i * 64));
+        hi[i] = __builtin_nontemporal_load(src + 2 * (p0 + i * 64) + 1);
+      } else {
+        lo[i] = u32x4{0, 0, 0, 0};
+        hi[i] = u32x4{0, 0, 0, 0};
+      }
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      float f[16];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f[2 * j] = bf16_lo(lo[i][j]);
+        f[2 * j + 1] = bf16_hi(lo[i][j]);
+        f[8 + 2 * j] = bf16_lo(hi[i][j]);
+        f[8 + 2 * j + 1] = bf16_hi(hi[i][j]);
+      }
+      float amax = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) amax = fmaxf(amax, fabsf(f[j]));
+      amax = fmaxf(amax, __shfl_xor(amax, 1));
+      amax = fmaxf(amax, __shfl_xor(amax, 2));
+      amax = fmaxf(amax, __shfl_xor(amax, 4));
+      float scale = 1.0f, inv = 1.0f;
+      if (amax >= 0x1p-100f) {
+        scale = amax / 448.0f;
+        inv = 448.0f / amax;
+      }
+      sc[i] = scale;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        unsigned d = cvt2_e4m3<false>(f[4 * j] * inv, f[4 * j + 1] * inv, 0u);
+        q[i][j] = cvt2_e4m3<true>(f[4 * j + 2] * inv, f[4 * j + 3] * inv, d);
+      }
+    }
+    unsigned long long mm = vmask;
+    while (mm) {
+      const int k = __builtin_ctzll(mm);
+      mm &= mm - 1;
+      const int row = __builtin_amdgcn_readlane(m.row, k);
+      u32x4 *dq = (u32x4 *)a.recv + (size_t)row * npair;
+      float *ds = a.recv_scale + (size_t)row * nblk;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+        if (p0 + i * 64 < npair) {
+          __builtin_nontemporal_store(q[i], dq + p0 + i * 64);
+          if ((lane & 7) == 0) ds[(p0 + i * 64) >> 3] = sc[i];
+        }
+    }
+  }
+  if (!ring_on) return;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  if (a.parts > 1) __syncthreads();
+  if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  if (a.cmd_mode & EP_CMD_DRAIN) emit_drain(a, lane);
+}
+
+static int env_int(const char *name, int dflt) {
+  const char *s = getenv(name);
+  return (s && *s) ? atoi(s) : dflt;
+}
+
+static int pick_vpl(int units, const int *cands, int ncand) {
+  // smallest candidate that covers the row with one wavefront, else the largest
+  const int need = (units + 63) / 64;
+  for (int i = 0; i < ncand; ++i)
+    if (cands[i] >= need) return cands[i];
+  return cands[ncand - 1];
+}
+
+int tuned_dispatch_vpl(int H) {
+  static const int c[] = {1, 2, 4, 7, 8, 14, 16};
+  const int forced = env_int("EP_DISPATCH_VPL", 0);
+  for (int v : c)
+    if (v == forced) return v;
+  return pick_vpl(H / 8, c, 7);
+}
+
+static int tuned_dispatch_fp8_vpl(int H) {
+  static const int c[] = {1, 2, 4};  // more than 4 groups per lane would spill at 128 VGPRs
+  const int forced = env_int("EP_DISPATCH_FP8_VPL", 0);
+  for (int v : c)
+    if (v == forced) return v;
+  return pick_vpl(H / 16, c, 3);
+}
+
+int tuned_combine_vpl(int H) {
+  static const int c[] = {1, 2, 4};
+  const int forced = env_int("EP_COMBINE_VPL", 0);
+  for (int v : c)
+    if (v == forced) return v;
+  (void)H;
+  return 2;
+}
+
+template <int VPL>
+static void launch_dispatch_bf16_t(DispatchArgs a, hipStream_t st) {
+  const int nvec = a.H / 8;
+  a.parts = (nvec + VPL * 64 - 1) / (VPL * 64);
+  a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
+  const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
+  hipLaunchKernelGGL(dispatch_bf16_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st, a);
+}
+
+template <int VPL>
+static void launch_dispatch_fp8_t(DispatchArgs a, hipStream_t st) {
+  const int npair = a.H / 16;
+  a.parts = (npair + VPL * 64 - 1) / (VPL * 64);
+  a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
+  const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
+  hipLaunchKernelGGL(dispatch_fp8_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st, a);
+}
+
+int launch_dispatch(const DispatchArgs &a, int payload, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  // T == 0 with the ring on still launches one (idle) workgroup: it owes the zero-count atomics
+  if (a.T <= 0 && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_NONE) return 0;
+  if (payload == EP_BF16) {
+    const int vpl = tuned_dispatch_vpl(a.H);
+    if ((a.H / 8 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
+    switch (vpl) {
+      case 1: launch_dispatch_bf16_t<1>(a, st); break;
+      case 2: launch_dispatch_bf16_t<2>(a, st); break;
+      case 4: launch_dispatch_bf16_t<4>(a, st); break;
+      case 7: launch_dispatch_bf16_t<7>(a, st); break;
+      case 8: launch_dispatch_bf16_t<8>(a, st); break;
+      case 14: launch_dispatch_bf16_t<14>(a, st); break;
+      default: launch_dispatch_bf16_t<16>(a, st); break;
+    }
+  } else {
+    const int vpl = tuned_dispatch_fp8_vpl(a.H);
+    if ((a.H / 16 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
+    switch (vpl) {
+      case 1: launch_dispatch_fp8_t<1>(a, st); break;
+      case 2: launch_dispatch_fp8_t<2>(a, st); break;
+      default: launch_dispatch_fp8_t<4>(a, st); break;
+    }
+  }
+  return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------- combine
+// out[t, 8 channels] = bf16( sum_k w[t,k] * y[row_k, 8 channels] ): per 16-byte
+// column slice, K independent 16-byte loads are in flight per lane, then the
+// fp32 fused multiply-add chain runs in ascending k from +0, and the result is
+// rounded once (nearest even) to bf16.  Rows and weights are wave-uniform.
+EP_DEV unsigned pack_bf16_rne(float a, float b) {
+  unsigned ua = __float_as_uint(a), ub = __float_as_uint(b);
+  ua = (ua + 0x7FFFu + ((ua >> 16) & 1u)) >> 16;
+  ub = (ub + 0x7FFFu + ((ub >> 16) & 1u)) & 0xFFFF0000u;
+  return ua | ub;
+}
+
+EP_DEV void fma8(float (&acc)[8], float w, const u32x4 &v) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    acc[2 * j] = __builtin_fmaf(w, bf16_lo(v[j]), acc[2 * j]);
+    acc[2 * j + 1] = __builtin_fmaf(w, bf16_hi(v[j]), acc[2 * j + 1]);
+  }
+}
+
+template <int VPL, int KT>
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const long long item = (long long)blockIdx.x * 4 + wave;
+  const int t = (int)(item / a.parts), part = (int)(item % a.parts);
+  if (t >= a.T) return;
+  const int K = KT > 0 ? KT : a.K;
+  int row = -1;
+  float wt = 0.0f;
+  if (lane < K) {
+    row = a.dst_row[(size_t)t * K + lane];
+    wt = a.w[(size_t)t * K + lane];
+    if (row < -1 || row >= a.y_rows) {
+      dev_set_error(a.error, EP_EBOUNDS);
+      row = -1;
+    }
+  }
+  const unsigned long long vmask = __ballot(row >= 0);
+  const int nvec = a.H >> 3;
+  const int v0 = part * VPL * 64 + lane;
+  u32x4 *out = (u32x4 *)a.out + (size_t)t * nvec;
+  if (vmask == 0) {  // every k masked: +0
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (v0 + i * 64 < nvec) out[v0 + i * 64] = u32x4{0, 0, 0, 0};
+    return;
+  }
+  const u32x4 *y = (const u32x4 *)a.y;
+  if constexpr (KT > 0) {
+    const int safe = __builtin_amdgcn_readlane(row, __builtin_ctzll(vmask));
+    int rows[KT];
+    float ws[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+      rows[k] = __builtin_amdgcn_readlane(row, k);
+      ws[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wt), k));
+    }
+    u32x4 ld[VPL][KT];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (v0 + i * 64 < nvec) {
+#pragma unroll
+        for (int k = 0; k < KT; ++k)
+          ld[i][k] = __builtin_nontemporal_load(y + (size_t)(rows[k] >= 0 ? rows[k] : safe) * nvec + v0 + i * 64);
+      }
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (v0 + i * 64 < nvec) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < KT; ++k)
+          if (rows[k] >= 0) fma8(acc, ws[k], ld[i][k]);
+        u32x4 o = {pack_bf16_rne(acc[0], acc[1]), pack_bf16_rne(acc[2], acc[3]),
+                   pack_bf16_rne(acc[4], acc[5]), pack_bf16_rne(acc[6], acc[7])};
+        __builtin_nontemporal_store(o, out + v0 + i * 64);
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (v0 + i * 64 < nvec) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < K; ++k) {
+          const int r = __builtin_amdgcn_readlane(row, k);
+          const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wt), k));
+          if (r >= 0) fma8(acc, w, __builtin_nontemporal_load(y + (size_t)r * nvec + v0 + i * 64));
+        }
+        u32x4 o = {pack_bf16_rne(acc[0], acc[1]), pack_bf16_rne(acc[2], acc[3]),
+                   pack_bf16_rne(acc[4], acc[5]), pack_bf16_rne(acc[6], acc[7])};
+        __builtin_nontemporal_store(o, out + v0 + i * 64);
+      }
+  }
+}
+
+template <int VPL>
+static void launch_combine_t(CombineArgs a, hipStream_t st) {
+  const int nvec = a.H / 8;
+  a.parts = (nvec + VPL * 64 - 1) / (VPL * 64);
+  const long long items = (long long)a.T * a.parts;
+  const unsigned grid = (unsigned)((items + 3) / 4);
+  switch (a.K) {
+    case 1: hipLaunchKernelGGL((combine_kernel<VPL, 1>), dim3(grid), dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((combine_kernel<VPL, 2>), dim3(grid), dim3(256), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((combine_kernel<VPL, 4>), dim3(grid), dim3(256), 0, st, a); break;
+    case 6: hipLaunchKernelGGL((combine_kernel<VPL, 6>), dim3(grid), dim3(256), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((combine_kernel<VPL, 8>), dim3(grid), dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((combine_kernel<VPL, 0>), dim3(grid), dim3(256), 0, st, a); break;
+  }
+}
+
+int launch_combine(const CombineArgs &a, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (a.T <= 0) return 0;
+  switch (tuned_combine_vpl(a.H)) {
+    case 1: launch_combine_t<1>(a, st); break;
+    case 4: launch_combine_t<4>(a, st); break;
+    default: launch_combine_t<2>(a, st); break;
+  }
+  return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------------------- misc
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream) {
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, p, v, n);
+  return (int)hipGetLastError();
+}
+
+}  // namespace ep

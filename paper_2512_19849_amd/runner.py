@@ -1,0 +1,104 @@
+"""Device-buffer plumbing around the binding: allocates the torch tensors one
+workload needs and sequences ep_layout -> ep_dispatch -> ep_combine on the
+current stream.  No arithmetic of the method happens here."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as ep
+
+
+def bits_to_bf16(a: np.ndarray, device="cuda") -> torch.Tensor:
+    """uint16 bit patterns -> torch.bfloat16 tensor on the device (a reinterpretation)."""
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def bf16_to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@dataclass
+class LayoutOut:
+    count: torch.Tensor
+    expert_total: torch.Tensor
+    rank_total: torch.Tensor
+    base: torch.Tensor
+    expert_offset: torch.Tensor
+    rank_offset: torch.Tensor
+    slot: torch.Tensor
+    dst_row: torch.Tensor
+
+    def numpy(self) -> dict:
+        return {k: getattr(self, k).cpu().numpy() for k in self.__dataclass_fields__}
+
+
+class EPRunner:
+    """One handle plus the buffers of one workload shape."""
+
+    def __init__(self, R: int, E: int, K: int, H: int, max_tokens: int, S: int = 1, self_rank: int = 0,
+                 num_channels: int = 8, ring_entries: int = 4096, num_proxy_threads: int = 4,
+                 reorder_window: int = 0, reorder_seed: int = 0, spin_timeout_ms: int = 0, heap_rows: int = 0,
+                 flags: int = 0, device: str = "cuda"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("EPRunner needs a HIP device; there is no CPU path")
+        self.R, self.E, self.K, self.H, self.S, self.T_cap = R, E, K, H, S, max_tokens
+        self.E_loc = E // R
+        self.dev = torch.device(device)
+        self.heap_rows = heap_rows or S * max_tokens * K
+        self.h = ep.ep_proxy_start(R, E, K, H, max_tokens, S, self_rank, num_channels, ring_entries,
+                                   num_proxy_threads, reorder_window, reorder_seed, spin_timeout_ms, heap_rows,
+                                   flags)
+        i32 = dict(dtype=torch.int32, device=self.dev)
+        self.lay = LayoutOut(
+            count=torch.zeros((S, E), **i32), expert_total=torch.zeros(E, **i32), rank_total=torch.zeros(R, **i32),
+            base=torch.zeros((S, E), **i32), expert_offset=torch.zeros(E + 1, **i32),
+            rank_offset=torch.zeros(R + 1, **i32), slot=torch.zeros((S, max_tokens, K), **i32),
+            dst_row=torch.zeros((S, max_tokens, K), **i32))
+
+    def close(self) -> None:
+        if self.h:
+            ep.ep_proxy_stop(self.h)
+            self.h = 0
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # ---- the three calls -------------------------------------------------
+    def layout(self, topk_idx: torch.Tensor) -> LayoutOut:
+        """topk_idx int32 [S,T,K] on the device."""
+        S, T, K = topk_idx.shape
+        assert S == self.S and K == self.K and T <= self.T_cap and topk_idx.dtype == torch.int32
+        L = self.lay
+        slot, dst = L.slot, L.dst_row
+        if T != self.T_cap:
+            slot = torch.zeros((S, T, K), dtype=torch.int32, device=self.dev)
+            dst = torch.zeros((S, T, K), dtype=torch.int32, device=self.dev)
+        ep.ep_layout(self.h, topk_idx, T, L.count, L.expert_total, L.rank_total, L.base, L.expert_offset,
+                     L.rank_offset, slot, dst)
+        return LayoutOut(L.count, L.expert_total, L.rank_total, L.base, L.expert_offset, L.rank_offset, slot, dst)
+
+    def dispatch(self, x: torch.Tensor, topk_idx_s: torch.Tensor, lay: LayoutOut, recv: torch.Tensor,
+                 recv_scale: Optional[torch.Tensor] = None, src: int = 0, rank_filter: int = -1,
+                 payload: int = ep.EP_BF16, cmd_mode: int = ep.EP_CMD_NONE) -> None:
+        T = x.shape[0]
+        ep.ep_dispatch(self.h, x, topk_idx_s, lay.dst_row[src], lay.count[src], lay.base[src], T, src, rank_filter,
+                       payload, cmd_mode, recv, recv_scale, recv.shape[0])
+
+    def combine(self, y: torch.Tensor, topk_w_s: torch.Tensor, dst_row_s: torch.Tensor, out: torch.Tensor) -> None:
+        ep.ep_combine(self.h, y, topk_w_s, dst_row_s, out.shape[0], y.shape[0], out)
+
+    def wait(self) -> None:
+        ep.ep_wait(self.h)
+
+    def stats(self) -> dict:
+        return ep.ep_stats(self.h)
+
+    def counters(self) -> np.ndarray:
+        return ep.ep_counters(self.h, self.S, self.E)

@@ -1,0 +1,406 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Integer / byte work is compared bit-exactly;
+combine within 1 bf16 ulp of the oracle and within the fp64 bound."""
+import numpy as np
+import pytest
+
+import ep_inputs as g
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def epmod():
+    import paper_2512_19849_amd as ep
+    ep.load_library(build_if_missing=False)      # the built library must be there: no fallback
+    return ep
+
+
+def _runner(epmod, cfg, T=None, **kw):
+    from paper_2512_19849_amd.runner import EPRunner
+    kw.setdefault("spin_timeout_ms", 3000)
+    return EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, T if T is not None else cfg.T, S=cfg.S, **kw)
+
+
+def _dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def _check_layout(oracle, got: dict, idx, E, R):
+    want = oracle.layout(idx, E, R)
+    for name in ("count", "expert_total", "rank_total", "base", "expert_offset", "rank_offset", "slot", "dst_row"):
+        assert np.array_equal(got[name], want[name]), name
+    return want
+
+
+# ------------------------------------------------------------------ layout
+@pytest.mark.parametrize("cid,T,mask", [(1, None, 0.0), (1, 37, 0.3), (2, None, 0.0), (2, 100, 0.1),
+                                        (4, None, 0.0), (4, 4095, 0.05), (5, None, 0.0), (5, 1, 0.0),
+                                        (4, 65, 0.0), (1, 0, 0.0)])
+def test_layout_parity(epmod, oracle, cid, T, mask):
+    cfg = g.config(cid)
+    idx, _ = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=17)
+    with _runner(epmod, cfg, idx.shape[1] or 1) as r:
+        for rep in range(2):                                   # second call: scratch must have reset itself
+            lay = r.layout(_dev(idx))
+            torch.cuda.synchronize()
+            _check_layout(oracle, lay.numpy(), idx, cfg.E, cfg.R)
+        assert r.stats()["device_error"] == 0
+
+
+def test_layout_special_shapes(epmod, oracle):
+    rng = np.random.default_rng(0)
+    for (S, T, K, E, R) in [(1, 300, 1, 1, 1), (3, 129, 4, 8, 8), (2, 64, 6, 96, 3), (1, 1000, 8, 1024, 4),
+                            (5, 77, 3, 12, 2)]:
+        idx = np.stack([np.stack([rng.permutation(E)[:K] for _ in range(T)]) for _ in range(S)]).astype(np.int32)
+        cfg = g.EPConfig("x", T=T, H=128, E=E, K=K, R=R, S=S)
+        with _runner(epmod, cfg) as r:
+            lay = r.layout(_dev(idx))
+            torch.cuda.synchronize()
+            _check_layout(oracle, lay.numpy(), idx, E, R)
+    # all tokens to one expert; everything masked
+    cfg = g.EPConfig("x", T=500, H=128, E=16, K=1, R=4)
+    for idx in (np.full((1, 500, 1), 9, np.int32), np.full((1, 500, 1), -1, np.int32)):
+        with _runner(epmod, cfg) as r:
+            lay = r.layout(_dev(idx))
+            torch.cuda.synchronize()
+            _check_layout(oracle, lay.numpy(), idx, 16, 4)
+
+
+# ---------------------------------------------------------- dispatch bf16
+def _dispatch_case(epmod, oracle, cfg, T, mask, cmd_mode, rank_filter=-1, src=0, extra_rows=3, **kw):
+    idx, w = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=23)
+    T = idx.shape[1]
+    x = g.activations(cfg, src, T=T)
+    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    rows = int((idx >= 0).sum()) + extra_rows
+    with _runner(epmod, cfg, T, flags=flags, heap_rows=rows, **kw) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        recv = torch.full((rows, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")     # sentinel 0xBFC0
+        from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+        r.dispatch(bits_to_bf16(x), d_idx[src], lay, recv, src=src, rank_filter=rank_filter, cmd_mode=cmd_mode)
+        if (cmd_mode & 0xFF) != epmod.EP_CMD_NONE:
+            r.wait()
+        torch.cuda.synchronize()
+        layn = lay.numpy()
+        want_lay = _check_layout(oracle, layn, idx, cfg.E, cfg.R)
+        want, wc = oracle.dispatch_bf16(x, idx[src], want_lay["dst_row"][src], cfg.E_loc, rows, rank_filter,
+                                        fill=0xBFC0)
+        got = bf16_to_bits(recv)
+        assert np.array_equal(got, want)
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        return dict(stats=st, cmds=epmod.ep_cmd_log(r.h), events=epmod.ep_event_log(r.h), lay=want_lay, idx=idx,
+                    counters=r.counters().copy(), x=x, recv=got)
+
+
+@pytest.mark.parametrize("cid,T,mask", [(1, None, 0.0), (1, 50, 0.25), (2, None, 0.0), (4, 300, 0.0),
+                                        (5, 257, 0.1), (4, 1, 0.0)])
+def test_dispatch_bf16_ring_off(epmod, oracle, cid, T, mask):
+    cfg = g.config(cid)
+    out = _dispatch_case(epmod, oracle, cfg, T, mask, epmod.EP_CMD_NONE)
+    assert out["stats"]["cmds"] == 0
+
+
+def test_dispatch_bf16_other_source_and_rank_filter(epmod, oracle):
+    cfg = g.config(2)                                           # 32 sources, inbound share of rank 0
+    _dispatch_case(epmod, oracle, cfg, 64, 0.0, epmod.EP_CMD_NONE, rank_filter=0, src=7)
+    _dispatch_case(epmod, oracle, cfg, 64, 0.0, epmod.EP_CMD_PER_TOKEN, rank_filter=5, src=31)
+
+
+@pytest.mark.parametrize("vpl", [1, 2, 4, 7, 8, 14, 16])
+def test_dispatch_bf16_every_row_split(epmod, oracle, vpl, monkeypatch):
+    monkeypatch.setenv("EP_DISPATCH_VPL", str(vpl))
+    _dispatch_case(epmod, oracle, g.config(4), 70, 0.05, epmod.EP_CMD_CHUNK32)
+    _dispatch_case(epmod, oracle, g.config(1), 33, 0.0, epmod.EP_CMD_PER_TOKEN)
+
+
+# ------------------------------------------------------ commands and proxy
+def _check_commands(epmod, oracle, cfg, out, mode_name, payload="bf16", src=0, rank_filter=-1):
+    want = oracle.expected_cmds(out["idx"][src], out["lay"], src, cfg.E_loc, cfg.H, payload, mode_name, rank_filter)
+    got = oracle.cmd_multiset(out["cmds"])
+    assert got == want
+    for w in out["cmds"]:
+        d = oracle.decode_cmd(w)
+        assert d["gen"] == d["gen_hi"]
+    res = oracle.check_fence_trace(out["events"], out["lay"]["count"])
+    E_loc = cfg.E_loc
+    sel = np.arange(cfg.E) // E_loc == rank_filter if rank_filter >= 0 else np.ones(cfg.E, bool)
+    assert np.array_equal(out["counters"][src][sel], out["lay"]["count"][src][sel])
+    st = out["stats"]
+    assert st["atomics_applied"] == int(sel.sum()) == st["atomics"]
+    assert st["write_rows"] == int(out["lay"]["count"][src][sel].sum())
+    assert st["write_bytes"] == st["write_rows"] * oracle.row_bytes(cfg.H, payload)
+    return res
+
+
+@pytest.mark.parametrize("cid,T,mask,window", [(1, None, 0.0, 0), (1, None, 0.2, 4), (2, 128, 0.0, 64),
+                                               (4, 200, 0.0, 0), (5, 300, 0.1, 7)])
+def test_dispatch_per_token_commands(epmod, oracle, cid, T, mask, window):
+    cfg = g.config(cid, S=1)
+    out = _dispatch_case(epmod, oracle, cfg, T, mask, epmod.EP_CMD_PER_TOKEN, reorder_window=window, reorder_seed=5)
+    _check_commands(epmod, oracle, cfg, out, "per_token")
+    # the commands alone determine the receive buffer
+    rows = out["recv"].shape[0]
+    send = out["x"].view(np.uint8).reshape(out["x"].shape[0], -1)
+    heap, hits = oracle.replay_writes_per_token(out["cmds"], send, rows, fill_byte=0)
+    nvalid = int((out["idx"] >= 0).sum())
+    assert (hits[:nvalid] == 1).all() and (hits[nvalid:] == 0).all()
+    assert np.array_equal(heap[:nvalid], out["recv"].view(np.uint8).reshape(rows, -1)[:nvalid])
+
+
+@pytest.mark.parametrize("cid,T,mask,window", [(1, None, 0.0, 0), (4, 700, 0.0, 0), (4, 700, 0.1, 16),
+                                               (5, 1000, 0.0, 64)])
+def test_dispatch_chunk32_commands(epmod, oracle, cid, T, mask, window):
+    cfg = g.config(cid, S=1)
+    out = _dispatch_case(epmod, oracle, cfg, T, mask, epmod.EP_CMD_CHUNK32, reorder_window=window, reorder_seed=9)
+    _check_commands(epmod, oracle, cfg, out, "chunk32")
+    oracle.check_chunk_cover(out["cmds"], out["lay"], 0, cfg.E_loc, oracle.row_bytes(cfg.H, "bf16"))
+
+
+def test_atomics_first_forces_the_fence_path(epmod, oracle):
+    cfg = g.config(1)
+    for mode, name in ((epmod.EP_CMD_PER_TOKEN, "per_token"), (epmod.EP_CMD_CHUNK32, "chunk32")):
+        out = _dispatch_case(epmod, oracle, cfg, None, 0.0, mode | epmod.EP_CMD_ATOMICS_FIRST, num_channels=1,
+                             num_proxy_threads=1)
+        res = _check_commands(epmod, oracle, cfg, out, name)
+        # one channel, atomics pushed by the first wavefront before it stores anything: atomics with a
+        # nonzero count reach the receiver ahead of (some of) their rows and must wait
+        assert res["waited"] == out["stats"]["atomics_deferred"] and res["waited"] >= 1
+
+
+def test_drain_blocks_until_popped_and_small_ring_backpressure(epmod, oracle):
+    cfg = g.config(1)
+    out = _dispatch_case(epmod, oracle, cfg, None, 0.0, epmod.EP_CMD_PER_TOKEN | epmod.EP_CMD_DRAIN,
+                         ring_entries=8, num_channels=2, num_proxy_threads=2, reorder_window=3)
+    _check_commands(epmod, oracle, cfg, out, "per_token")
+    assert out["stats"]["drains"] == 2
+    # 128 writes + 16 atomics through 2 rings of 8 slots: laps wrapped many times without loss
+    assert out["stats"]["cmds"] == 128 + 16 + 2
+
+
+def test_repeated_dispatch_reuses_scratch_and_counters(epmod, oracle):
+    cfg = g.config(5, S=1)
+    idx, _ = g.routing_all(cfg, 600)
+    x = g.activations(cfg, 0, T=600)
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    with _runner(epmod, cfg, 600) as r:
+        d_idx, d_x = _dev(idx), bits_to_bf16(x)
+        lay = r.layout(d_idx)
+        want_lay = oracle.layout(idx, cfg.E, cfg.R)
+        want, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, idx.size)
+        for it, mode in enumerate([epmod.EP_CMD_CHUNK32, epmod.EP_CMD_PER_TOKEN, epmod.EP_CMD_CHUNK32]):
+            recv = torch.zeros((idx.size, cfg.H), dtype=torch.bfloat16, device="cuda")
+            r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=mode)
+            r.wait()
+            torch.cuda.synchronize()
+            assert np.array_equal(bf16_to_bits(recv), want)
+            st = r.stats()
+            assert st["atomics_applied"] == cfg.E * (it + 1) and st["write_rows"] == idx.size * (it + 1)
+            assert np.array_equal(r.counters()[0], want_lay["count"][0])
+
+
+# ------------------------------------------------------------------- FP8
+def _fp8_case(epmod, oracle, cfg, x, idx, cmd_mode):
+    T = idx.shape[1]
+    rows = int((idx >= 0).sum()) + 2
+    from paper_2512_19849_amd.runner import bits_to_bf16
+    with _runner(epmod, cfg, T, flags=epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS, heap_rows=rows) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        rq = torch.full((rows, cfg.H), 0xA5, dtype=torch.uint8, device="cuda")
+        rs = torch.full((rows, cfg.H // 128), -1.0, dtype=torch.float32, device="cuda")
+        r.dispatch(bits_to_bf16(x), d_idx[0], lay, rq, rs, payload=epmod.EP_FP8_E4M3, cmd_mode=cmd_mode)
+        if cmd_mode != epmod.EP_CMD_NONE:
+            r.wait()
+        torch.cuda.synchronize()
+        want_lay = oracle.layout(idx, cfg.E, cfg.R)
+        wq, ws, _ = oracle.dispatch_fp8(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+        gq, gs = rq.cpu().numpy(), rs.cpu().numpy()
+        assert np.array_equal(gs.view(np.uint32), ws.view(np.uint32)), "scales differ"
+        bad = np.argwhere(gq != wq)
+        assert bad.size == 0, f"{len(bad)} codes differ, first at {bad[:3].tolist()}"
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0
+        return dict(stats=st, cmds=epmod.ep_cmd_log(r.h), events=epmod.ep_event_log(r.h), lay=want_lay, idx=idx,
+                    counters=r.counters().copy())
+
+
+@pytest.mark.parametrize("cid,T,mask,mode", [(3, None, 0.0, "none"), (3, None, 0.2, "per_token"),
+                                             (5, 400, 0.0, "chunk32"), (4, 150, 0.0, "none")])
+def test_dispatch_fp8_parity(epmod, oracle, cid, T, mask, mode):
+    cfg = g.config(cid, S=1)
+    idx, _ = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=29)
+    x = g.activations(cfg, 0, T=idx.shape[1])
+    out = _fp8_case(epmod, oracle, cfg, x, idx, epmod.CMD_MODES[mode])
+    if mode != "none":
+        _check_commands(epmod, oracle, cfg, out, mode, payload="fp8")
+
+
+def test_fp8_quantiser_all_bf16_inputs_and_corner_blocks(epmod, oracle):
+    """Every finite bf16 value goes through the kernel's quantiser, grouped so
+    that blocks hold similar magnitudes (dense coverage of rounding cases),
+    then again in a seeded shuffle (wide dynamic range inside a block); plus
+    zero / tiny / threshold blocks and exact ties."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    fin = bits[np.isfinite(g.bf16_bits_to_f32(bits))]
+    by_mag = fin[np.argsort(np.abs(g.bf16_bits_to_f32(fin)), kind="stable")]
+    rng = np.random.default_rng(7)
+    H = 1024
+    pad = (-len(fin)) % H
+    parts = [np.concatenate([by_mag, by_mag[:pad]]), np.concatenate([rng.permutation(fin), fin[:pad]])]
+    # neighbouring-magnitude blocks with one larger peak: exercises many inv values per value
+    for mul in (2, 3, 7, 11):
+        blk = np.concatenate([by_mag, by_mag[:pad]]).reshape(-1, 128).copy()
+        peak = np.abs(g.bf16_bits_to_f32(blk)).max(axis=1) * mul
+        ok = np.isfinite(peak.astype(np.float32)) & (peak < 3e38)
+        blk[ok, 0] = g.f32_to_bf16_bits(peak[ok].astype(np.float32))
+        parts.append(blk.reshape(-1))
+    corner = np.zeros((8, H), np.uint16)
+    corner[0, 5] = 0x8000                                       # zero block with a -0
+    corner[1, :128] = 0x0080; corner[1, 1] = 0x8080             # 2^-126 everywhere
+    corner[2, 0] = g.f32_to_bf16_bits(np.array([2.0 ** -100], np.float32))[0]
+    corner[2, 1] = g.f32_to_bf16_bits(np.array([-(2.0 ** -101)], np.float32))[0]
+    corner[3, 0] = g.f32_to_bf16_bits(np.array([2.0 ** -101], np.float32))[0]
+    corner[4, :128] = g.f32_to_bf16_bits(np.array([1.5703125] * 128, np.float32)); corner[4, 0] = \
+        g.f32_to_bf16_bits(np.array([2.09375], np.float32))[0]  # y = 336: exact tie between 320 and 352
+    corner[5, :128] = 0x0001                                    # smallest bf16 subnormal
+    corner[6, :256] = g.f32_to_bf16_bits(rng.normal(0, 1e-30, 256).astype(np.float32))
+    corner[7, :] = g.f32_to_bf16_bits(rng.normal(0, 1e30, H).astype(np.float32))
+    x = np.concatenate([p.reshape(-1, H) for p in parts] + [corner])
+    T = x.shape[0]
+    cfg = g.EPConfig("fp8sweep", T=T, H=H, E=4, K=1, R=2)
+    idx = (np.arange(T, dtype=np.int32) % 4).reshape(1, T, 1)
+    _fp8_case(epmod, oracle, cfg, x, idx, epmod.EP_CMD_NONE)
+
+
+# --------------------------------------------------------------- combine
+def _combine_check(oracle, out_bits, y, w, dst_row, K):
+    want = oracle.combine(y, w, dst_row)
+    ulp = oracle.bf16_ulp_distance(out_bits, want)
+    assert ulp.max() <= 1, f"max distance {ulp.max()} bf16 steps"
+    ref, mag = oracle.combine_f64(y, w, dst_row)
+    got = g.bf16_bits_to_f32(out_bits).astype(np.float64)
+    bound = 2.0 ** -8 * np.abs(ref) + K * 2.0 ** -24 * mag * (1 + 2.0 ** -7) + 2.0 ** -133
+    assert (np.abs(got - ref) <= bound).all()
+    return int((ulp != 0).sum())
+
+
+@pytest.mark.parametrize("cid,T,mask", [(1, None, 0.0), (1, 41, 0.3), (2, None, 0.0), (4, 200, 0.0),
+                                        (5, 300, 0.1)])
+def test_combine_parity(epmod, oracle, cid, T, mask):
+    cfg = g.config(cid, S=1)
+    idx, w = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=31)
+    T = idx.shape[1]
+    lay = oracle.layout(idx, cfg.E, cfg.R)
+    rows = max(1, int((idx >= 0).sum()))
+    y = g.activations(cfg, 0, tid=g.TID_Y, T=rows)
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    with _runner(epmod, cfg, T) as r:
+        out = torch.full((T, cfg.H), 7.0, dtype=torch.bfloat16, device="cuda")
+        r.combine(bits_to_bf16(y), _dev(w[0]), _dev(lay["dst_row"][0]), out)
+        torch.cuda.synchronize()
+        ndiff = _combine_check(oracle, bf16_to_bits(out), y, w[0], lay["dst_row"][0], cfg.K)
+        assert ndiff == 0          # same fused chain on both sides: expected bit-equal
+        assert r.stats()["device_error"] == 0
+
+
+@pytest.mark.parametrize("K,vpl", [(1, 1), (3, 2), (5, 4), (6, 1), (8, 4), (2, 2), (4, 1)])
+def test_combine_generic_k_and_splits(epmod, oracle, K, vpl, monkeypatch):
+    monkeypatch.setenv("EP_COMBINE_VPL", str(vpl))
+    cfg = g.EPConfig("ck", T=90, H=1536, E=24, K=K, R=3, seed=99)
+    idx, w = g.routing_all(cfg)
+    idx = g.mask_random(idx, 0.2, seed=3)
+    idx[0, 5, :] = -1                                          # a token with every k masked
+    lay = oracle.layout(idx, cfg.E, cfg.R)
+    rows = int((idx >= 0).sum())
+    y = g.activations(cfg, 0, tid=g.TID_Y, T=rows)
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    with _runner(epmod, cfg) as r:
+        out = torch.full((cfg.T, cfg.H), 7.0, dtype=torch.bfloat16, device="cuda")
+        r.combine(bits_to_bf16(y), _dev(w[0]), _dev(lay["dst_row"][0]), out)
+        torch.cuda.synchronize()
+        ob = bf16_to_bits(out)
+        assert _combine_check(oracle, ob, y, w[0], lay["dst_row"][0], K) == 0
+        assert (ob[5] == 0).all()
+
+
+def test_round_trip_identity_expert(epmod, oracle):
+    """dispatch -> identity expert -> combine returns the input scaled by the
+    sum of its weights; with K = 1 and w = 1 it is the input, bit for bit."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    for cid, K in ((1, None), (1, 1), (4, None)):
+        cfg = g.config(cid, S=1) if K is None else g.config(cid, S=1, K=K)
+        T = min(cfg.T, 256)
+        idx, w = g.routing_all(cfg, T)
+        if K == 1:
+            w = np.ones_like(w)
+        x = g.activations(cfg, 0, T=T)
+        with _runner(epmod, cfg, T) as r:
+            d_idx = _dev(idx)
+            lay = r.layout(d_idx)
+            recv = torch.zeros((idx.size, cfg.H), dtype=torch.bfloat16, device="cuda")
+            r.dispatch(bits_to_bf16(x), d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_PER_TOKEN)
+            out = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+            r.combine(recv, _dev(w[0]), lay.dst_row[0], out)
+            r.wait()
+            torch.cuda.synchronize()
+            ob = bf16_to_bits(out)
+            if K == 1:
+                assert np.array_equal(ob, x)
+            else:
+                xf = g.bf16_bits_to_f32(x).astype(np.float64)
+                want = xf * w[0].astype(np.float64).sum(1, keepdims=True)
+                got = g.bf16_bits_to_f32(ob).astype(np.float64)
+                assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) * (1 + 2.0 ** -10) + 2.0 ** -133).all()
+                assert oracle.bf16_ulp_distance(ob, x).max() <= 1
+
+
+# ------------------------------------------------------------- error paths
+def test_host_side_argument_errors(epmod):
+    from paper_2512_19849_amd.runner import EPRunner
+    with pytest.raises(epmod.EPError):
+        epmod.ep_proxy_start(3, 16, 2, 1024, 64)               # E % R != 0
+    with pytest.raises(epmod.EPError):
+        epmod.ep_proxy_start(4, 16, 2, 1000, 64)               # H % 128 != 0
+    with EPRunner(4, 16, 2, 1024, 64, num_proxy_threads=0) as r:
+        idx = torch.zeros((1, 64, 2), dtype=torch.int32, device="cuda")
+        lay = r.layout(idx)
+        x = torch.zeros((64, 1024), dtype=torch.bfloat16, device="cuda")
+        recv = torch.zeros((128, 1024), dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(epmod.EPError):                     # ring on but no proxy thread
+            r.dispatch(x, idx[0], lay, recv, cmd_mode=epmod.EP_CMD_PER_TOKEN)
+        with pytest.raises(epmod.EPError):                     # more tokens than the handle's capacity
+            epmod.ep_layout(r.h, idx, 65, lay.count, lay.expert_total, lay.rank_total, lay.base,
+                            lay.expert_offset, lay.rank_offset, lay.slot, lay.dst_row)
+        torch.cuda.synchronize()
+
+
+def test_device_side_bounds_check_reports_instead_of_faulting(epmod, oracle):
+    """A destination row beyond the receive buffer is skipped by the kernel's
+    own bounds check and surfaces as EP_EBOUNDS."""
+    from paper_2512_19849_amd.runner import EPRunner
+    cfg = g.config(1)
+    idx, _ = g.routing_all(cfg)
+    with EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, cfg.T, spin_timeout_ms=2000) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        x = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        recv = torch.zeros((100, cfg.H), dtype=torch.bfloat16, device="cuda")   # 128 rows needed
+        r.dispatch(x, d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_NONE)
+        torch.cuda.synchronize()
+        assert r.stats()["device_error"] == epmod.EP_EBOUNDS
+        with pytest.raises(epmod.EPError):
+            r.wait()

@@ -7,17 +7,20 @@ import pytest
 import ep_inputs as g
 
 
-def _encode(op, src, dst_rank, local, w1, src_off, dst_or_counter, gen=1):
-    """Build the four words by hand from the documented bit layout."""
+def _encode(op, src, dst_rank, local, w1, src_off, dst_or_counter, gen=1, rb=None):
+    """Build the four words by hand from the documented bit layout.  For a
+    Write, w1 arrives as a byte count and rb is the bytes of one row."""
     w0 = (gen << 31) | (op << 28) | (src << 20) | (dst_rank << 12) | local
+    if op == 1:
+        w1 = ((w1 // rb - 1) << 26) | (w1 >> 4)
     w3 = (gen << 31) | (dst_or_counter >> 4 if op == 1 else dst_or_counter)
     return [w0, w1, src_off >> 4, w3]
 
 
-def _log_from(ms):
+def _log_from(ms, rb):
     rows = []
     for key, n in ms.items():
-        rows += [_encode(*key)] * n
+        rows += [_encode(*key, rb=rb)] * n
     return np.array(rows, np.uint32).reshape(-1, 4)
 
 
@@ -36,7 +39,7 @@ def test_expected_per_token_commands_replay_to_the_dispatch_result(oracle, paylo
     rb = oracle.row_bytes(cfg.H, payload)
     assert sum(k[4] * n for k, n in ms.items() if k[0] == oracle.OP_WRITE) == rows * rb
     assert sum(k[4] * n for k, n in ms.items() if k[0] == oracle.OP_ATOMIC) == rows
-    log = _log_from(ms)
+    log = _log_from(ms, rb)
     assert oracle.cmd_multiset(log) == ms                       # decode is the inverse of the layout
     if payload == "bf16":
         send = x.view(np.uint8).reshape(cfg.T, rb)
@@ -69,14 +72,14 @@ def test_expected_chunk_commands_tile_every_expert(oracle):
     ms = oracle.expected_cmds(idx, lay, 0, cfg.E_loc, cfg.H, "bf16", "chunk32")
     nW = sum(n for k, n in ms.items() if k[0] == oracle.OP_WRITE)
     assert nW == int(np.ceil(lay["count"][0] / 32).sum())
-    log = _log_from(ms)
+    log = _log_from(ms, 14336)
     oracle.check_chunk_cover(log, lay, 0, cfg.E_loc, oracle.row_bytes(cfg.H, "bf16"))
     # planted mistakes: a dropped chunk, a chunk that crosses into the next expert
     writes = [i for i, w in enumerate(log) if oracle.decode_cmd(w)["op"] == oracle.OP_WRITE]
     with pytest.raises(AssertionError):
         oracle.check_chunk_cover(np.delete(log, writes[3], axis=0), lay, 0, cfg.E_loc, 14336)
     bad = log.copy()
-    bad[writes[0], 1] += 14336
+    bad[writes[0], 1] += (1 << 26) + (14336 >> 4)
     with pytest.raises(AssertionError):
         oracle.check_chunk_cover(bad, lay, 0, cfg.E_loc, 14336)
     # filter keeps only one rank's experts
@@ -87,10 +90,10 @@ def test_expected_chunk_commands_tile_every_expert(oracle):
 
 def test_replay_rejects_out_of_region_commands(oracle):
     send = np.zeros((4, 64), np.uint8)
-    ok = np.array([_encode(1, 0, 0, 0, 64, 64, 128)], np.uint32)
+    ok = np.array([_encode(1, 0, 0, 0, 64, 64, 128, rb=64)], np.uint32)
     oracle.replay_writes_per_token(ok, send, 3)
-    for bad in (_encode(1, 0, 0, 0, 64, 64 * 4, 0), _encode(1, 0, 0, 0, 64, 0, 64 * 3),
-                _encode(1, 0, 0, 0, 48, 0, 0)):
+    for bad in (_encode(1, 0, 0, 0, 64, 64 * 4, 0, rb=64), _encode(1, 0, 0, 0, 64, 0, 64 * 3, rb=64),
+                _encode(1, 0, 0, 0, 48, 0, 0, rb=48), _encode(1, 0, 0, 0, 128, 0, 0, rb=128)):
         with pytest.raises(ValueError):
             oracle.replay_writes_per_token(np.array([bad], np.uint32), send, 3)
 
