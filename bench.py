@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the expert-parallel hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input:
+ep_layout -> ep_dispatch (payload placement + transfer commands through the
+FIFO channels to the CPU proxy) -> identity expert -> ep_combine -> ep_wait
+(the proxy has posted every completion counter of the step).
+
+Workload: the 4096-token x hidden-7168 x 256-expert top-8 prefill share
+(16 simulated ranks, Zipf-skewed routing), inputs resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(T, H, K, rows, payload="bf16"):
+    """Bytes the method itself must move (per launch).  dispatch bf16: read each token row once,
+    write one row per valid (t,k), plus 8 bytes of (expert, row) metadata per (t,k).
+    combine: read one row per valid (t,k), write each token row once, plus 8 bytes
+    (row, weight) per (t,k)."""
+    meta = 8 * T * K
+    if payload == "bf16":
+        disp = 2 * H * T + 2 * H * rows + meta
+    else:
+        disp = 2 * H * T + (H + H // 32) * rows + meta
+    comb = 2 * H * rows + 2 * H * T + meta
+    return disp, comb
+
+
+def read_traffic(kernel_key: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+    copy kernel of known size); taken from the committed summary under profiles/ if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg4.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(rf"^{kernel_key}\s+traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload id (4 = the headline prefill share)")
+    ap.add_argument("--payload", default=None, choices=["bf16", "fp8"])
+    ap.add_argument("--cmd-mode", default=None, choices=["per_token", "chunk32", "none"])
+    ap.add_argument("--proxy-threads", type=int, default=4)
+    ap.add_argument("--channels", type=int, default=8)
+    ap.add_argument("--ring-entries", type=int, default=4096)
+    ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0,
+                    help="also launch N plain device copies of 1 GiB (counter calibration for rocprofv3 --pmc)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the other EP ranks are partitions of its HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import ep_inputs as g
+    import paper_2512_19849_amd as ep
+    from paper_2512_19849_amd.runner import EPRunner, bf16_to_bits, bits_to_bf16
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device; there is no CPU path", file=sys.stderr)
+        return 3
+    ep.load_library(build_if_missing=False)
+
+    cfg = g.config(args.config, S=1)
+    payload = args.payload or cfg.payload
+    cmd_mode_name = args.cmd_mode or cfg.cmd_mode
+    cmd_mode = ep.CMD_MODES[cmd_mode_name]
+    T, H, K, E, R = cfg.T, cfg.H, cfg.K, cfg.E, cfg.R
+    idx, w = g.routing_all(cfg)
+    x = g.activations(cfg)
+    rows = int((idx >= 0).sum())
+    disp_bytes, comb_bytes = algorithmic_bytes(T, H, K, rows, payload)
+
+    threads = args.proxy_threads if cmd_mode != ep.EP_CMD_NONE else 0
+    r = EPRunner(R, E, K, H, T, S=1, num_channels=args.channels, ring_entries=args.ring_entries,
+                 num_proxy_threads=max(threads, 0), spin_timeout_ms=10000)
+    d_idx = torch.from_numpy(idx).cuda()
+    d_w = torch.from_numpy(w[0]).cuda()
+    d_x = bits_to_bf16(x)
+    if payload == "bf16":
+        recv = torch.zeros((rows, H), dtype=torch.bfloat16, device="cuda")
+        scale = None
+        y = recv                                   # identity expert: combine reads the received rows
+    else:
+        recv = torch.zeros((rows, H), dtype=torch.uint8, device="cuda")
+        scale = torch.zeros((rows, H // 128), dtype=torch.float32, device="cuda")
+        y = bits_to_bf16(g.activations(cfg, 0, tid=g.TID_Y, T=rows))   # expert outputs are bf16
+    out = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+    pl = ep.PAYLOADS[payload]
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        lay = r.layout(d_idx)
+        if ev:
+            ev[1].record()
+        r.dispatch(d_x, d_idx[0], lay, recv, scale, payload=pl, cmd_mode=cmd_mode)
+        if ev:
+            ev[2].record()
+        r.combine(y, d_w, lay.dst_row[0], out)
+        if ev:
+            ev[3].record()
+        if cmd_mode != ep.EP_CMD_NONE:
+            r.wait()
+        return lay
+
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(args.calibrate_copy):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if cmd_mode != ep.EP_CMD_NONE:
+        ep.ep_reset_stats(r.h)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        lay = step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    st = r.stats()
+
+    lay_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    disp_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    comb_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    total_bytes = disp_bytes + comb_bytes
+    value = total_bytes / (ms_per_step * 1e-3) / 1e9
+
+    dom = "dispatch" if disp_ms >= comb_ms else "combine"
+    dom_ms, dom_bytes = (disp_ms, disp_bytes) if dom == "dispatch" else (comb_ms, comb_bytes)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {"kernel": f"{dom}_{payload if dom == 'dispatch' else 'bf16'}", "bound": "hbm",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(dom),
+                "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes": dom_bytes}
+
+    verified = None
+    cpu_baseline = None
+    if not (args.no_verify and args.no_cpu_baseline):
+        from oracle import ep_oracle as oracle
+        ncores = min(oracle.max_threads(), len(os.sched_getaffinity(0)), 16)
+        best = {}
+        res = {}
+        for nthr in ([1, ncores] if not args.no_cpu_baseline else [ncores]):
+            oracle.set_threads(nthr)
+            for rep in range(2 if not args.no_cpu_baseline else 1):
+                c0 = time.perf_counter()
+                olay = oracle.layout(idx, E, R)
+                if payload == "bf16":
+                    orecv, _ = oracle.dispatch_bf16(x, idx[0], olay["dst_row"][0], cfg.E_loc, rows)
+                    oy = orecv
+                else:
+                    oq, os_, _ = oracle.dispatch_fp8(x, idx[0], olay["dst_row"][0], cfg.E_loc, rows)
+                    oy = bf16_to_bits(y)
+                oout = oracle.combine(oy, w[0], olay["dst_row"][0])
+                dt = time.perf_counter() - c0
+                best[nthr] = min(best.get(nthr, 1e9), dt)
+            res = dict(olay=olay, oout=oout)
+        if not args.no_cpu_baseline:
+            cpu_baseline = {"value": round(total_bytes / best[ncores] / 1e9, 3), "unit": "GB/s", "cores": ncores,
+                            "kind": "oracle",
+                            "sample": f"the full {cfg.name} workload ({T} tokens), one pass of layout+dispatch+combine, "
+                                      f"best of 2",
+                            "value_1_thread": round(total_bytes / best[1] / 1e9, 3),
+                            "tokens_per_s": round(T / best[ncores], 1)}
+        if not args.no_verify:
+            got = lay.numpy()
+            ok = all(np.array_equal(got[k], v) for k, v in res["olay"].items())
+            if payload == "bf16":
+                ok = ok and np.array_equal(bf16_to_bits(recv), oy)
+            else:
+                ok = ok and np.array_equal(recv.cpu().numpy(), oq) and np.array_equal(scale.cpu().numpy(), os_)
+            ok = ok and int(oracle.bf16_ulp_distance(bf16_to_bits(out), res["oout"]).max()) <= 1
+            verified = bool(ok)
+
+    r.close()
+    line = {
+        "metric": "dispatch+combine GB/s (one pass of layout+dispatch+proxy+combine per step)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if payload == "bf16" else "fp8_e4m3+bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {T} tokens x hidden {H}, {E} experts top-{K}, {R} simulated ranks, "
+                               f"{cfg.routing} routing, payload {payload}, commands {cmd_mode_name}",
+                   "rows": rows, "proxy_threads": threads, "channels": args.channels,
+                   "ring_entries": args.ring_entries},
+        "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "kernels_ms": {"layout": round(lay_ms, 4), "dispatch": round(disp_ms, 4), "combine": round(comb_ms, 4)},
+        "kernels_gbs": {"dispatch": round(disp_bytes / disp_ms / 1e6, 1), "combine": round(comb_bytes / comb_ms / 1e6, 1)},
+        "ring": {"cmds_per_step": st["cmds"] / max(1, args.steps), "gpu_ring_full": st["gpu_ring_full"],
+                 "atomics_deferred": st["atomics_deferred"]},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "verified_vs_oracle": verified,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -44,6 +44,11 @@ inline uint64_t mix64(uint64_t &state) {
   return z ^ (z >> 31);
 }
 
+// Statistics counters have one writer (the owning proxy thread): a plain add, no locked instruction.
+inline void bump(std::atomic<uint64_t> &a, uint64_t v = 1) {
+  a.store(a.load(std::memory_order_relaxed) + v, std::memory_order_relaxed);
+}
+
 // What travels from the sender half to the receiver half: the 32-bit immediate
 // (Section 3.3) plus what the receiver knows from the connection it arrived on.
 //   Write : [31]=0 [30:19] local expert [18:13] rows-1 [12:0] low bits of dst_off/16
@@ -124,7 +129,7 @@ void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_
   __atomic_store_n(&h->recv_count[key], value, __ATOMIC_RELEASE);
   log_event(h, P, 3, src, e, (uint32_t)value);
   P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
-  P.applied.fetch_add(1, std::memory_order_release);
+  P.applied.store(P.applied.load(std::memory_order_relaxed) + 1, std::memory_order_release);
 }
 
 // Receiver half: interpret one immediate.  Writes have already landed; they
@@ -154,7 +159,7 @@ void deliver(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
       apply_atomic(h, P, ev.src, e, value);
     } else {
       q.push_back(value);
-      P.deferred.fetch_add(1, std::memory_order_relaxed);
+      bump(P.deferred, 1);
     }
   }
 }
@@ -190,7 +195,7 @@ void flush_window(ep_handle *h, ProxyThread &P) {
 }
 
 void reject(ep_handle *h, ProxyThread &P) {
-  P.rejected.fetch_add(1, std::memory_order_relaxed);
+  bump(P.rejected, 1);
   int zero = 0;
   h->proxy_error.compare_exchange_strong(zero, EP_EBOUNDS);
 }
@@ -201,7 +206,7 @@ void reject(ep_handle *h, ProxyThread &P) {
 void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) {
   const ep_config &c = h->cfg;
   const uint32_t op = (w0 >> 28) & 7u, src = (w0 >> 20) & 0xFFu, dr = (w0 >> 12) & 0xFFu, le = w0 & 0xFFFu;
-  P.cmds.fetch_add(1, std::memory_order_relaxed);
+  bump(P.cmds, 1);
   if (P.first_poll_ns.load(std::memory_order_relaxed) == 0)
     P.first_poll_ns.store(now_ns(), std::memory_order_relaxed);
   if (c.flags & EP_FLAG_LOG_CMDS) {
@@ -218,9 +223,9 @@ void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_
         reject(h, P);
         return;
       }
-      P.writes.fetch_add(1, std::memory_order_relaxed);
-      P.write_bytes.fetch_add(len, std::memory_order_relaxed);
-      P.write_rows.fetch_add(rows, std::memory_order_relaxed);
+      bump(P.writes, 1);
+      bump(P.write_bytes, len);
+      bump(P.write_rows, rows);
       // The payload already sits in the destination partition (the kernel stored it);
       // what remains of the peer write is its arrival notice.
       transmit(h, P, WireEvent{(le << 19) | ((rows - 1) << 13) | (uint32_t)((dof >> 4) & 0x1FFFu), (uint16_t)src,
@@ -234,13 +239,13 @@ void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_
         reject(h, P);
         return;
       }
-      P.atomics.fetch_add(1, std::memory_order_relaxed);
+      bump(P.atomics, 1);
       transmit(h, P, WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint16_t)dr});
       break;
     }
     case EP_OP_DRAIN:
       // everything this thread handed to the transport must have completed
-      P.drains.fetch_add(1, std::memory_order_relaxed);
+      bump(P.drains, 1);
       flush_window(h, P);
       break;
     default:  // Barrier needs peer processes; not part of this single-GPU build
