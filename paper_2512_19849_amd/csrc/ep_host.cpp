@@ -209,10 +209,11 @@ void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_
   bump(P.cmds, 1);
   if (P.first_poll_ns.load(std::memory_order_relaxed) == 0)
     P.first_poll_ns.store(now_ns(), std::memory_order_relaxed);
-  if (c.flags & EP_FLAG_LOG_CMDS) {
+  if (c.flags & EP_FLAG_LOG_CMDS) {  // as polled, lap-parity bits included
     std::lock_guard<std::mutex> g(P.log_mu);
     P.cmd_log.insert(P.cmd_log.end(), {w0, w1, w2, w3});
   }
+  w3 &= 0x7FFFFFFFu;
   switch (op) {
     case EP_OP_WRITE: {
       const uint64_t len = (uint64_t)(w1 & 0x3FFFFFFu) << 4;
@@ -273,7 +274,7 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
         const uint32_t gen = (((uint32_t)(hd >> h->log2_entries)) & 1u) ^ 1u;
         const uint32_t w0 = (uint32_t)lo, w3 = (uint32_t)(hi >> 32);
         if ((w0 >> 31) != gen || (w3 >> 31) != gen) break;
-        process_cmd(h, P, w0 & 0x7FFFFFFFu, (uint32_t)(lo >> 32), (uint32_t)hi, w3 & 0x7FFFFFFFu);
+        process_cmd(h, P, w0, (uint32_t)(lo >> 32), (uint32_t)hi, w3);
         ++hd;
         ++n;
       }
@@ -407,7 +408,7 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
   if (!rc && !h->host_only) {
     h->ntiles_cap = (cfg->max_tokens + kLayoutTile - 1) / kLayoutTile;
     h->chunks_per_expert = (cfg->max_tokens + kChunkRows - 1) / kChunkRows;
-    const size_t hist = (size_t)S * h->ntiles_cap * E * 4;
+    const size_t hist = ((size_t)S * h->ntiles_cap + 1) * E * 4;
     rc = dev_alloc_zero(&h->ring.tail, (size_t)C * 8);
     if (!rc) rc = dev_alloc_zero(&h->ring.cached_head, (size_t)C * 8);
     if (!rc) rc = dev_alloc_zero(&h->ring.stalls, 8);

@@ -15,7 +15,6 @@ constexpr int kChunkRows = 32;  // rows per Write in EP_CMD_CHUNK32 (Section 3.3
 constexpr int kMaxChannels = 64;
 constexpr int kMaxThreads = 16;
 constexpr int kLayoutTile = 64;        // tokens per layout tile = one wavefront
-constexpr int kLayoutWaves = 4;        // tiles per layout workgroup
 constexpr int kMaxExperts = 1024;
 
 // TransferCmd fields (layout documented in include/ep.h).
@@ -44,8 +43,8 @@ struct RingDev {
 struct LayoutArgs {
   const int32_t *idx;  // [S,T,K]
   int32_t S, T, K, E, R, E_loc, ntiles;
-  int32_t *tile_hist;  // scratch [S, ntiles, E]: tile histograms
-  int32_t *tile_base;  // scratch [S, ntiles, E]: exclusive scan over the tiles of one source
+  int32_t *tile_hist;  // scratch [S*ntiles][E]: histogram of every 64-token tile
+  int32_t *tile_base;  // scratch [S*ntiles + 1][E]: exclusive scan over flat tiles, last row = totals
   unsigned *ticket;    // scratch: workgroups finished (self-resetting)
   int32_t *count, *expert_total, *rank_total, *base, *expert_offset, *rank_offset;
   int32_t *slot, *dst_row;

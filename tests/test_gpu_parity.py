@@ -404,3 +404,99 @@ def test_device_side_bounds_check_reports_instead_of_faulting(epmod, oracle):
         assert r.stats()["device_error"] == epmod.EP_EBOUNDS
         with pytest.raises(epmod.EPError):
             r.wait()
+
+
+# ------------------------------------------- full sizes, bench launch configuration
+@pytest.mark.parametrize("cid,payload,mode,threads", [(4, "bf16", "chunk32", 4), (4, "bf16", "per_token", 4),
+                                                      (5, "bf16", "chunk32", 4), (5, "fp8", "chunk32", 1),
+                                                      (5, "fp8", "per_token", 4)])
+def test_full_size_round_trip(epmod, oracle, cid, payload, mode, threads):
+    """The whole path at the workload's full size, element by element, with the
+    launch configuration bench.py times (8 channels x 4096 slots)."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    cfg = g.config(cid, S=1)
+    idx, w = g.routing_all(cfg)
+    x = g.activations(cfg)
+    rows = idx.size
+    oracle.set_threads(min(16, oracle.max_threads()))
+    try:
+        want = oracle.layout(idx, cfg.E, cfg.R)
+        with EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, cfg.T, num_proxy_threads=threads, spin_timeout_ms=10000) as r:
+            d_idx, d_x, d_w = _dev(idx), bits_to_bf16(x), _dev(w[0])
+            lay = r.layout(d_idx)
+            out = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+            if payload == "bf16":
+                recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+                r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=epmod.CMD_MODES[mode])
+                y_dev = recv
+            else:
+                rq = torch.zeros((rows, cfg.H), dtype=torch.uint8, device="cuda")
+                rs = torch.zeros((rows, cfg.H // 128), dtype=torch.float32, device="cuda")
+                r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=epmod.EP_FP8_E4M3, cmd_mode=epmod.CMD_MODES[mode])
+                y_bits = g.activations(cfg, 0, tid=g.TID_Y, T=rows)
+                y_dev = bits_to_bf16(y_bits)
+            r.combine(y_dev, d_w, lay.dst_row[0], out)
+            r.wait()
+            torch.cuda.synchronize()
+            got = lay.numpy()
+            for name, v in want.items():
+                assert np.array_equal(got[name], v), name
+            if payload == "bf16":
+                wrecv, wc = oracle.dispatch_bf16(x, idx[0], want["dst_row"][0], cfg.E_loc, rows)
+                assert np.array_equal(bf16_to_bits(recv), wrecv)
+                y_bits = wrecv
+            else:
+                wq, ws, _ = oracle.dispatch_fp8(x, idx[0], want["dst_row"][0], cfg.E_loc, rows)
+                assert np.array_equal(rq.cpu().numpy(), wq)
+                assert np.array_equal(rs.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+            wout = oracle.combine(y_bits, w[0], want["dst_row"][0])
+            assert oracle.bf16_ulp_distance(bf16_to_bits(out), wout).max() <= 1
+            assert np.array_equal(bf16_to_bits(out), wout)
+            st = r.stats()
+            assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+            assert st["atomics_applied"] == cfg.E and st["write_rows"] == rows
+            assert np.array_equal(r.counters()[0], want["count"][0])
+            nchunks = int(np.ceil(want["count"][0] / 32).sum())
+            assert st["writes"] == (rows if mode == "per_token" else nchunks)
+    finally:
+        oracle.set_threads(1)
+
+
+def test_full_size_decode_share_32_sources(epmod, oracle):
+    """Config 2: this rank sends its 128 tokens to all 32 ranks, and receives in
+    its own partition what the routing of all 32 source ranks sends to rank 0."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    cfg = g.config(2)
+    idx, w = g.routing_all(cfg)
+    rows = idx.size
+    want = oracle.layout(idx, cfg.E, cfg.R)
+    xs = [g.activations(cfg, s) for s in range(cfg.S)]
+    with EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, cfg.T, S=cfg.S, spin_timeout_ms=10000,
+                  flags=epmod.EP_FLAG_LOG_EVENTS) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        recv = torch.full((rows, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")
+        r.dispatch(bits_to_bf16(xs[0]), d_idx[0], lay, recv, src=0, cmd_mode=epmod.EP_CMD_PER_TOKEN)   # send share
+        for s in range(1, cfg.S):                                                                        # inbound share
+            r.dispatch(bits_to_bf16(xs[s]), d_idx[s], lay, recv, src=s, rank_filter=0,
+                       cmd_mode=epmod.EP_CMD_PER_TOKEN)
+        out = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        r.combine(recv, _dev(w[0]), lay.dst_row[0], out)
+        r.wait()
+        torch.cuda.synchronize()
+        got = lay.numpy()
+        for name, v in want.items():
+            assert np.array_equal(got[name], v), name
+        wrecv = np.full((rows, cfg.H), 0xBFC0, np.uint16)
+        oracle.dispatch_bf16(xs[0], idx[0], want["dst_row"][0], cfg.E_loc, rows, recv=wrecv)
+        for s in range(1, cfg.S):
+            oracle.dispatch_bf16(xs[s], idx[s], want["dst_row"][s], cfg.E_loc, rows, rank_filter=0, recv=wrecv)
+        assert np.array_equal(bf16_to_bits(recv), wrecv)
+        assert np.array_equal(bf16_to_bits(out), oracle.combine(wrecv, w[0], want["dst_row"][0]))
+        cnt = r.counters()
+        assert np.array_equal(cnt[0], want["count"][0])
+        assert np.array_equal(cnt[1:, :cfg.E_loc], want["count"][1:, :cfg.E_loc])       # rank 0's experts
+        assert (cnt[1:, cfg.E_loc:] == 0).all()
+        oracle.check_fence_trace(epmod.ep_event_log(r.h), want["count"])
+        st = r.stats()
+        assert st["atomics_applied"] == cfg.E + (cfg.S - 1) * cfg.E_loc

@@ -1,0 +1,296 @@
+"""Host logic of libep.so without a GPU: the library loads and exports what the
+header declares, and the ring + proxy (Poll/Pop, bounds check, immediates,
+completion fence, Drain, back-pressure) behave as Section 3 of the paper
+describes.  The producer is ep_host_push, which speaks the same slot protocol
+as the kernels' device-side Push."""
+import os
+import re
+import threading
+import time
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ep():
+    import paper_2512_19849_amd as ep
+    ep.load_library()
+    return ep
+
+
+def test_library_exports_every_declared_symbol(ep):
+    hdr = open(os.path.join(ROOT, "include", "ep.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(ep_[a-z_]+)\s*\(", hdr))
+    assert {"ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine"} <= names
+    lib = ep.load_library()
+    for n in sorted(names):
+        assert getattr(lib, n) is not None, n
+    assert names == set(ep.EXPORTS)
+
+
+def _w0(op, src, dr, le):
+    return (op << 28) | (src << 20) | (dr << 12) | le
+
+
+def _write(ep, h, ch, src, dr, le, rows, rb, row0):
+    off = row0 * rb
+    return ep.ep_host_push(h, ch, _w0(1, src, dr, le), ((rows - 1) << 26) | ((rows * rb) >> 4), off >> 4, off >> 4)
+
+
+def _atomic(ep, h, ch, src, dr, le, value, E_loc):
+    return ep.ep_host_push(h, ch, _w0(2, src, dr, le), value, 0, src * E_loc + le)
+
+
+def _start(ep, **kw):
+    base = dict(num_ranks=4, num_experts=16, top_k=2, hidden=1024, max_tokens=4096, num_src=2, num_channels=4,
+                ring_entries=64, num_proxy_threads=2, spin_timeout_ms=2000,
+                flags=ep.EP_FLAG_HOST_ONLY | ep.EP_FLAG_LOG_CMDS | ep.EP_FLAG_LOG_EVENTS)
+    base.update(kw)
+    return ep.ep_proxy_start(**base)
+
+
+def test_compute_calls_refuse_a_host_only_handle(ep):
+    h = _start(ep)
+    try:
+        lib = ep.load_library()
+        assert lib.ep_layout(h, None, 0, *([None] * 8), None) == ep.EP_ESTATE
+        assert lib.ep_combine(h, None, None, None, 0, 0, None, None) == ep.EP_ESTATE
+        assert lib.ep_dispatch(h, None, None, None, None, None, 0, 0, -1, 0, 2, None, None, 0, None) == ep.EP_ESTATE
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+@pytest.mark.parametrize("window", [0, 4, 64])
+@pytest.mark.parametrize("atomics_first", [False, True])
+def test_completion_fence_under_reordering(ep, oracle, window, atomics_first):
+    E, R, E_loc, C, rb = 16, 4, 4, 4, 2048
+    rng = np.random.default_rng(window * 2 + atomics_first)
+    count = rng.integers(0, 40, size=(2, E)).astype(np.int32)
+    count[0, 3] = 0
+    h = _start(ep, reorder_window=window, reorder_seed=11)
+    try:
+        ep.ep_host_expect_atomics(h, 2 * E)
+        row = 0
+        jobs = []
+        for s in range(2):
+            for e in range(E):
+                dr, le = e // E_loc, e % E_loc
+                ws = []
+                left = int(count[s, e])
+                while left:
+                    n = min(32, left, int(rng.integers(1, 33)))
+                    ws.append(("w", s, dr, le, n, row))
+                    row += n
+                    left -= n
+                a = [("a", s, dr, le, int(count[s, e]))]
+                jobs.append((a + ws) if atomics_first else (ws + a))
+        order = rng.permutation(len(jobs))
+        for j in order:                                         # per (src, expert) order kept, experts interleaved
+            for item in jobs[j]:
+                ch = item[2] % C
+                if item[0] == "w":
+                    _write(ep, h, ch, item[1], item[2], item[3], item[4], rb, item[5])
+                else:
+                    _atomic(ep, h, ch, item[1], item[2], item[3], item[4], E_loc)
+        ep.ep_wait(h)
+        st = ep.ep_stats(h)
+        assert st["rejected"] == 0 and st["proxy_error"] == 0
+        assert st["atomics_applied"] == 2 * E and st["write_rows"] == int(count.sum())
+        assert np.array_equal(ep.ep_counters(h, 2, E), count)
+        res = oracle.check_fence_trace(ep.ep_event_log(h), count)
+        assert res["applied"] == 2 * E and res["waited"] == st["atomics_deferred"]
+        if atomics_first and window == 0:
+            assert res["waited"] == int((count > 0).sum())      # every non-empty expert's atomic had to wait
+        if not atomics_first and window == 0:
+            assert res["waited"] == 0                           # in-order delivery: never early
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_fifo_order_wraparound_and_backpressure(ep, oracle):
+    """10 000 commands through 8-slot rings: nothing lost or overwritten, order
+    inside a channel is the push order, Idx is the sequence number, and the
+    producer has to wait for the consumer (stall count > 0)."""
+    C, n = 2, 5000
+    h = _start(ep, num_channels=C, ring_entries=8, num_proxy_threads=2, num_src=1)
+    try:
+        for i in range(n):
+            for ch in range(C):
+                idx = ep.ep_host_push(h, ch, _w0(1, 0, ch, 0), (0 << 26) | (2048 >> 4), i, (i % 1000) * 128)
+                assert idx == i
+        for ch in range(C):
+            deadline = time.time() + 5
+            while not ep.ep_host_check_completion(h, ch, n - 1):
+                assert time.time() < deadline
+                time.sleep(0.001)
+            assert ep.ep_host_check_completion(h, ch, 0) and not ep.ep_host_check_completion(h, ch, n)
+        log = ep.ep_cmd_log(h)
+        assert len(log) == C * n
+        for ch in range(C):
+            mine = log[((log[:, 0] >> 12) & 0xFF) == ch]
+            assert np.array_equal(mine[:, 2], np.arange(n, dtype=np.uint32))      # w2 carried the push index
+            gens = (mine[:, 0] >> 31).astype(np.int64)
+            assert np.array_equal(gens, ((np.arange(n) // 8) & 1) ^ 1)              # lap parity alternates per lap
+            assert np.array_equal(mine[:, 0] >> 31, mine[:, 3] >> 31)
+        st = ep.ep_stats(h)
+        assert st["cmds"] == C * n and st["gpu_ring_full"] > 0 and st["rejected"] == 0
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_concurrent_producers_share_a_channel(ep):
+    h = _start(ep, num_channels=1, ring_entries=16, num_proxy_threads=1, num_src=1)
+    try:
+        n, nthr = 2000, 4
+        seen = [[] for _ in range(nthr)]
+
+        def work(k):
+            for i in range(n):
+                seen[k].append(ep.ep_host_push(h, 0, _w0(1, 0, 0, k), 2048 >> 4, i, 0))
+        ts = [threading.Thread(target=work, args=(k,)) for k in range(nthr)]
+        [t.start() for t in ts]
+        [t.join() for t in ts]
+        allidx = sorted(i for s in seen for i in s)
+        assert allidx == list(range(n * nthr))                   # every Idx handed out exactly once
+        deadline = time.time() + 5
+        while not ep.ep_host_check_completion(h, 0, n * nthr - 1):
+            assert time.time() < deadline
+            time.sleep(0.001)
+        log = ep.ep_cmd_log(h)
+        assert len(log) == n * nthr
+        for k in range(nthr):                                    # each producer's own commands stay in order
+            mine = log[(log[:, 0] & 0xFFF) == k]
+            assert np.array_equal(mine[:, 2], np.arange(n, dtype=np.uint32))
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_bounds_check_rejects_bad_commands(ep):
+    """Offsets are translated against the registered heap and checked
+    (Section 3.2, "Symmetric memory"); bad field values are rejected too."""
+    heap_rows, H = 100, 1024
+    heap = heap_rows * 2 * H
+    h = _start(ep, heap_rows=heap_rows, num_src=1)
+    try:
+        good = ep.ep_host_push(h, 0, _w0(1, 0, 0, 0), 2048 >> 4, 0, (heap - 2048) >> 4)
+        bad = [
+            (_w0(1, 0, 0, 0), 2048 >> 4, 0, (heap - 2048 + 16) >> 4),     # destination runs past the heap
+            (_w0(1, 0, 0, 0), 2048 >> 4, (heap - 1024) >> 4, 0),          # source runs past the heap
+            (_w0(1, 0, 0, 0), 0, 0, 0),                                   # zero length
+            (_w0(1, 1, 0, 0), 2048 >> 4, 0, 0),                           # source rank 1 of 1
+            (_w0(1, 0, 4, 0), 2048 >> 4, 0, 0),                           # destination rank 4 of 4
+            (_w0(1, 0, 0, 4), 2048 >> 4, 0, 0),                           # local expert 4 of 4
+            (_w0(2, 0, 1, 2), 5, 0, 3),                                   # atomic whose counter index is not src*E_loc+le
+            (_w0(2, 0, 1, 2), 1 << 19, 0, 2),                             # atomic value too large for the immediate
+            (_w0(4, 0, 0, 0), 0, 0, 0),                                   # Barrier: no peers in this build
+        ]
+        for w in bad:
+            ep.ep_host_push(h, 0, *w)
+        last = ep.ep_host_push(h, 0, _w0(1, 0, 0, 0), 2048 >> 4, 0, 0)
+        deadline = time.time() + 5
+        while not ep.ep_host_check_completion(h, 0, last):
+            assert time.time() < deadline
+            time.sleep(0.001)
+        st = ep.ep_stats(h)
+        assert st["rejected"] == len(bad) and st["writes"] == 2 and st["proxy_error"] == ep.EP_EBOUNDS
+        assert good == 0
+        ep.ep_host_expect_atomics(h, 1)
+        with pytest.raises(ep.EPError) as ei:
+            ep.ep_wait(h)
+        assert ei.value.rc == ep.EP_EBOUNDS
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_drain_completes_everything_in_flight(ep, oracle):
+    """With a large reordering window nothing is delivered until the window
+    overflows; a Drain forces every outstanding notice to land before it pops."""
+    E_loc = 4
+    h = _start(ep, reorder_window=1000, num_channels=1, num_proxy_threads=1, num_src=1)
+    try:
+        ep.ep_host_expect_atomics(h, 1)
+        _atomic(ep, h, 0, 0, 2, 1, 5, E_loc)
+        for i in range(5):
+            _write(ep, h, 0, 0, 2, 1, 1, 2048, i)
+        d = ep.ep_host_push(h, 0, _w0(3, 0, 0, 0), 0, 0, 0)
+        deadline = time.time() + 5
+        while not ep.ep_host_check_completion(h, 0, d):
+            assert time.time() < deadline
+            time.sleep(0.0005)
+        st = ep.ep_stats(h)
+        assert st["drains"] == 1 and st["atomics_applied"] == 1
+        ev = ep.ep_event_log(h)
+        assert len(ev) == 5 + 1 + 1
+        count = np.zeros((1, 16), np.int32)
+        count[0, 2 * E_loc + 1] = 5
+        oracle.check_fence_trace(ev, count)
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_full_ring_with_no_consumer_times_out_instead_of_hanging(ep):
+    h = _start(ep, num_proxy_threads=0, num_channels=1, ring_entries=2, spin_timeout_ms=50, num_src=1)
+    try:
+        ep.ep_host_push(h, 0, _w0(1, 0, 0, 0), 2048 >> 4, 0, 0)
+        ep.ep_host_push(h, 0, _w0(1, 0, 0, 0), 2048 >> 4, 0, 0)
+        t0 = time.time()
+        with pytest.raises(ep.EPError) as ei:
+            ep.ep_host_push(h, 0, _w0(1, 0, 0, 0), 2048 >> 4, 0, 0)
+        assert ei.value.rc == ep.EP_ETIMEOUT and time.time() - t0 < 2
+        assert ep.ep_stats(h)["device_error"] == ep.EP_ETIMEOUT
+        with pytest.raises(ep.EPError):
+            ep.ep_wait(h)                                        # sticky
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_wait_times_out_when_an_atomic_never_gets_its_writes(ep):
+    h = _start(ep, spin_timeout_ms=100, num_src=1)
+    try:
+        ep.ep_host_expect_atomics(h, 1)
+        _atomic(ep, h, 1, 0, 1, 0, 3, 4)
+        _write(ep, h, 1, 0, 1, 0, 2, 2048, 0)                    # only 2 of the 3 rows ever arrive
+        _write(ep, h, 1, 0, 1, 1, 32, 2048, 2)                   # rows for another expert must not count
+        with pytest.raises(ep.EPError) as ei:
+            ep.ep_wait(h)
+        assert ei.value.rc == ep.EP_ETIMEOUT
+        assert ep.ep_stats(h)["atomics_applied"] == 0 and ep.ep_counters(h, 1, 16).sum() == 0
+        _write(ep, h, 1, 0, 1, 0, 1, 2048, 40)                   # the missing row
+        ep.ep_wait(h)
+        assert ep.ep_counters(h, 1, 16)[0, 4] == 3
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_config_validation(ep):
+    ok = dict(num_ranks=4, num_experts=16, top_k=2, hidden=1024, max_tokens=64, flags=ep.EP_FLAG_HOST_ONLY)
+    for bad in (dict(num_ranks=0), dict(num_experts=18), dict(num_experts=2048, num_ranks=1), dict(top_k=0),
+                dict(hidden=100), dict(max_tokens=0), dict(max_tokens=1 << 19), dict(ring_entries=48),
+                dict(ring_entries=1), dict(num_channels=0), dict(num_channels=65), dict(num_proxy_threads=17),
+                dict(self_rank=4), dict(num_src=0), dict(heap_rows=1 << 40)):
+        with pytest.raises(ep.EPError) as ei:
+            ep.ep_proxy_start(**{**ok, **bad})
+        assert ei.value.rc == ep.EP_EINVAL, bad
+    h = ep.ep_proxy_start(**ok)
+    ep.ep_proxy_stop(h)
+
+
+def test_reset_stats_and_repeat(ep):
+    h = _start(ep, num_src=1)
+    try:
+        for rep in range(3):
+            ep.ep_host_expect_atomics(h, 1)
+            _write(ep, h, 0, 0, 0, 1, 7, 2048, 0)
+            _atomic(ep, h, 0, 0, 0, 1, 7, 4)
+            ep.ep_wait(h)
+            st = ep.ep_stats(h)
+            assert st["cmds"] == 2 and st["write_rows"] == 7 and st["first_poll_ns"] <= st["last_apply_ns"]
+            assert ep.ep_counters(h, 1, 16)[0, 1] == 7
+            ep.ep_reset_stats(h)
+            assert ep.ep_stats(h)["cmds"] == 0 and ep.ep_counters(h, 1, 16).sum() == 0
+    finally:
+        ep.ep_proxy_stop(h)
