@@ -43,6 +43,8 @@ struct RingDev {
 struct LayoutArgs {
   const int32_t *idx;  // [S,T,K]
   int32_t S, T, K, E, R, E_loc, ntiles;
+  int32_t scan_split;  // threads per expert in the tile scan (set by the launcher)
+  int32_t tiles_per_block;  // wavefronts of a layout workgroup that own a tile (set by the launcher)
   int32_t *tile_hist;  // scratch [S*ntiles][E]: histogram of every 64-token tile
   int32_t *tile_base;  // scratch [S*ntiles + 1][E]: exclusive scan over flat tiles, last row = totals
   unsigned *ticket;    // scratch: workgroups finished (self-resetting)

@@ -103,24 +103,27 @@ EP_DEV int wave_inclusive_scan(int v, int lane) {
   return v;
 }
 
+static int env_int(const char *name, int dflt);
+
 constexpr int kScanBatch = 32;  // flat tiles a scanning thread holds in registers
 
 __global__ __launch_bounds__(1024) void layout_count_kernel(LayoutArgs a) {
   extern __shared__ unsigned long long s_mask[];  // [waves][E]
   __shared__ int s_off[kMaxExperts + 1];
+  __shared__ int s_part[1024];
   __shared__ int s_last;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int W = blockDim.x >> 6;
+  const int W = a.tiles_per_block;  // wavefronts that own a tile; the rest only help with the scan
   const int nblk = max(1, (a.ntiles + W - 1) / W);
   const int s = blockIdx.x / nblk;
-  const int tile = (blockIdx.x % nblk) * W + wave;
+  const int tile = wave < W ? (blockIdx.x % nblk) * W + wave : a.ntiles;
   const int E = a.E, K = a.K;
   const int F = a.S * a.ntiles;  // flat tiles
 
   for (int i = tid; i < W * E; i += blockDim.x) s_mask[i] = 0ull;
   __syncthreads();
 
-  unsigned long long *m = s_mask + (size_t)wave * E;
+  unsigned long long *m = s_mask + (size_t)(wave < W ? wave : 0) * E;
   const int t = tile * kLayoutTile + lane;
   const bool active = tile < a.ntiles && t < a.T;
   const size_t ebase = ((size_t)s * a.T + (active ? t : 0)) * K;
@@ -131,10 +134,23 @@ __global__ __launch_bounds__(1024) void layout_count_kernel(LayoutArgs a) {
     for (int k = 0; k < 8; ++k) ev[k] = (active && k < K) ? a.idx[ebase + k] : -1;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      if (ev[k] >= 0 && ev[k] < E)
-        atomicOr(&m[ev[k]], 1ull << lane);
-      else if (ev[k] != -1)
-        dev_set_error(a.error, EP_EBOUNDS);
+      const int e = ev[k];
+      bool pend = e >= 0 && e < E;
+      if (!pend && e != -1) dev_set_error(a.error, EP_EBOUNDS);
+      // Skewed routing sends most lanes of a wave to the same few experts, and an LDS atomic
+      // serialises lanes that hit one address.  Peel the two most common values first: their
+      // lanes are found with a ballot and one lane writes the whole bit set.
+#pragma unroll
+      for (int round = 0; round < 2; ++round) {
+        const unsigned long long pm = __ballot(pend);
+        if (pm == 0) break;
+        const int leader = __builtin_ctzll(pm);
+        const int e0 = __builtin_amdgcn_readlane(e, leader);
+        const unsigned long long same = __ballot(pend && e == e0);
+        if (lane == leader) m[e0] |= same;
+        pend = pend && e != e0;
+      }
+      if (pend) atomicOr(&m[e], 1ull << lane);
     }
     __syncthreads();
 #pragma unroll
@@ -175,24 +191,55 @@ __global__ __launch_bounds__(1024) void layout_count_kernel(LayoutArgs a) {
   if (!s_last) return;
   if (tid == 0) __hip_atomic_store(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-  for (int e = tid; e < E; e += blockDim.x) {  // P[*][e]: one thread per expert
-    int carry = 0;
-    for (int f0 = 0; f0 < F; f0 += kScanBatch) {
-      int v[kScanBatch];
+  // P[*][e]: scan_split threads per expert, each owning a contiguous range of flat tiles
+  // (thread = part * E + e, so a wavefront reads consecutive experts of one tile row).
+  const int P = a.scan_split;
+  const int len = (F + P - 1) / P;
+  for (int e_base = 0; e_base < E; e_base += blockDim.x / P) {  // one pass unless E * P > workgroup size
+    const int ne = min(E - e_base, (int)blockDim.x / P);
+    const bool mine = tid < P * ne;
+    const int part = mine ? tid / ne : 0;
+    const int e = e_base + (mine ? tid - part * ne : 0);
+    const int lo = min(F, part * len), hi = min(F, lo + len);
+    int v[kScanBatch];
+    int tot = 0;
+    if (mine) {
+      for (int f0 = lo; f0 < hi; f0 += kScanBatch) {
 #pragma unroll
-      for (int j = 0; j < kScanBatch; ++j)
-        v[j] = (f0 + j < F) ? __hip_atomic_load(a.tile_hist + (size_t)(f0 + j) * E + e, __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT)
-                            : 0;
+        for (int j = 0; j < kScanBatch; ++j)
+          v[j] = (f0 + j < hi) ? __hip_atomic_load(a.tile_hist + (size_t)(f0 + j) * E + e, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT)
+                               : 0;
 #pragma unroll
-      for (int j = 0; j < kScanBatch; ++j) {
-        if (f0 + j < F) a.tile_base[(size_t)(f0 + j) * E + e] = carry;
-        carry += v[j];
+        for (int j = 0; j < kScanBatch; ++j) tot += v[j];
+      }
+      s_part[tid] = tot;
+    }
+    __syncthreads();
+    if (mine) {
+      int carry = 0;
+      for (int q = 0; q < part; ++q) carry += s_part[q * ne + (e - e_base)];
+      for (int f0 = lo; f0 < hi; f0 += kScanBatch) {
+        if (hi - lo > kScanBatch) {  // the range did not fit the registers: fetch the batch again
+#pragma unroll
+          for (int j = 0; j < kScanBatch; ++j)
+            v[j] = (f0 + j < hi) ? __hip_atomic_load(a.tile_hist + (size_t)(f0 + j) * E + e, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT)
+                                 : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < kScanBatch; ++j) {
+          if (f0 + j < hi) a.tile_base[(size_t)(f0 + j) * E + e] = carry;
+          carry += v[j];
+        }
+      }
+      if (part == P - 1) {
+        a.tile_base[(size_t)F * E + e] = carry;
+        a.expert_total[e] = carry;
+        s_off[e] = carry;
       }
     }
-    a.tile_base[(size_t)F * E + e] = carry;
-    a.expert_total[e] = carry;
-    s_off[e] = carry;
+    __syncthreads();
   }
   __syncthreads();
   if (wave == 0) {  // exclusive scan over experts: 64 lanes x contiguous runs
@@ -250,13 +297,20 @@ __global__ __launch_bounds__(256) void layout_finish_kernel(LayoutArgs a) {
 
 int launch_layout(const LayoutArgs &a, void *stream) {
   hipStream_t st = (hipStream_t)stream;
-  // wavefronts (tiles) per workgroup: as many as the LDS masks allow, at most 16
-  int W = 16;
-  while (W > 1 && (size_t)W * a.E * sizeof(unsigned long long) > 65536 - 8192) W >>= 1;
+  // Workgroups are 1024 threads so that the last one has many hands for the scan, but only a few
+  // wavefronts of each own a tile: the LDS atomics of one tile then compete with few others.
+  const int kBlock = 1024;
+  int W = env_int("EP_LAYOUT_TPB", 4);
+  if (W != 1 && W != 2 && W != 4 && W != 8 && W != 16) W = 4;
+  while (W > 1 && (size_t)W * a.E * sizeof(unsigned long long) > 65536 - 12288) W >>= 1;
+  LayoutArgs b = a;
+  b.tiles_per_block = W;
+  b.scan_split = 1;  // threads per expert in the scan: a power of two, at most 16, all in one workgroup
+  while (b.scan_split < 16 && b.scan_split * 2 * a.E <= kBlock) b.scan_split *= 2;
   const int nblk = (a.ntiles + W - 1) / W;
   const int grid1 = a.S * (nblk > 0 ? nblk : 1);
   const size_t lds = (size_t)W * a.E * sizeof(unsigned long long);
-  hipLaunchKernelGGL(layout_count_kernel, dim3(grid1), dim3(W * 64), lds, st, a);
+  hipLaunchKernelGGL(layout_count_kernel, dim3(grid1), dim3(kBlock), lds, st, b);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return (int)err;
   const long long n = (long long)a.S * a.T * a.K;
