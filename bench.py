@@ -50,6 +50,116 @@ def read_traffic(kernel_key: str):
     return float(m.group(1)) if m else None
 
 
+def run_suite(args) -> int:
+    """Per-call timings of all five workloads (the measurement table of the design doc): layout, dispatch
+    with the ring off / per-token / chunk32, FP8 where the workload names it, combine, the command
+    rate the proxy sustains with 1 and 4 threads, warm and (small workloads) cold caches."""
+    import numpy as np
+    import torch
+
+    import ep_inputs as g
+    import paper_2512_19849_amd as ep
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16
+
+    ep.load_library(build_if_missing=False)
+    scrub = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+
+    def timed(fn, n=20, warm=3, cold=False, after=None):
+        """Median event-to-event time of one call.  Warm: calls are queued back to back (no host sync
+        in between, so the time is the kernel plus its launch gap, not the idle-start latency).
+        Cold: a 512 MiB fill runs before every call to push the call's data out of the caches."""
+        for _ in range(warm):
+            fn()
+            if after:
+                after()
+        torch.cuda.synchronize()
+        evs = []
+        for _ in range(n):
+            if cold:
+                scrub.fill_(1)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            if after:
+                after()
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        return round(ts[len(ts) // 2], 2)
+
+    out = {}
+    for cid in (1, 2, 3, 4, 5):
+        cfg = g.config(cid)
+        T, H, K, E, R, S = cfg.T, cfg.H, cfg.K, cfg.E, cfg.R, cfg.S
+        idx, w = g.routing_all(cfg)
+        rows = idx.size
+        my_rows = T * K
+        d_idx = torch.from_numpy(idx).cuda()
+        d_w = torch.from_numpy(w[0]).cuda()
+        d_x = bits_to_bf16(g.activations(cfg))
+        recv = torch.zeros((rows, H), dtype=torch.bfloat16, device="cuda")
+        rq = torch.zeros((rows, H), dtype=torch.uint8, device="cuda")
+        rs = torch.zeros((rows, H // 128), dtype=torch.float32, device="cuda")
+        o = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+        db, cb = algorithmic_bytes(T, H, K, my_rows, "bf16")
+        fb, _ = algorithmic_bytes(T, H, K, my_rows, "fp8")
+        res = {"T": T, "H": H, "E": E, "K": K, "R": R, "S": S, "dispatch_bytes": db, "combine_bytes": cb}
+        small = rows * H * 2 < (128 << 20)
+        for threads, chans in (((1, 8), (4, 8), (4, 64)) if cid in (4, 5) else ((4, 8),)):
+            with EPRunner(R, E, K, H, T, S=S, num_proxy_threads=threads, num_channels=chans,
+                          spin_timeout_ms=10000) as r:
+                lay = r.layout(d_idx)
+                key = f"threads{threads}_channels{chans}"
+                rr = {}
+                if threads == 4 and chans == 8:
+                    rr["layout_us"] = timed(lambda: r.layout(d_idx))
+                    rr["dispatch_bf16_ring_off_us"] = timed(
+                        lambda: r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=ep.EP_CMD_NONE))
+                    rr["combine_us"] = timed(lambda: r.combine(recv, d_w, lay.dst_row[0], o))
+                    if small:
+                        rr["layout_cold_us"] = timed(lambda: r.layout(d_idx), cold=True)
+                        rr["dispatch_bf16_ring_off_cold_us"] = timed(
+                            lambda: r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=ep.EP_CMD_NONE), cold=True)
+                        rr["combine_cold_us"] = timed(lambda: r.combine(recv, d_w, lay.dst_row[0], o), cold=True)
+                    if cid in (3, 5):
+                        rr["dispatch_fp8_ring_off_us"] = timed(
+                            lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3,
+                                               cmd_mode=ep.EP_CMD_NONE))
+                for mode in ("per_token", "chunk32"):
+                    cm = ep.CMD_MODES[mode]
+                    rr[f"dispatch_bf16_{mode}_us"] = timed(
+                        lambda: r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=cm), after=r.wait)
+                    # one dispatch, host clock from launch to the last completion counter, and the proxy's own
+                    # first-poll -> last-apply span
+                    e2e, rate = [], []
+                    for _ in range(10):
+                        ep.ep_reset_stats(r.h)
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=cm)
+                        r.wait()
+                        e2e.append((time.perf_counter() - t0) * 1e6)
+                        st = r.stats()
+                        span = (st["last_apply_ns"] - st["first_poll_ns"]) * 1e-9
+                        rate.append(st["cmds"] / span / 1e6 if span > 0 else 0.0)
+                    e2e.sort()
+                    rate.sort()
+                    rr[f"{mode}_cmds"] = st["cmds"]
+                    rr[f"{mode}_launch_to_last_counter_us"] = round(e2e[len(e2e) // 2], 1)
+                    rr[f"{mode}_proxy_Mcmd_per_s"] = round(rate[len(rate) // 2], 2)
+                    if cid in (3, 5):
+                        rr[f"dispatch_fp8_{mode}_us"] = timed(
+                            lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3, cmd_mode=cm),
+                            after=r.wait)
+                res[key] = rr
+        out[cfg.name] = res
+        del recv, rq, rs, d_x, o
+        torch.cuda.empty_cache()
+    print(json.dumps({"suite": out}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,11 +171,17 @@ def main() -> int:
     ap.add_argument("--proxy-threads", type=int, default=4)
     ap.add_argument("--channels", type=int, default=8)
     ap.add_argument("--ring-entries", type=int, default=4096)
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="bracket the three calls with HIP events on every Nth timed step (each event costs ~2-3 us "
+                         "of stream time, so bracketing every step would slow the path being measured)")
     ap.add_argument("--no-verify", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also launch N plain device copies of 1 GiB (counter calibration for rocprofv3 --pmc)")
+    ap.add_argument("--suite", action="store_true", help="per-call timings of all five workloads instead")
     args = ap.parse_args()
+    if args.suite and args.gpus == 1:
+        return run_suite(args)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the other EP ranks are partitions of its HBM); "
               "--gpus must be 1", file=sys.stderr)
@@ -138,11 +254,12 @@ def main() -> int:
     torch.cuda.synchronize()
     if cmd_mode != ep.EP_CMD_NONE:
         ep.ep_reset_stats(r.h)
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    every = max(1, args.event_every)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range((args.steps + every - 1) // every)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        lay = step(events[i])
+        lay = step(events[i // every] if i % every == 0 else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -160,7 +277,8 @@ def main() -> int:
     roofline = {"kernel": f"{dom}_{payload if dom == 'dispatch' else 'bf16'}", "bound": "hbm",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(dom),
-                "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes": dom_bytes}
+                "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes": dom_bytes,
+                "launches_timed": len(events)}
 
     verified = None
     cpu_baseline = None

@@ -105,7 +105,7 @@ typedef struct ep_stats_t {
   uint64_t atomics_applied;
   uint64_t atomics_deferred; /* atomics that had to wait in the control buffer         */
   uint64_t rejected;         /* commands that failed offset translation / bounds check */
-  uint64_t gpu_ring_full;    /* times a GPU push found its channel full                */
+  uint64_t gpu_ring_full;    /* times a GPU push saw "full" in its cached head and re-read the head over PCIe */
   uint64_t first_poll_ns;    /* CLOCK_MONOTONIC of the first command seen since ep_reset_stats */
   uint64_t last_apply_ns;    /* ... and of the last atomic applied                     */
   uint64_t per_thread_cmds[16];
@@ -152,7 +152,7 @@ int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T,
  * are row src_rank of ep_layout's outputs.  Rows not addressed keep their
  * contents.  Unless cmd_mode is EP_CMD_NONE the kernel also pushes the
  * transfer commands of Section 3.1 into the handle's FIFO channels (channel =
- * destination rank mod C): Writes at the granularity cmd_mode selects, after
+ * destination expert mod C): Writes at the granularity cmd_mode selects, after
  * the rows they describe are stored, and per destination expert one Atomic
  * carrying count[e] (also when 0).  A full channel blocks the pushing wave
  * until the proxy pops (bounded by spin_timeout_ms). */

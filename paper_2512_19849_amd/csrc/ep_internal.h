@@ -91,7 +91,7 @@ int launch_combine(const CombineArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
 
 // Tunables (read once from the environment, for sweeps): vectors per lane.
-int tuned_dispatch_vpl(int H);
+int tuned_dispatch_vpl(int H, int T);
 int tuned_combine_vpl(int H);
 
 }  // namespace ep

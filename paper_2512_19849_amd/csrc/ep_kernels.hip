@@ -360,7 +360,7 @@ EP_DEV TokenMeta load_meta(const DispatchArgs &a, int t, int lane) {
 
 EP_DEV void push_count_atomic(const DispatchArgs &a, int e, int value) {
   const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
-  ring_push(a.ring, dr % a.ring.channels, cmd_w0(EP_OP_ATOMIC, a.src, dr, le), (unsigned)value, 0u,
+  ring_push(a.ring, (unsigned)e % a.ring.channels, cmd_w0(EP_OP_ATOMIC, a.src, dr, le), (unsigned)value, 0u,
             (unsigned)(a.src * a.E_loc) + le);
 }
 
@@ -385,7 +385,9 @@ EP_DEV void emit_leading_atomics(const DispatchArgs &a, int lane) {
 EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
   const int e = m.e;
   const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
-  const unsigned ch = dr % a.ring.channels;
+  // Everything for one destination expert goes through one FIFO (and therefore one proxy thread):
+  // in-FIFO order is the only order the channel guarantees (Section 3.1, "GPU-side contention").
+  const unsigned ch = (unsigned)e % a.ring.channels;
   const int c = a.count[e];
   const int mode = a.cmd_mode & EP_CMD_MODE_MASK;
   int finished_rows = 0;
@@ -582,28 +584,52 @@ static int env_int(const char *name, int dflt) {
   return (s && *s) ? atoi(s) : dflt;
 }
 
-static int pick_vpl(int units, const int *cands, int ncand) {
-  // smallest candidate that covers the row with one wavefront, else the largest
-  const int need = (units + 63) / 64;
+// units = 16-byte vectors (bf16) or 16-channel groups (FP8) per row; returns how many of them one
+// lane carries.  The row then takes ceil(units / (64 * result)) waves, at most 16.
+static int split_for(int units, int T, const int *cands, int ncand) {
+  int best = cands[ncand - 1];
   for (int i = 0; i < ncand; ++i)
-    if (cands[i] >= need) return cands[i];
-  return cands[ncand - 1];
+    if (cands[i] * 256 >= units) {
+      best = cands[i];
+      break;
+    }
+  for (int i = ncand - 1; i >= 0; --i) {
+    if (cands[i] >= best) continue;
+    const long long waves_now = (long long)T * ((units + best * 64 - 1) / (best * 64));
+    if (waves_now >= 4096) break;
+    if ((units + cands[i] * 64 - 1) / (cands[i] * 64) > 16) break;
+    best = cands[i];
+  }
+  while ((units + best * 64 - 1) / (best * 64) > 16) {  // very wide rows: stay within 16 waves per token
+    int next = best;
+    for (int i = 0; i < ncand; ++i)
+      if (cands[i] > best) {
+        next = cands[i];
+        break;
+      }
+    if (next == best) break;
+    best = next;
+  }
+  return best;
 }
 
-int tuned_dispatch_vpl(int H) {
+int tuned_dispatch_vpl(int H, int T) {
   static const int c[] = {1, 2, 4, 7, 8, 14, 16};
   const int forced = env_int("EP_DISPATCH_VPL", 0);
   for (int v : c)
     if (v == forced) return v;
-  return pick_vpl(H / 8, c, 7);
+  // About four waves per token stream best (measured in the full path on 7168- and 4096-wide rows:
+  // the command tail of one wave then overlaps the stores of the others); with few tokens the row
+  // is split further until there are about 4096 waves (16 per compute unit).
+  return split_for(H / 8, T, c, 7);
 }
 
-static int tuned_dispatch_fp8_vpl(int H) {
+static int tuned_dispatch_fp8_vpl(int H, int T) {
   static const int c[] = {1, 2, 4};  // more than 4 groups per lane would spill at 128 VGPRs
   const int forced = env_int("EP_DISPATCH_FP8_VPL", 0);
   for (int v : c)
     if (v == forced) return v;
-  return pick_vpl(H / 16, c, 3);
+  return split_for(H / 16, T, c, 3);
 }
 
 int tuned_combine_vpl(int H) {
@@ -612,7 +638,7 @@ int tuned_combine_vpl(int H) {
   for (int v : c)
     if (v == forced) return v;
   (void)H;
-  return 2;
+  return 1;  // one 16-byte column slice per lane: fewest registers, most waves in flight (measured best)
 }
 
 template <int VPL>
@@ -638,7 +664,7 @@ int launch_dispatch(const DispatchArgs &a, int payload, void *stream) {
   // T == 0 with the ring on still launches one (idle) workgroup: it owes the zero-count atomics
   if (a.T <= 0 && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_NONE) return 0;
   if (payload == EP_BF16) {
-    const int vpl = tuned_dispatch_vpl(a.H);
+    const int vpl = tuned_dispatch_vpl(a.H, a.T);
     if ((a.H / 8 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
     switch (vpl) {
       case 1: launch_dispatch_bf16_t<1>(a, st); break;
@@ -650,7 +676,7 @@ int launch_dispatch(const DispatchArgs &a, int payload, void *stream) {
       default: launch_dispatch_bf16_t<16>(a, st); break;
     }
   } else {
-    const int vpl = tuned_dispatch_fp8_vpl(a.H);
+    const int vpl = tuned_dispatch_fp8_vpl(a.H, a.T);
     if ((a.H / 16 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
     switch (vpl) {
       case 1: launch_dispatch_fp8_t<1>(a, st); break;
@@ -773,10 +799,11 @@ static void launch_combine_t(CombineArgs a, hipStream_t st) {
 int launch_combine(const CombineArgs &a, void *stream) {
   hipStream_t st = (hipStream_t)stream;
   if (a.T <= 0) return 0;
+  if ((a.H / 8 + 63) / 64 > 65535) return (int)hipErrorInvalidValue;
   switch (tuned_combine_vpl(a.H)) {
-    case 1: launch_combine_t<1>(a, st); break;
+    case 2: launch_combine_t<2>(a, st); break;
     case 4: launch_combine_t<4>(a, st); break;
-    default: launch_combine_t<2>(a, st); break;
+    default: launch_combine_t<1>(a, st); break;
   }
   return (int)hipGetLastError();
 }
