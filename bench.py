@@ -174,6 +174,9 @@ def main() -> int:
     ap.add_argument("--event-every", type=int, default=4,
                     help="bracket the three calls with HIP events on every Nth timed step (each event costs ~2-3 us "
                          "of stream time, so bracketing every step would slow the path being measured)")
+    ap.add_argument("--gpu-wait", action="store_true",
+                    help="put ep_recv_wait between dispatch and combine: the combine kernel starts only after the "
+                         "proxy's completion counters reached the GPU (the GPU->CPU->GPU loop of the paper)")
     ap.add_argument("--no-verify", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0,
@@ -235,6 +238,8 @@ def main() -> int:
         r.dispatch(d_x, d_idx[0], lay, recv, scale, payload=pl, cmd_mode=cmd_mode)
         if ev:
             ev[2].record()
+        if args.gpu_wait and cmd_mode != ep.EP_CMD_NONE:
+            r.recv_wait(None)
         r.combine(y, d_w, lay.dst_row[0], out)
         if ev:
             ev[3].record()
@@ -327,7 +332,7 @@ def main() -> int:
         "dtype": "bf16" if payload == "bf16" else "fp8_e4m3+bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {T} tokens x hidden {H}, {E} experts top-{K}, {R} simulated ranks, "
                                f"{cfg.routing} routing, payload {payload}, commands {cmd_mode_name}",
-                   "rows": rows, "proxy_threads": threads, "channels": args.channels,
+                   "rows": rows, "proxy_threads": threads, "channels": args.channels, "gpu_wait": args.gpu_wait,
                    "ring_entries": args.ring_entries},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),

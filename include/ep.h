@@ -178,6 +178,19 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w,
  * sticky device/proxy error, or EP_ETIMEOUT after spin_timeout_ms. */
 int ep_wait(ep_handle *h);
 
+/* ep_recv_wait - the receiving side's wait, on the GPU (Section 4.1: the GPU
+ * observes the host-allocated counters and uses them for control decisions).
+ * Enqueues a kernel that blocks `stream` until the proxy has posted the
+ * completion counter of every expert of dst_rank_filter (every expert if -1)
+ * for source src_rank, i.e. until that dispatch's rows are in place and
+ * announced.  The kernel then writes the posted counts to d_counts_out (int32
+ * [E], device, may be NULL; experts outside the filter get -1) and clears the
+ * arrival flags so the next dispatch of that source can be awaited.  One
+ * ep_recv_wait per ep_dispatch of a (source, filter) pair, in stream order.
+ * The wait is bounded by spin_timeout_ms: on expiry the kernel exits and the
+ * sticky device error becomes EP_ETIMEOUT. */
+int ep_recv_wait(ep_handle *h, int32_t src_rank, int32_t dst_rank_filter, int32_t *d_counts_out, void *stream);
+
 /* ep_counters - *recv_count points at the pinned-host completion counters,
  * int32 [S, E] ([source][global expert]), written by the proxy when it applies
  * an Atomic (Section 4.1: host-allocated counters the GPU may also read).

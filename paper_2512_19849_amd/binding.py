@@ -57,7 +57,8 @@ class ep_stats_t(C.Structure):
         return d
 
 
-EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_wait", "ep_counters",
+EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
+           "ep_counters",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error"]
 
@@ -91,6 +92,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_dispatch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp]
     L.ep_combine.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
     L.ep_wait.argtypes = [vp]
+    L.ep_recv_wait.argtypes = [vp, i32, i32, vp, vp]
     L.ep_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     L.ep_stats.argtypes = [vp, C.POINTER(ep_stats_t)]
     L.ep_reset_stats.argtypes = [vp]
@@ -164,6 +166,11 @@ def ep_dispatch(h: int, x, topk_idx, dst_row, count, base, T: int, src_rank: int
 def ep_combine(h: int, y, topk_w, dst_row, T: int, y_rows: int, out, stream=None) -> None:
     _check("ep_combine", load_library().ep_combine(h, _ptr(y), _ptr(topk_w), _ptr(dst_row), T, y_rows, _ptr(out),
                                                    _stream(stream)))
+
+
+def ep_recv_wait(h: int, src_rank: int, dst_rank_filter: int, counts_out, stream=None) -> None:
+    _check("ep_recv_wait", load_library().ep_recv_wait(h, src_rank, dst_rank_filter, _ptr(counts_out),
+                                                       _stream(stream)))
 
 
 def ep_wait(h: int) -> None:

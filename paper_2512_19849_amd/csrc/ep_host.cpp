@@ -91,6 +91,8 @@ struct ep_handle {
   uint64_t *slots = nullptr;  // 2 x uint64 per command
   uint64_t *head = nullptr;   // [C * kHeadStride]
   int32_t *recv_count = nullptr;
+  int *recv_flag = nullptr;  // posted count + 1, cleared by the GPU-side wait
+  void *d_recv_flag = nullptr;
   int *dev_error = nullptr;
   void *d_recv_count = nullptr;
   // device state
@@ -127,6 +129,7 @@ void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_
   P.seen[key] -= value;
   // completion counter in pinned host memory, visible to the GPU (Section 4.1)
   __atomic_store_n(&h->recv_count[key], value, __ATOMIC_RELEASE);
+  __atomic_store_n(&h->recv_flag[key], value + 1, __ATOMIC_RELEASE);
   log_event(h, P, 3, src, e, (uint32_t)value);
   P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
   P.applied.store(P.applied.load(std::memory_order_relaxed) + 1, std::memory_order_release);
@@ -329,11 +332,13 @@ void free_all(ep_handle *h) {
     free(h->slots);
     free(h->head);
     free(h->recv_count);
+    free(h->recv_flag);
     free(h->dev_error);
   } else {
     if (h->slots) (void)hipHostFree(h->slots);
     if (h->head) (void)hipHostFree(h->head);
     if (h->recv_count) (void)hipHostFree(h->recv_count);
+    if (h->recv_flag) (void)hipHostFree(h->recv_flag);
     if (h->dev_error) (void)hipHostFree(h->dev_error);
     void *dev[] = {h->ring.tail, h->ring.cached_head, h->ring.stalls, h->tile_hist, h->tile_base,
                    h->chunk_cnt, h->expert_done, h->ticket, h->waves_done};
@@ -404,6 +409,7 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
   rc = pinned_alloc(h->host_only, &h->slots, (size_t)C * h->entries * 16);
   if (!rc) rc = pinned_alloc(h->host_only, &h->head, (size_t)C * kHeadStride * 8);
   if (!rc) rc = pinned_alloc(h->host_only, &h->recv_count, (size_t)S * E * 4);
+  if (!rc) rc = pinned_alloc(h->host_only, &h->recv_flag, (size_t)S * E * 4);
   if (!rc) rc = pinned_alloc(h->host_only, &h->dev_error, 64);
   if (!rc && !h->host_only) {
     h->ntiles_cap = (cfg->max_tokens + kLayoutTile - 1) / kLayoutTile;
@@ -426,6 +432,7 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     if (!rc && !HIP_OK(hipHostGetDevicePointer(&dp, h->dev_error, 0))) rc = EP_EHIP;
     h->ring.error = (int *)dp;
     if (!rc && !HIP_OK(hipHostGetDevicePointer(&h->d_recv_count, h->recv_count, 0))) rc = EP_EHIP;
+    if (!rc && !HIP_OK(hipHostGetDevicePointer(&h->d_recv_flag, h->recv_flag, 0))) rc = EP_EHIP;
     h->ring.entries = h->entries;
     h->ring.log2_entries = h->log2_entries;
     h->ring.channels = (unsigned)C;
@@ -589,6 +596,24 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32
   return HIP_OK((hipError_t)launch_combine(a, stream)) ? EP_OK : EP_EHIP;
 }
 
+int ep_recv_wait(ep_handle *h, int32_t src_rank, int32_t dst_rank_filter, int32_t *d_counts_out, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (src_rank < 0 || src_rank >= h->cfg.num_src) return EP_EINVAL;
+  if (dst_rank_filter < -1 || dst_rank_filter >= h->cfg.num_ranks) return EP_EINVAL;
+  if (h->nthreads < 1) return EP_ESTATE;  // nobody would ever post a counter
+  RecvWaitArgs a{};
+  a.flags = (int *)h->d_recv_flag;
+  a.out = d_counts_out;
+  a.E = h->cfg.num_experts;
+  a.E_loc = h->E_loc;
+  a.src = src_rank;
+  a.filter = dst_rank_filter;
+  a.error = h->ring.error;
+  a.timeout_ticks = h->ring.timeout_ticks;
+  return HIP_OK((hipError_t)launch_recv_wait(a, stream)) ? EP_OK : EP_EHIP;
+}
+
 int ep_wait(ep_handle *h) {
   if (!h) return EP_EINVAL;
   const uint64_t t0 = now_ns();
@@ -663,6 +688,7 @@ int ep_reset_stats(ep_handle *h) {
   }
   h->expected_atomics.store(0);
   memset(h->recv_count, 0, (size_t)h->cfg.num_src * h->cfg.num_experts * 4);
+  memset(h->recv_flag, 0, (size_t)h->cfg.num_src * h->cfg.num_experts * 4);
   if (h->host_only) {
     h->host_stalls.store(0);
   } else if (!HIP_OK(hipMemset(h->ring.stalls, 0, 8))) {

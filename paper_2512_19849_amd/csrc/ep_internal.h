@@ -84,10 +84,19 @@ struct CombineArgs {
   int *error;
 };
 
+struct RecvWaitArgs {
+  int *flags;        // pinned host [S*E]: 0 = not arrived, else posted count + 1 (written by the proxy)
+  int32_t *out;      // device [E] or null
+  int32_t E, E_loc, src, filter;
+  int *error;
+  unsigned long long timeout_ticks;
+};
+
 // Launchers implemented in ep_kernels.hip.  All return a hipError_t as int.
 int launch_layout(const LayoutArgs &a, void *stream);
 int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
 int launch_combine(const CombineArgs &a, void *stream);
+int launch_recv_wait(const RecvWaitArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
 
 // Tunables (read once from the environment, for sweeps): vectors per lane.

@@ -808,6 +808,40 @@ int launch_combine(const CombineArgs &a, void *stream) {
   return (int)hipGetLastError();
 }
 
+// ------------------------------------------------------------ receive wait
+// One thread per expert polls its arrival flag in pinned host memory with
+// system-scope loads (each poll is a PCIe read, so lanes sleep between polls),
+// hands the posted count to the caller and clears the flag.  Every lane leaves
+// the loop: either its flag arrived or the bound expired.
+__global__ __launch_bounds__(1024) void recv_wait_kernel(RecvWaitArgs a) {
+  for (int e = threadIdx.x; e < a.E; e += blockDim.x) {
+    if (a.filter >= 0 && e / a.E_loc != a.filter) {
+      if (a.out) a.out[e] = -1;
+      continue;
+    }
+    int *flag = a.flags + (size_t)a.src * a.E + e;
+    const unsigned long long t0 = wall_clock64();
+    int v;
+    for (;;) {
+      v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (v != 0) break;
+      if (wall_clock64() - t0 > a.timeout_ticks) {
+        dev_set_error(a.error, EP_ETIMEOUT);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(64);
+    }
+    if (v != 0) __hip_atomic_store(flag, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (a.out) a.out[e] = v - 1;
+  }
+}
+
+int launch_recv_wait(const RecvWaitArgs &a, void *stream) {
+  const int threads = a.E < 64 ? 64 : (a.E > 1024 ? 1024 : (a.E + 63) / 64 * 64);
+  hipLaunchKernelGGL(recv_wait_kernel, dim3(1), dim3(threads), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
 // ------------------------------------------------------------------- misc
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, long long n) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;

@@ -500,3 +500,65 @@ def test_full_size_decode_share_32_sources(epmod, oracle):
         oracle.check_fence_trace(epmod.ep_event_log(r.h), want["count"])
         st = r.stats()
         assert st["atomics_applied"] == cfg.E + (cfg.S - 1) * cfg.E_loc
+
+
+# ------------------------------------------------------- GPU-side receive wait
+def test_recv_wait_orders_combine_after_the_counters_on_the_gpu(epmod, oracle):
+    """dispatch -> ep_recv_wait -> combine in one stream, no host wait in between:
+    the wait kernel polls the pinned-host counters the proxy posts, returns the
+    counts and clears the flags; three rounds reuse the same flags."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    cfg = g.config(4, S=1)
+    T = 512
+    idx, w = g.routing_all(cfg, T)
+    x = g.activations(cfg, 0, T=T)
+    want = oracle.layout(idx, cfg.E, cfg.R)
+    wrecv, _ = oracle.dispatch_bf16(x, idx[0], want["dst_row"][0], cfg.E_loc, idx.size)
+    wout = oracle.combine(wrecv, w[0], want["dst_row"][0])
+    with _runner(epmod, cfg, T) as r:
+        d_idx, d_x, d_w = _dev(idx), bits_to_bf16(x), _dev(w[0])
+        for rnd, mode in enumerate((epmod.EP_CMD_PER_TOKEN, epmod.EP_CMD_CHUNK32, epmod.EP_CMD_PER_TOKEN)):
+            lay = r.layout(d_idx)
+            recv = torch.zeros((idx.size, cfg.H), dtype=torch.bfloat16, device="cuda")
+            out = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+            counts = torch.full((cfg.E,), -7, dtype=torch.int32, device="cuda")
+            r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=mode)
+            r.recv_wait(counts)
+            r.combine(recv, d_w, lay.dst_row[0], out)
+            torch.cuda.synchronize()
+            assert np.array_equal(counts.cpu().numpy(), want["count"][0])
+            assert np.array_equal(bf16_to_bits(out), wout)
+            r.wait()                                             # already satisfied
+            assert r.stats()["device_error"] == 0
+
+
+def test_recv_wait_with_rank_filter_and_other_source(epmod, oracle):
+    from paper_2512_19849_amd.runner import bits_to_bf16
+    cfg = g.config(2)
+    idx, _ = g.routing_all(cfg, 64)
+    want = oracle.layout(idx, cfg.E, cfg.R)
+    x = g.activations(cfg, 5, T=64)
+    with _runner(epmod, cfg, 64) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        recv = torch.zeros((idx.size, cfg.H), dtype=torch.bfloat16, device="cuda")
+        counts = torch.full((cfg.E,), -7, dtype=torch.int32, device="cuda")
+        r.dispatch(bits_to_bf16(x), d_idx[5], lay, recv, src=5, rank_filter=3, cmd_mode=epmod.EP_CMD_PER_TOKEN)
+        r.recv_wait(counts, src=5, rank_filter=3)
+        torch.cuda.synchronize()
+        got = counts.cpu().numpy()
+        lo, hi = 3 * cfg.E_loc, 4 * cfg.E_loc
+        assert np.array_equal(got[lo:hi], want["count"][5, lo:hi])
+        assert (got[:lo] == -1).all() and (got[hi:] == -1).all()
+
+
+def test_recv_wait_times_out_when_nothing_was_dispatched(epmod):
+    """No dispatch, so no counter is ever posted: the host never satisfies the
+    kernel's bounded wait, which expires, reports EP_ETIMEOUT and exits."""
+    cfg = g.config(1)
+    with _runner(epmod, cfg, spin_timeout_ms=100) as r:
+        counts = torch.zeros((cfg.E,), dtype=torch.int32, device="cuda")
+        r.recv_wait(counts)
+        torch.cuda.synchronize()
+        assert r.stats()["device_error"] == epmod.EP_ETIMEOUT
+        assert (counts.cpu().numpy() == -1).all()
