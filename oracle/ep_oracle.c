@@ -304,3 +304,81 @@ int oracle_combine_f64(const uint16_t *y, const float *w, const int32_t *dst_row
     }
   return bad ? -2 : 0;
 }
+
+/* ------------------------------------------ high-throughput mode additions
+ * Section 2.2 describes two optimisations of the high-throughput mode: a token
+ * routed to several experts of one node is sent once and forwarded inside the
+ * node ("message deduplication"), and expert outputs are first reduced inside
+ * the node (weighted sum) and then once more at the sender ("hierarchical
+ * reduce").  A "group" below is ranks_per_group consecutive ranks (1 = one GPU,
+ * 8 = a node of eight).
+ *
+ * Dedup: group(e) = (e / E_loc) / ranks_per_group.  For every token, walking k
+ * ascending: the first entry that names a group keeps it (group_idx = group),
+ * later entries of the same group are duplicates (group_idx = -1); first_k is
+ * the k of that first entry (-1 for masked entries).  group_idx is then a
+ * routing table over groups that the ordinary layout/dispatch steps consume:
+ * one copy per (token, group).
+ */
+int oracle_dedup(const int32_t *idx, long n_tokens, int K, int E_loc, int ranks_per_group,
+                 int32_t *group_idx, int32_t *first_k) {
+  for (long t = 0; t < n_tokens; ++t)
+    for (int k = 0; k < K; ++k) {
+      int e = idx[t * K + k];
+      if (e < 0) { group_idx[t * K + k] = -1; first_k[t * K + k] = -1; continue; }
+      int g = (e / E_loc) / ranks_per_group;
+      int first = k;
+      for (int j = 0; j < k; ++j) {
+        int ej = idx[t * K + j];
+        if (ej >= 0 && (ej / E_loc) / ranks_per_group == g) { first = j; break; }
+      }
+      group_idx[t * K + k] = (first == k) ? g : -1;
+      first_k[t * K + k] = first;
+    }
+  return 0;
+}
+
+/* Per-expert index list: expert-major row i of the ordinary layout reads its
+ * input from row index[i] of the deduplicated receive buffer. */
+int oracle_gather_index(const int32_t *dst_row, const int32_t *dst_row_g, const int32_t *first_k,
+                        long T, int K, long rows, int32_t *index) {
+  for (long i = 0; i < rows; ++i) index[i] = -1;
+  for (long t = 0; t < T; ++t)
+    for (int k = 0; k < K; ++k) {
+      long r = dst_row[t * K + k];
+      if (r < 0) continue;
+      if (r >= rows) return -2;
+      index[r] = dst_row_g[t * K + first_k[t * K + k]];
+    }
+  return 0;
+}
+
+/* Hierarchical reduce, first level (done where the experts live): one partial
+ * row per (token, group),
+ *   partial[dst_row_g[t,j], h] = bf16( sum_{k : first_k[t,k] == j} w[t,k] * y[dst_row[t,k], h] )
+ * fp32 accumulator from +0, k ascending, fused multiply-add, one rounding to
+ * bf16 (the partial travels as bf16).  The second level is the ordinary
+ * combine over the group rows with unit weights. */
+int oracle_combine_partial(const uint16_t *y, const float *w, const int32_t *dst_row, const int32_t *first_k,
+                           const int32_t *dst_row_g, int T, int K, int H, long rows, long rows_g,
+                           uint16_t *partial) {
+  int bad = 0;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+  for (int t = 0; t < T; ++t)
+    for (int j = 0; j < K; ++j) {
+      if (first_k[(long)t * K + j] != j) continue; /* not the first entry of its group */
+      long prow = dst_row_g[(long)t * K + j];
+      if (prow < 0 || prow >= rows_g) { bad = 1; continue; }
+      for (int h = 0; h < H; ++h) {
+        float acc = 0.0f;
+        for (int k = 0; k < K; ++k) {
+          if (first_k[(long)t * K + k] != j) continue;
+          long row = dst_row[(long)t * K + k];
+          if (row < 0 || row >= rows) { bad = 1; continue; }
+          acc = fmaf(w[(long)t * K + k], bf16_to_f32(y[row * H + h]), acc);
+        }
+        partial[prow * H + h] = f32_to_bf16_rne(acc);
+      }
+    }
+  return bad ? -2 : 0;
+}

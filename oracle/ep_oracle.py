@@ -69,6 +69,13 @@ def _load():
         L.oracle_f32_to_bf16.restype = C.c_uint16
         L.oracle_bf16_to_f32.argtypes = [C.c_uint16]
         L.oracle_bf16_to_f32.restype = C.c_float
+        L.oracle_dedup.argtypes = [i32p, C.c_long, C.c_int, C.c_int, C.c_int, i32p, i32p]
+        L.oracle_dedup.restype = C.c_int
+        L.oracle_gather_index.argtypes = [i32p, i32p, i32p, C.c_long, C.c_int, C.c_long, i32p]
+        L.oracle_gather_index.restype = C.c_int
+        L.oracle_combine_partial.argtypes = [u16p, f32p, i32p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_long,
+                                             C.c_long, u16p]
+        L.oracle_combine_partial.restype = C.c_int
         L.oracle_set_threads.argtypes = [C.c_int]
         L.oracle_max_threads.restype = C.c_int
         L.oracle_get_threads.restype = C.c_int
@@ -218,6 +225,43 @@ def combine_f64(y, w, dst_row) -> Tuple[np.ndarray, np.ndarray]:
     if rc != 0:
         raise ValueError("oracle_combine_f64: row out of range")
     return out, mag
+
+
+# ------------------------------------------------ high-throughput mode
+def dedup(idx: np.ndarray, E_loc: int, ranks_per_group: int) -> Tuple[np.ndarray, np.ndarray]:
+    """idx int32 [..., K] -> (group_idx, first_k), same shape (see ep_oracle.c)."""
+    idx = _c(idx, np.int32)
+    K = idx.shape[-1]
+    g = np.zeros_like(idx)
+    f = np.zeros_like(idx)
+    _load().oracle_dedup(_p(idx, C.c_int32), idx.size // K, K, E_loc, ranks_per_group, _p(g, C.c_int32),
+                         _p(f, C.c_int32))
+    return g, f
+
+
+def gather_index(dst_row, dst_row_g, first_k, rows: int) -> np.ndarray:
+    dst_row = _c(dst_row, np.int32); dst_row_g = _c(dst_row_g, np.int32); first_k = _c(first_k, np.int32)
+    T, K = dst_row.shape
+    out = np.zeros(rows, np.int32)
+    rc = _load().oracle_gather_index(_p(dst_row, C.c_int32), _p(dst_row_g, C.c_int32), _p(first_k, C.c_int32), T, K,
+                                     rows, _p(out, C.c_int32))
+    if rc != 0:
+        raise ValueError("oracle_gather_index: row out of range")
+    return out
+
+
+def combine_partial(y, w, dst_row, first_k, dst_row_g, rows_g: int, fill: int = 0) -> np.ndarray:
+    y = _c(y, np.uint16); w = _c(w, np.float32)
+    dst_row = _c(dst_row, np.int32); first_k = _c(first_k, np.int32); dst_row_g = _c(dst_row_g, np.int32)
+    rows, H = y.shape
+    T, K = dst_row.shape
+    partial = np.full((rows_g, H), fill, np.uint16)
+    rc = _load().oracle_combine_partial(_p(y, C.c_uint16), _p(w, C.c_float), _p(dst_row, C.c_int32),
+                                        _p(first_k, C.c_int32), _p(dst_row_g, C.c_int32), T, K, H, rows, rows_g,
+                                        _p(partial, C.c_uint16))
+    if rc != 0:
+        raise ValueError("oracle_combine_partial: row out of range")
+    return partial
 
 
 def f32_to_bf16(a: np.ndarray) -> np.ndarray:
