@@ -178,6 +178,39 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w,
  * sticky device/proxy error, or EP_ETIMEOUT after spin_timeout_ms. */
 int ep_wait(ep_handle *h);
 
+/* ---- high-throughput mode (Section 2.2: message deduplication and hierarchical reduce) ----
+ * A "group" is ranks_per_group consecutive ranks (1 = a GPU, 8 = a node of eight).
+ *
+ * ep_dedup - a token routed to several experts of one group travels once:
+ *   group(e) = (e / (E/R)) / ranks_per_group; walking k ascending, the first
+ *   entry of a token that names a group keeps it (group_idx[s,t,k] = group),
+ *   later entries of that group are duplicates (group_idx = -1); first_k[s,t,k]
+ *   is the k of that first entry (-1 for masked entries).  d_group_idx is a
+ *   routing table over R/ranks_per_group "experts" that ep_layout / ep_dispatch
+ *   of a second handle (num_ranks = num_experts = R/ranks_per_group, same K, H)
+ *   consume unchanged: one receive row per (token, group).  All int32 [S,T,K]. */
+int ep_dedup(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t ranks_per_group,
+             int32_t *d_group_idx, int32_t *d_first_k, void *stream);
+
+/* ep_gather_index - the per-expert index list: row i of the ordinary
+ * (expert-major) layout reads its input from row d_index[i] of the deduplicated
+ * receive buffer: d_index[dst_row[t,k]] = dst_row_g[t, first_k[t,k]] for every
+ * valid (t,k) of one source.  d_dst_row, d_dst_row_g, d_first_k int32 [T,K];
+ * d_index int32 [rows]; entries no (t,k) addresses keep their contents. */
+int ep_gather_index(ep_handle *h, const int32_t *d_dst_row, const int32_t *d_dst_row_g, const int32_t *d_first_k,
+                    int32_t T, int64_t rows, int32_t *d_index, void *stream);
+
+/* ep_combine_partial - first level of the hierarchical reduce, done where the
+ * experts live: one partial row per (token, group),
+ *   partial[dst_row_g[t,j], :] = bf16( sum_{k : first_k[t,k] == j} w[t,k] * y[dst_row[t,k], :] )
+ * (fp32 accumulator from +0, k ascending, fused multiply-add, one rounding to
+ * bf16: the partial travels as bf16).  The second level is ep_combine over the
+ * partial rows with dst_row_g and unit weights.  d_y bf16 [y_rows,H];
+ * d_partial bf16 [rows_g,H]; the index arrays are int32 [T,K]. */
+int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, const int32_t *d_dst_row,
+                       const int32_t *d_first_k, const int32_t *d_dst_row_g, int32_t T, int64_t y_rows,
+                       int64_t rows_g, void *d_partial, void *stream);
+
 /* ep_recv_wait - the receiving side's wait, on the GPU (Section 4.1: the GPU
  * observes the host-allocated counters and uses them for control decisions).
  * Enqueues a kernel that blocks `stream` until the proxy has posted the

@@ -58,7 +58,7 @@ class ep_stats_t(C.Structure):
 
 
 EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
-           "ep_counters",
+           "ep_counters", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error"]
 
@@ -92,6 +92,9 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_dispatch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp]
     L.ep_combine.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
     L.ep_wait.argtypes = [vp]
+    L.ep_dedup.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    L.ep_gather_index.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
+    L.ep_combine_partial.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, vp, vp]
     L.ep_recv_wait.argtypes = [vp, i32, i32, vp, vp]
     L.ep_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     L.ep_stats.argtypes = [vp, C.POINTER(ep_stats_t)]
@@ -166,6 +169,23 @@ def ep_dispatch(h: int, x, topk_idx, dst_row, count, base, T: int, src_rank: int
 def ep_combine(h: int, y, topk_w, dst_row, T: int, y_rows: int, out, stream=None) -> None:
     _check("ep_combine", load_library().ep_combine(h, _ptr(y), _ptr(topk_w), _ptr(dst_row), T, y_rows, _ptr(out),
                                                    _stream(stream)))
+
+
+def ep_dedup(h: int, topk_idx, T: int, ranks_per_group: int, group_idx, first_k, stream=None) -> None:
+    _check("ep_dedup", load_library().ep_dedup(h, _ptr(topk_idx), T, ranks_per_group, _ptr(group_idx),
+                                               _ptr(first_k), _stream(stream)))
+
+
+def ep_gather_index(h: int, dst_row, dst_row_g, first_k, T: int, rows: int, index, stream=None) -> None:
+    _check("ep_gather_index", load_library().ep_gather_index(h, _ptr(dst_row), _ptr(dst_row_g), _ptr(first_k), T,
+                                                             rows, _ptr(index), _stream(stream)))
+
+
+def ep_combine_partial(h: int, y, topk_w, dst_row, first_k, dst_row_g, T: int, y_rows: int, rows_g: int, partial,
+                       stream=None) -> None:
+    _check("ep_combine_partial", load_library().ep_combine_partial(h, _ptr(y), _ptr(topk_w), _ptr(dst_row),
+                                                                   _ptr(first_k), _ptr(dst_row_g), T, y_rows,
+                                                                   rows_g, _ptr(partial), _stream(stream)))
 
 
 def ep_recv_wait(h: int, src_rank: int, dst_rank_filter: int, counts_out, stream=None) -> None:

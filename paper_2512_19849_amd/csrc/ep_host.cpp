@@ -596,6 +596,70 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32
   return HIP_OK((hipError_t)launch_combine(a, stream)) ? EP_OK : EP_EHIP;
 }
 
+int ep_dedup(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t ranks_per_group, int32_t *d_group_idx,
+             int32_t *d_first_k, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (T < 0 || T > h->cfg.max_tokens) return EP_EINVAL;
+  if (ranks_per_group < 1 || h->cfg.num_ranks % ranks_per_group) return EP_EINVAL;
+  if (T > 0 && (!d_topk_idx || !d_group_idx || !d_first_k)) return EP_EINVAL;
+  DedupArgs a{};
+  a.idx = d_topk_idx;
+  a.group_idx = d_group_idx;
+  a.first_k = d_first_k;
+  a.n_tokens = (long long)h->cfg.num_src * T;
+  a.K = h->cfg.top_k;
+  a.E = h->cfg.num_experts;
+  a.E_loc = h->E_loc;
+  a.ranks_per_group = ranks_per_group;
+  a.error = h->ring.error;
+  return HIP_OK((hipError_t)launch_dedup(a, stream)) ? EP_OK : EP_EHIP;
+}
+
+int ep_gather_index(ep_handle *h, const int32_t *d_dst_row, const int32_t *d_dst_row_g, const int32_t *d_first_k,
+                    int32_t T, int64_t rows, int32_t *d_index, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (T < 0 || T > h->cfg.max_tokens || rows < 0) return EP_EINVAL;
+  if (T > 0 && (!d_dst_row || !d_dst_row_g || !d_first_k || !d_index)) return EP_EINVAL;
+  GatherIndexArgs a{};
+  a.dst_row = d_dst_row;
+  a.dst_row_g = d_dst_row_g;
+  a.first_k = d_first_k;
+  a.index = d_index;
+  a.rows = rows;
+  a.T = T;
+  a.K = h->cfg.top_k;
+  a.error = h->ring.error;
+  return HIP_OK((hipError_t)launch_gather_index(a, stream)) ? EP_OK : EP_EHIP;
+}
+
+int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, const int32_t *d_dst_row,
+                       const int32_t *d_first_k, const int32_t *d_dst_row_g, int32_t T, int64_t y_rows,
+                       int64_t rows_g, void *d_partial, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (T < 0 || T > h->cfg.max_tokens || y_rows < 0 || rows_g < 0) return EP_EINVAL;
+  if (T == 0) return EP_OK;
+  if (!d_topk_w || !d_dst_row || !d_first_k || !d_dst_row_g || (y_rows > 0 && !d_y) || (rows_g > 0 && !d_partial))
+    return EP_EINVAL;
+  if (((uintptr_t)d_y | (uintptr_t)d_partial) & 15) return EP_EINVAL;
+  CombinePartialArgs a{};
+  a.y = d_y;
+  a.w = d_topk_w;
+  a.dst_row = d_dst_row;
+  a.first_k = d_first_k;
+  a.dst_row_g = d_dst_row_g;
+  a.partial = d_partial;
+  a.y_rows = y_rows;
+  a.rows_g = rows_g;
+  a.T = T;
+  a.K = h->cfg.top_k;
+  a.H = h->cfg.hidden;
+  a.error = h->ring.error;
+  return HIP_OK((hipError_t)launch_combine_partial(a, stream)) ? EP_OK : EP_EHIP;
+}
+
 int ep_recv_wait(ep_handle *h, int32_t src_rank, int32_t dst_rank_filter, int32_t *d_counts_out, void *stream) {
   if (!h) return EP_EINVAL;
   if (h->host_only) return EP_ESTATE;

@@ -84,6 +84,32 @@ struct CombineArgs {
   int *error;
 };
 
+struct DedupArgs {
+  const int32_t *idx;  // [n_tokens, K]
+  int32_t *group_idx, *first_k;
+  long long n_tokens;
+  int32_t K, E, E_loc, ranks_per_group;
+  int *error;
+};
+
+struct GatherIndexArgs {
+  const int32_t *dst_row, *dst_row_g, *first_k;  // [T,K]
+  int32_t *index;                                // [rows]
+  long long rows;
+  int32_t T, K;
+  int *error;
+};
+
+struct CombinePartialArgs {
+  const void *y;       // bf16 [y_rows,H]
+  const float *w;      // [T,K]
+  const int32_t *dst_row, *first_k, *dst_row_g;  // [T,K]
+  void *partial;       // bf16 [rows_g,H]
+  long long y_rows, rows_g;
+  int32_t T, K, H, parts;
+  int *error;
+};
+
 struct RecvWaitArgs {
   int *flags;        // pinned host [S*E]: 0 = not arrived, else posted count + 1 (written by the proxy)
   int32_t *out;      // device [E] or null
@@ -97,6 +123,9 @@ int launch_layout(const LayoutArgs &a, void *stream);
 int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
 int launch_combine(const CombineArgs &a, void *stream);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
+int launch_dedup(const DedupArgs &a, void *stream);
+int launch_gather_index(const GatherIndexArgs &a, void *stream);
+int launch_combine_partial(const CombinePartialArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
 
 // Tunables (read once from the environment, for sweeps): vectors per lane.

@@ -562,3 +562,82 @@ def test_recv_wait_times_out_when_nothing_was_dispatched(epmod):
         torch.cuda.synchronize()
         assert r.stats()["device_error"] == epmod.EP_ETIMEOUT
         assert (counts.cpu().numpy() == -1).all()
+
+
+# ------------------------------------------------- high-throughput mode (dedup + hierarchical reduce)
+@pytest.mark.parametrize("cid,G,T,mask", [(1, 1, None, 0.0), (1, 2, 50, 0.3), (2, 8, 128, 0.0), (4, 1, 4096, 0.0),
+                                          (4, 8, 1000, 0.1), (5, 2, 8192, 0.0)])
+def test_ht_dedup_parity(epmod, oracle, cid, G, T, mask):
+    cfg = g.config(cid)
+    idx, _ = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=43)
+    wg, wf = oracle.dedup(idx, cfg.E_loc, G)
+    with _runner(epmod, cfg, idx.shape[1], num_proxy_threads=0) as r:
+        d_idx = _dev(idx)
+        gi = torch.full_like(d_idx, -9)
+        fk = torch.full_like(d_idx, -9)
+        epmod.ep_dedup(r.h, d_idx, idx.shape[1], G, gi, fk)
+        torch.cuda.synchronize()
+        assert np.array_equal(gi.cpu().numpy(), wg) and np.array_equal(fk.cpu().numpy(), wf)
+        assert r.stats()["device_error"] == 0
+
+
+@pytest.mark.parametrize("cid,G,T,mask,mode", [(1, 1, None, 0.0, "per_token"), (1, 2, None, 0.25, "chunk32"),
+                                               (4, 1, 600, 0.0, "chunk32"), (4, 8, 600, 0.1, "chunk32"),
+                                               (5, 4, 500, 0.0, "per_token"), (4, 1, 4096, 0.0, "chunk32")])
+def test_ht_round_trip(epmod, oracle, cid, G, T, mask, mode):
+    """dedup -> group-level layout and dispatch (second handle) -> per-expert index
+    list -> expert outputs -> partial reduce per group -> final reduce."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    cfg = g.config(cid, S=1)
+    idx, w = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=47)
+    T = idx.shape[1]
+    NG = cfg.R // G
+    x = g.activations(cfg, 0, T=T)
+    # oracle side
+    wg, wf = oracle.dedup(idx, cfg.E_loc, G)
+    lay = oracle.layout(idx, cfg.E, cfg.R)
+    lay_g = oracle.layout(wg, NG, NG)
+    rows, rows_g = int((idx >= 0).sum()), int((wg >= 0).sum())
+    wrecv_g, _ = oracle.dispatch_bf16(x, wg[0], lay_g["dst_row"][0], 1, rows_g)
+    windex = oracle.gather_index(lay["dst_row"][0], lay_g["dst_row"][0], wf[0], rows)
+    y = g.activations(cfg, 0, tid=g.TID_Y, T=max(rows, 1))
+    wpartial = oracle.combine_partial(y, w[0], lay["dst_row"][0], wf[0], lay_g["dst_row"][0], rows_g, fill=0x3F80)
+    wout = oracle.combine(wpartial, np.ones_like(w[0]), lay_g["dst_row"][0])
+
+    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    with EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, T, num_proxy_threads=0, spin_timeout_ms=3000) as r, \
+            EPRunner(NG, NG, cfg.K, cfg.H, T, spin_timeout_ms=3000, flags=flags) as rg:
+        d_idx, d_x, d_w = _dev(idx), bits_to_bf16(x), _dev(w[0])
+        gi, fk = torch.empty_like(d_idx), torch.empty_like(d_idx)
+        epmod.ep_dedup(r.h, d_idx, T, G, gi, fk)
+        L = r.layout(d_idx)
+        Lg = rg.layout(gi)
+        recv_g = torch.full((rows_g + 1, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")
+        rg.dispatch(d_x, gi[0], Lg, recv_g, cmd_mode=epmod.CMD_MODES[mode])
+        index = torch.full((rows,), -1, dtype=torch.int32, device="cuda")
+        epmod.ep_gather_index(r.h, L.dst_row[0], Lg.dst_row[0], fk[0], T, rows, index)
+        partial = torch.ones((rows_g, cfg.H), dtype=torch.bfloat16, device="cuda")
+        epmod.ep_combine_partial(r.h, bits_to_bf16(y), d_w, L.dst_row[0], fk[0], Lg.dst_row[0], T, y.shape[0],
+                                 rows_g, partial)
+        out = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        rg.combine(partial, torch.ones_like(d_w), Lg.dst_row[0], out)
+        rg.wait()
+        torch.cuda.synchronize()
+        got_g = Lg.numpy()
+        for name, v in lay_g.items():
+            assert np.array_equal(got_g[name], v), name
+        assert np.array_equal(bf16_to_bits(recv_g)[:rows_g], wrecv_g)
+        assert (bf16_to_bits(recv_g)[rows_g:] == 0xBFC0).all()
+        assert np.array_equal(index.cpu().numpy(), windex)
+        assert np.array_equal(bf16_to_bits(partial), wpartial)
+        assert np.array_equal(bf16_to_bits(out), wout)
+        # the wire: commands of the group-level dispatch, fewer rows than one per (token, expert)
+        want_cmds = oracle.expected_cmds(wg[0], lay_g, 0, 1, cfg.H, "bf16", mode)
+        assert oracle.cmd_multiset(epmod.ep_cmd_log(rg.h)) == want_cmds
+        oracle.check_fence_trace(epmod.ep_event_log(rg.h), lay_g["count"])
+        st = rg.stats()
+        assert st["write_rows"] == rows_g <= rows and st["device_error"] == 0 and r.stats()["device_error"] == 0
