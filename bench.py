@@ -153,6 +153,36 @@ def run_suite(args) -> int:
                             lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3, cmd_mode=cm),
                             after=r.wait)
                 res[key] = rr
+        if cid in (4, 5):
+            # high-throughput mode: one copy per (token, group), partial reduce per group, final reduce
+            for G in ((1, 8) if cid == 4 else (1,)):
+                NG = R // G
+                with EPRunner(R, E, K, H, T, num_proxy_threads=0) as r1, \
+                        EPRunner(NG, NG, K, H, T, num_proxy_threads=4, spin_timeout_ms=10000) as rg:
+                    gi, fk = torch.empty_like(d_idx), torch.empty_like(d_idx)
+                    ep.ep_dedup(r1.h, d_idx, T, G, gi, fk)
+                    L = r1.layout(d_idx)
+                    Lg = rg.layout(gi)
+                    torch.cuda.synchronize()
+                    rows_g = int((gi >= 0).sum().item())
+                    recv_g = torch.zeros((rows_g, H), dtype=torch.bfloat16, device="cuda")
+                    partial = torch.zeros((rows_g, H), dtype=torch.bfloat16, device="cuda")
+                    index = torch.zeros((rows,), dtype=torch.int32, device="cuda")
+                    ones = torch.ones_like(d_w)
+                    hh = {"groups": NG, "rows_per_token_expert": rows, "rows_per_token_group": rows_g,
+                          "wire_bytes_ratio": round(rows_g / rows, 4)}
+                    hh["dedup_us"] = timed(lambda: ep.ep_dedup(r1.h, d_idx, T, G, gi, fk))
+                    hh["layout_groups_us"] = timed(lambda: rg.layout(gi))
+                    hh["dispatch_groups_chunk32_us"] = timed(
+                        lambda: rg.dispatch(d_x, gi[0], Lg, recv_g, cmd_mode=ep.EP_CMD_CHUNK32), after=rg.wait)
+                    hh["gather_index_us"] = timed(
+                        lambda: ep.ep_gather_index(r1.h, L.dst_row[0], Lg.dst_row[0], fk[0], T, rows, index))
+                    hh["combine_partial_us"] = timed(
+                        lambda: ep.ep_combine_partial(r1.h, recv, d_w, L.dst_row[0], fk[0], Lg.dst_row[0], T, rows,
+                                                      rows_g, partial))
+                    hh["combine_final_us"] = timed(lambda: rg.combine(partial, ones, Lg.dst_row[0], o))
+                    res[f"ht_ranks_per_group{G}"] = hh
+                    del recv_g, partial
         out[cfg.name] = res
         del recv, rq, rs, d_x, o
         torch.cuda.empty_cache()
