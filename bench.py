@@ -126,7 +126,7 @@ def run_suite(args) -> int:
                         rr["dispatch_fp8_ring_off_us"] = timed(
                             lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3,
                                                cmd_mode=ep.EP_CMD_NONE))
-                for mode in ("per_token", "chunk32"):
+                for mode in ("per_token", "chunk32", "chunk32_ordered"):
                     cm = ep.CMD_MODES[mode]
                     rr[f"dispatch_bf16_{mode}_us"] = timed(
                         lambda: r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=cm), after=r.wait)

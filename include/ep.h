@@ -67,6 +67,12 @@ enum ep_cmd_mode {
   EP_CMD_PER_TOKEN = 0,       /* one Write command per (token, expert)                 */
   EP_CMD_CHUNK32 = 1,         /* one Write per run of <= 32 consecutive rows of an expert */
   EP_CMD_NONE = 2,            /* ring off: payload placement only                      */
+  EP_CMD_CHUNK32_ORDERED = 3, /* high-throughput style (Section 3.3, "partial ordering"): per chunk an ordered
+                                 Write and an ordered Atomic that advances the receiver's tail counter of the
+                                 communication channel (source rank -> destination rank); both carry the
+                                 channel's sequence number and go through the FIFO destination rank mod C; the
+                                 receiver applies them strictly in sequence.  No per-expert count Atomics.
+                                 Always ends with a Drain on every FIFO (EP_CMD_DRAIN is implied).          */
   EP_CMD_MODE_MASK = 0xFF,
   EP_CMD_ATOMICS_FIRST = 0x100, /* push every count Atomic before any Write (forces the fence path) */
   EP_CMD_DRAIN = 0x200          /* last wave pushes Drain on every channel and blocks on Check-completion */
@@ -104,6 +110,7 @@ typedef struct ep_stats_t {
   uint64_t write_rows;       /* sum of rows carried by Writes                          */
   uint64_t atomics_applied;
   uint64_t atomics_deferred; /* atomics that had to wait in the control buffer         */
+  uint64_t ordered_parked;   /* sequenced messages that arrived ahead of their turn    */
   uint64_t rejected;         /* commands that failed offset translation / bounds check */
   uint64_t gpu_ring_full;    /* times a GPU push saw "full" in its cached head and re-read the head over PCIe */
   uint64_t first_poll_ns;    /* CLOCK_MONOTONIC of the first command seen since ep_reset_stats */
@@ -230,6 +237,11 @@ int ep_recv_wait(ep_handle *h, int32_t src_rank, int32_t dst_rank_filter, int32_
  * *d_recv_count (may be NULL) receives the same memory's device address. */
 int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv_count);
 
+/* ep_tail_counters - *recv_tail points at pinned-host int32 [S, R]: rows
+ * announced so far on the communication channel (source, destination rank) by
+ * ordered Atomics (EP_CMD_CHUNK32_ORDERED), added up in sequence order. */
+int ep_tail_counters(ep_handle *h, const int32_t **recv_tail);
+
 /* ep_stats / ep_reset_stats - proxy and ring statistics.  Reset also zeroes
  * the completion counters; call it only when ep_wait has returned. */
 int ep_stats(ep_handle *h, ep_stats_t *out);
@@ -240,7 +252,10 @@ int ep_reset_stats(ep_handle *h);
  * Needs EP_FLAG_LOG_CMDS; call after ep_wait.
  * ep_event_log - same for the receiver-side trace (4 x uint32 per record:
  * kind | thread << 8, source rank, global expert, value; kind 1 = Write
- * delivered (value = rows), 2 = Atomic delivered, 3 = Atomic applied). */
+ * delivered (value = rows), 2 = Atomic delivered, 3 = Atomic applied.  Ordered
+ * mode: [2] is the destination rank and value the sequence number; kind 4 =
+ * ordered Write delivered, 5 = ordered Atomic delivered, 6 = ordered Write
+ * applied, 7 = ordered Atomic applied). */
 int ep_cmd_log(ep_handle *h, void *buf, size_t cap, size_t *n);
 int ep_event_log(ep_handle *h, void *buf, size_t cap, size_t *n);
 
@@ -274,7 +289,13 @@ const char *ep_last_error(void);
  * The lap parity of slot Idx is ((Idx / ring_entries) & 1) ^ 1; a slot is
  * ready when both parity bits match the lap the consumer is on.  The sequence
  * number of a command is its Idx (order inside one channel is kept). */
-enum ep_cmd_op { EP_OP_WRITE = 1, EP_OP_ATOMIC = 2, EP_OP_DRAIN = 3, EP_OP_BARRIER = 4 };
+enum ep_cmd_op {
+  EP_OP_WRITE = 1, EP_OP_ATOMIC = 2, EP_OP_DRAIN = 3, EP_OP_BARRIER = 4,
+  /* Sequenced variants used by EP_CMD_CHUNK32_ORDERED: w2 carries the 32-bit sequence number of the
+   * communication channel (source rank, destination rank); an ordered Write's source offset equals its
+   * destination offset; an ordered Atomic ADDS w1 to the tail counter w3 = source * R + destination rank. */
+  EP_OP_ORDERED_WRITE = 5, EP_OP_ORDERED_ATOMIC = 6
+};
 
 #ifdef __cplusplus
 }

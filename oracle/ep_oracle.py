@@ -295,7 +295,7 @@ def bf16_ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
 #   w2: Write: source offset / 16
 #   w3: [31] lap parity  [30:0] Write: destination offset / 16;
 #                               Atomic: counter index src * E_loc + local expert
-OP_WRITE, OP_ATOMIC, OP_DRAIN, OP_BARRIER = 1, 2, 3, 4
+OP_WRITE, OP_ATOMIC, OP_DRAIN, OP_BARRIER, OP_ORDERED_WRITE, OP_ORDERED_ATOMIC = 1, 2, 3, 4, 5, 6
 CHUNK_ROWS = 32
 
 
@@ -413,6 +413,95 @@ def check_chunk_cover(log_words: np.ndarray, lay: Dict[str, np.ndarray], s: int,
         b, c = int(lay["base"][s, e]), int(lay["count"][s, e])
         want[b:b + c] = 1
     assert np.array_equal(covered, want), "chunk writes do not tile the destination rows exactly once"
+
+
+def check_ordered_cmds(log_words: np.ndarray, lay: Dict[str, np.ndarray], s: int, E_loc: int, rb: int,
+                       first_seq: Optional[Dict[int, int]] = None) -> Dict[int, int]:
+    """High-throughput-style command stream of source s (Section 3.3, "partial ordering"): per
+    communication channel (s -> destination rank) the sequence numbers form one contiguous run
+    (starting at first_seq[rank], default 0); every ordered Write with number n is paired with the
+    ordered Atomic n + 1 whose value is the Write's row count; the Writes tile every expert's rows
+    exactly once in chunks of <= 32 that start at multiples of 32 from the expert's first row; the
+    Atomics of a rank add up to the rows that rank receives from s.  Returns the next sequence
+    number per rank."""
+    E = lay["count"].shape[1]
+    R = E // E_loc
+    per_rank: Dict[int, Dict[int, dict]] = {r: {} for r in range(R)}
+    covered = np.zeros(int(lay["expert_offset"][E]), np.int32)
+    for w in np.asarray(log_words, np.uint32).reshape(-1, 4):
+        d = decode_cmd(w)
+        if d["op"] not in (OP_ORDERED_WRITE, OP_ORDERED_ATOMIC) or d["src"] != s:
+            continue
+        seq = int(w[2])
+        assert seq not in per_rank[d["dst_rank"]], f"sequence number {seq} used twice on rank {d['dst_rank']}"
+        per_rank[d["dst_rank"]][seq] = d
+        if d["op"] == OP_ORDERED_WRITE:
+            e = d["dst_rank"] * E_loc + d["local_expert"]
+            r0, n = d["dst_off"] // rb, d["nbytes"] // rb
+            assert d["dst_off"] % rb == 0 and d["nbytes"] % rb == 0 and 1 <= n <= CHUNK_ROWS and d["rows"] == n, d
+            b, c = int(lay["base"][s, e]), int(lay["count"][s, e])
+            assert b <= r0 and r0 + n <= b + c and (r0 - b) % CHUNK_ROWS == 0, (d, b, c)
+            covered[r0:r0 + n] += 1
+        else:
+            assert d["counter"] == s * R + d["dst_rank"], d
+    want = np.zeros_like(covered)
+    for e in range(E):
+        b, c = int(lay["base"][s, e]), int(lay["count"][s, e])
+        want[b:b + c] = 1
+    assert np.array_equal(covered, want), "ordered writes do not tile the destination rows exactly once"
+    nxt = {}
+    for r in range(R):
+        seqs = sorted(per_rank[r])
+        lo = (first_seq or {}).get(r, 0)
+        assert seqs == list(range(lo, lo + len(seqs))), f"rank {r}: sequence numbers are not one contiguous run"
+        assert len(seqs) % 2 == 0
+        total = 0
+        for q in seqs[::2]:
+            wr, at = per_rank[r][q], per_rank[r][q + 1]
+            assert wr["op"] == OP_ORDERED_WRITE and at["op"] == OP_ORDERED_ATOMIC and at["w1"] == wr["rows"], (wr, at)
+            total += wr["rows"]
+        assert total == int(lay["count"][s, r * E_loc:(r + 1) * E_loc].sum())
+        nxt[r] = lo + len(seqs)
+    return nxt
+
+
+EV_ORD_WRITE_IN, EV_ORD_ATOMIC_IN, EV_ORD_WRITE_APPLIED, EV_ORD_ATOMIC_APPLIED = 4, 5, 6, 7
+
+
+def check_order_trace(events: np.ndarray, first_seq: Optional[Dict[Tuple[int, int], int]] = None) -> Dict[str, int]:
+    """Receiver-side partial ordering (Section 3.3): on every communication channel (source,
+    destination rank) messages are applied strictly in sequence-number order starting at
+    first_seq[(source, rank)] (default 0), each exactly once and only after it was delivered; a
+    message delivered ahead of its turn waits; every delivered message is eventually applied.
+    Returns how many messages were applied and how many had to wait."""
+    ev = np.asarray(events, np.uint32).reshape(-1, 4)
+    delivered: Dict[Tuple[int, int], set] = {}
+    nxt: Dict[Tuple[int, int], int] = {}
+    owner: Dict[Tuple[int, int], int] = {}
+    kinds: Dict[Tuple[int, int, int], int] = {}
+    waited = applied = 0
+    for kind_thr, src, dr, seq in ev.tolist():
+        kind, thr = kind_thr & 0xFF, kind_thr >> 8
+        if kind not in (EV_ORD_WRITE_IN, EV_ORD_ATOMIC_IN, EV_ORD_WRITE_APPLIED, EV_ORD_ATOMIC_APPLIED):
+            continue
+        key = (src, dr)
+        assert owner.setdefault(key, thr) == thr, f"channel {key} handled by two threads"
+        nxt.setdefault(key, (first_seq or {}).get(key, 0))
+        if kind in (EV_ORD_WRITE_IN, EV_ORD_ATOMIC_IN):
+            assert seq not in delivered.setdefault(key, set()), f"{key}: sequence {seq} delivered twice"
+            delivered[key].add(seq)
+            kinds[(src, dr, seq)] = kind
+            if seq != nxt[key]:
+                waited += 1
+        else:
+            assert seq in delivered.get(key, set()), f"{key}: sequence {seq} applied before it was delivered"
+            assert kinds[(src, dr, seq)] == kind - 2, f"{key}: sequence {seq} applied as the wrong kind"
+            assert seq == nxt[key], f"{key}: applied {seq}, expected {nxt[key]} (out of order)"
+            nxt[key] = seq + 1
+            applied += 1
+    for key, got in delivered.items():
+        assert all(q < nxt[key] for q in got), f"{key}: delivered but never applied: {sorted(q for q in got if q >= nxt[key])}"
+    return dict(applied=applied, waited=waited)
 
 
 # Receiver-side event log (one record = 4 x uint32):

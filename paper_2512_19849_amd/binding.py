@@ -17,15 +17,16 @@ from . import build as _build
 
 EP_OK, EP_EINVAL, EP_ENOMEM, EP_ESTATE, EP_EHIP, EP_ETIMEOUT, EP_EBOUNDS = 0, -1, -2, -3, -4, -5, -6
 EP_BF16, EP_FP8_E4M3 = 0, 1
-EP_CMD_PER_TOKEN, EP_CMD_CHUNK32, EP_CMD_NONE = 0, 1, 2
+EP_CMD_PER_TOKEN, EP_CMD_CHUNK32, EP_CMD_NONE, EP_CMD_CHUNK32_ORDERED = 0, 1, 2, 3
 EP_CMD_ATOMICS_FIRST, EP_CMD_DRAIN = 0x100, 0x200
 EP_FLAG_LOG_CMDS, EP_FLAG_LOG_EVENTS, EP_FLAG_HOST_ONLY = 1, 2, 4
-EP_OP_WRITE, EP_OP_ATOMIC, EP_OP_DRAIN, EP_OP_BARRIER = 1, 2, 3, 4
+EP_OP_WRITE, EP_OP_ATOMIC, EP_OP_DRAIN, EP_OP_BARRIER, EP_OP_ORDERED_WRITE, EP_OP_ORDERED_ATOMIC = 1, 2, 3, 4, 5, 6
 
 _STATUS = {0: "EP_OK", -1: "EP_EINVAL", -2: "EP_ENOMEM", -3: "EP_ESTATE", -4: "EP_EHIP", -5: "EP_ETIMEOUT",
            -6: "EP_EBOUNDS"}
 PAYLOADS = {"bf16": EP_BF16, "fp8": EP_FP8_E4M3}
-CMD_MODES = {"per_token": EP_CMD_PER_TOKEN, "chunk32": EP_CMD_CHUNK32, "none": EP_CMD_NONE}
+CMD_MODES = {"per_token": EP_CMD_PER_TOKEN, "chunk32": EP_CMD_CHUNK32, "none": EP_CMD_NONE,
+             "chunk32_ordered": EP_CMD_CHUNK32_ORDERED}
 
 
 class EPError(RuntimeError):
@@ -47,7 +48,8 @@ class ep_config(C.Structure):
 
 class ep_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("cmds", "writes", "atomics", "drains", "write_bytes", "write_rows",
-                                          "atomics_applied", "atomics_deferred", "rejected", "gpu_ring_full",
+                                          "atomics_applied", "atomics_deferred", "ordered_parked", "rejected",
+                                          "gpu_ring_full",
                                           "first_poll_ns", "last_apply_ns")] + \
                [("per_thread_cmds", C.c_uint64 * 16), ("device_error", C.c_int32), ("proxy_error", C.c_int32)]
 
@@ -58,7 +60,7 @@ class ep_stats_t(C.Structure):
 
 
 EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
-           "ep_counters", "ep_dedup", "ep_gather_index", "ep_combine_partial",
+           "ep_counters", "ep_tail_counters", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error"]
 
@@ -98,6 +100,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_recv_wait.argtypes = [vp, i32, i32, vp, vp]
     L.ep_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     L.ep_stats.argtypes = [vp, C.POINTER(ep_stats_t)]
+    L.ep_tail_counters.argtypes = [vp, C.POINTER(vp)]
     L.ep_reset_stats.argtypes = [vp]
     L.ep_cmd_log.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
     L.ep_event_log.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
@@ -203,6 +206,14 @@ def ep_counters(h: int, S: int, E: int) -> np.ndarray:
     _check("ep_counters", load_library().ep_counters(h, C.byref(host), C.byref(dev)))
     buf = (C.c_int32 * (S * E)).from_address(host.value)
     return np.frombuffer(buf, dtype=np.int32).reshape(S, E)
+
+
+def ep_tail_counters(h: int, S: int, R: int) -> np.ndarray:
+    """numpy view (no copy) of the pinned-host tail counters [S, R] of the ordered mode."""
+    host = C.c_void_p()
+    _check("ep_tail_counters", load_library().ep_tail_counters(h, C.byref(host)))
+    buf = (C.c_int32 * (S * R)).from_address(host.value)
+    return np.frombuffer(buf, dtype=np.int32).reshape(S, R)
 
 
 def ep_stats(h: int) -> dict:

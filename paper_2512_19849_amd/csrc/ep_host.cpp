@@ -10,6 +10,7 @@
 
 #include <atomic>
 #include <deque>
+#include <map>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -56,7 +57,8 @@ inline void bump(std::atomic<uint64_t> &a, uint64_t v = 1) {
 struct WireEvent {
   uint32_t imm;
   uint16_t src;       // connection = source rank
-  uint16_t dst_rank;  // the receiving rank (whose proxy this event reaches)
+  uint8_t dst_rank;   // the receiving rank (whose proxy this event reaches)
+  uint8_t ordered;    // sequenced message of the high-throughput mode
 };
 
 struct alignas(64) ProxyThread {
@@ -68,10 +70,13 @@ struct alignas(64) ProxyThread {
   std::vector<int32_t> seen;
   std::vector<std::deque<int32_t>> parked;  // the control buffer
   std::vector<WireEvent> window;            // in-flight immediates (reordering hook)
+  // ordered (high-throughput) channels: next sequence number and early arrivals per (source, destination rank)
+  std::vector<uint32_t> next_seq;
+  std::vector<std::map<uint32_t, WireEvent>> early;
   uint64_t rng = 0;
   // statistics (written by the owner thread only, read racy-but-atomically)
   std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
-      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0};
+      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0};
   std::mutex log_mu;
   std::vector<uint32_t> cmd_log, event_log;
 };
@@ -92,13 +97,15 @@ struct ep_handle {
   uint64_t *head = nullptr;   // [C * kHeadStride]
   int32_t *recv_count = nullptr;
   int *recv_flag = nullptr;  // posted count + 1, cleared by the GPU-side wait
+  int32_t *recv_tail = nullptr;  // [S, R] rows announced per communication channel (ordered mode)
+  std::atomic<int64_t> expected_drains{0};
   void *d_recv_flag = nullptr;
   int *dev_error = nullptr;
   void *d_recv_count = nullptr;
   // device state
   RingDev ring{};
   int32_t *tile_hist = nullptr, *tile_base = nullptr, *chunk_cnt = nullptr, *expert_done = nullptr;
-  unsigned *ticket = nullptr, *waves_done = nullptr;
+  unsigned *ticket = nullptr, *waves_done = nullptr, *ht_seq = nullptr;
   int ntiles_cap = 0, chunks_per_expert = 0;
   // host-only producer state
   std::atomic<uint64_t> host_tail[kMaxChannels];
@@ -140,7 +147,13 @@ void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_
 // only when that count has reached its value, otherwise it waits in the
 // control buffer; arrivals for other experts never release it (Section 3.3,
 // "partial completion fence").
+void deliver_ordered(ep_handle *h, ProxyThread &P, const WireEvent &ev);
+
 void deliver(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  if (ev.ordered) {
+    deliver_ordered(h, P, ev);
+    return;
+  }
   const uint32_t le = (ev.imm >> 19) & 0xFFFu;
   const uint32_t e = (uint32_t)ev.dst_rank * h->E_loc + le;
   const size_t key = (size_t)ev.src * h->cfg.num_experts + e;
@@ -164,6 +177,47 @@ void deliver(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
       q.push_back(value);
       bump(P.deferred, 1);
     }
+  }
+}
+
+// Receiver half, sequenced messages (Section 3.3, "partial ordering"): the immediate carries the low
+// 16 bits of the communication channel's sequence number,
+//   [31] kind (0 Write, 1 Atomic)  [30:15] sequence & 0xFFFF  [14:0] rows (Write) / value (Atomic).
+// A message whose number is not the next one of its channel waits in the control buffer; when the
+// missing ones arrive, the buffered ones are applied one after the other, in sequence.  Order is
+// kept per channel only: other channels never hold a message back.
+void apply_ordered(ep_handle *h, ProxyThread &P, size_t chan, const WireEvent &ev, uint32_t seq) {
+  const uint32_t value = ev.imm & 0x7FFFu;
+  if (ev.imm >> 31) {
+    const int32_t now = __atomic_load_n(&h->recv_tail[chan], __ATOMIC_RELAXED) + (int32_t)value;
+    __atomic_store_n(&h->recv_tail[chan], now, __ATOMIC_RELEASE);
+    log_event(h, P, 7, ev.src, ev.dst_rank, seq);
+    P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
+  } else {
+    log_event(h, P, 6, ev.src, ev.dst_rank, seq);
+  }
+}
+
+void deliver_ordered(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  const size_t chan = (size_t)ev.src * h->cfg.num_ranks + ev.dst_rank;
+  uint32_t &next = P.next_seq[chan];
+  // rebuild the full number from its low 16 bits: it lies within +-32768 of the next expected one
+  uint32_t seq = (next & ~0xFFFFu) | ((ev.imm >> 15) & 0xFFFFu);
+  if (seq + 0x8000u < next) seq += 0x10000u;
+  else if (seq >= next + 0x8000u && seq >= 0x10000u) seq -= 0x10000u;
+  log_event(h, P, (ev.imm >> 31) ? 5 : 4, ev.src, ev.dst_rank, seq);
+  if (seq != next) {
+    P.early[chan].emplace(seq, ev);
+    bump(P.ordered_parked, 1);
+    return;
+  }
+  apply_ordered(h, P, chan, ev, seq);
+  ++next;
+  std::map<uint32_t, WireEvent> &q = P.early[chan];
+  for (auto it = q.find(next); it != q.end(); it = q.find(next)) {
+    apply_ordered(h, P, chan, it->second, next);
+    q.erase(it);
+    ++next;
   }
 }
 
@@ -206,7 +260,7 @@ void reject(ep_handle *h, ProxyThread &P) {
 // Sender half: one polled command.  Offsets are relative to the registered
 // heap; the proxy translates and bounds-checks them before acting
 // (Section 3.2, "Symmetric memory").
-void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) {
+void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) {
   const ep_config &c = h->cfg;
   const uint32_t op = (w0 >> 28) & 7u, src = (w0 >> 20) & 0xFFu, dr = (w0 >> 12) & 0xFFu, le = w0 & 0xFFFu;
   bump(P.cmds, 1);
@@ -233,7 +287,7 @@ void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_
       // The payload already sits in the destination partition (the kernel stored it);
       // what remains of the peer write is its arrival notice.
       transmit(h, P, WireEvent{(le << 19) | ((rows - 1) << 13) | (uint32_t)((dof >> 4) & 0x1FFFu), (uint16_t)src,
-                               (uint16_t)dr});
+                               (uint8_t)dr, 0});
       break;
     }
     case EP_OP_ATOMIC: {
@@ -244,14 +298,48 @@ void process_cmd(ep_handle *h, ProxyThread &P, uint32_t w0, uint32_t w1, uint32_
         return;
       }
       bump(P.atomics, 1);
-      transmit(h, P, WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint16_t)dr});
+      transmit(h, P, WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint8_t)dr, 0});
       break;
     }
-    case EP_OP_DRAIN:
-      // everything this thread handed to the transport must have completed
-      bump(P.drains, 1);
-      flush_window(h, P);
+    case EP_OP_ORDERED_WRITE: {
+      const uint64_t len = (uint64_t)(w1 & 0x3FFFFFFu) << 4;
+      const uint32_t rows = (w1 >> 26) + 1;
+      const uint64_t dof = (uint64_t)w3 << 4;
+      if ((int)src >= c.num_src || (int)dr >= c.num_ranks || (int)le >= h->E_loc || len == 0 ||
+          dof + len > h->heap_bytes) {
+        reject(h, P);
+        return;
+      }
+      bump(P.writes, 1);
+      bump(P.write_bytes, len);
+      bump(P.write_rows, rows);
+      transmit(h, P, WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 1});
       break;
+    }
+    case EP_OP_ORDERED_ATOMIC: {
+      if ((int)src >= c.num_src || (int)dr >= c.num_ranks || w1 > 0x7FFFu ||
+          w3 != src * (uint32_t)c.num_ranks + dr) {
+        reject(h, P);
+        return;
+      }
+      bump(P.atomics, 1);
+      transmit(h, P, WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | w1, (uint16_t)src, (uint8_t)dr, 1});
+      break;
+    }
+    case EP_OP_DRAIN: {
+      // everything this thread handed to the transport must have completed
+      flush_window(h, P);
+      // communication channels that travel through this FIFO (destination rank mod C == fifo) must
+      // have nothing left waiting: a leftover means a sequence number never arrived
+      for (int ss = 0; ss < c.num_src; ++ss)
+        for (int r = fifo; r < c.num_ranks; r += c.num_channels)
+          if (!P.early[(size_t)ss * c.num_ranks + r].empty()) {
+            int zero = 0;
+            h->proxy_error.compare_exchange_strong(zero, EP_ESTATE);
+          }
+      P.drains.store(P.drains.load(std::memory_order_relaxed) + 1, std::memory_order_release);
+      break;
+    }
     default:  // Barrier needs peer processes; not part of this single-GPU build
       reject(h, P);
       break;
@@ -277,7 +365,7 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
         const uint32_t gen = (((uint32_t)(hd >> h->log2_entries)) & 1u) ^ 1u;
         const uint32_t w0 = (uint32_t)lo, w3 = (uint32_t)(hi >> 32);
         if ((w0 >> 31) != gen || (w3 >> 31) != gen) break;
-        process_cmd(h, P, w0, (uint32_t)(lo >> 32), (uint32_t)hi, w3);
+        process_cmd(h, P, ch, w0, (uint32_t)(lo >> 32), (uint32_t)hi, w3);
         ++hd;
         ++n;
       }
@@ -333,15 +421,17 @@ void free_all(ep_handle *h) {
     free(h->head);
     free(h->recv_count);
     free(h->recv_flag);
+    free(h->recv_tail);
     free(h->dev_error);
   } else {
     if (h->slots) (void)hipHostFree(h->slots);
     if (h->head) (void)hipHostFree(h->head);
     if (h->recv_count) (void)hipHostFree(h->recv_count);
     if (h->recv_flag) (void)hipHostFree(h->recv_flag);
+    if (h->recv_tail) (void)hipHostFree(h->recv_tail);
     if (h->dev_error) (void)hipHostFree(h->dev_error);
     void *dev[] = {h->ring.tail, h->ring.cached_head, h->ring.stalls, h->tile_hist, h->tile_base,
-                   h->chunk_cnt, h->expert_done, h->ticket, h->waves_done};
+                   h->chunk_cnt, h->expert_done, h->ticket, h->waves_done, h->ht_seq};
     for (void *p : dev)
       if (p) (void)hipFree(p);
   }
@@ -410,6 +500,7 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
   if (!rc) rc = pinned_alloc(h->host_only, &h->head, (size_t)C * kHeadStride * 8);
   if (!rc) rc = pinned_alloc(h->host_only, &h->recv_count, (size_t)S * E * 4);
   if (!rc) rc = pinned_alloc(h->host_only, &h->recv_flag, (size_t)S * E * 4);
+  if (!rc) rc = pinned_alloc(h->host_only, &h->recv_tail, (size_t)S * cfg->num_ranks * 4);
   if (!rc) rc = pinned_alloc(h->host_only, &h->dev_error, 64);
   if (!rc && !h->host_only) {
     h->ntiles_cap = (cfg->max_tokens + kLayoutTile - 1) / kLayoutTile;
@@ -424,6 +515,7 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     if (!rc) rc = dev_alloc_zero(&h->expert_done, (size_t)E * 4);
     if (!rc) rc = dev_alloc_zero(&h->ticket, 4);
     if (!rc) rc = dev_alloc_zero(&h->waves_done, 4);
+    if (!rc) rc = dev_alloc_zero(&h->ht_seq, (size_t)S * cfg->num_ranks * 4);
     void *dp = nullptr;
     if (!rc && !HIP_OK(hipHostGetDevicePointer(&dp, h->slots, 0))) rc = EP_EHIP;
     h->ring.slots = dp;
@@ -459,6 +551,8 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     }
     P.seen.assign((size_t)S * E, 0);
     P.parked.resize((size_t)S * E);
+    P.next_seq.assign((size_t)S * cfg->num_ranks, 0);
+    P.early.resize((size_t)S * cfg->num_ranks);
     P.rng = cfg->reorder_seed * 0x9E3779B97F4A7C15ull + (uint64_t)i;
   }
   for (int i = 0; i < h->nthreads; ++i) h->threads[i].th = std::thread(proxy_main, h, &h->threads[i]);
@@ -524,7 +618,12 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
   if (T < 0 || T > c.max_tokens || src_rank < 0 || src_rank >= c.num_src) return EP_EINVAL;
   if (dst_rank_filter < -1 || dst_rank_filter >= c.num_ranks) return EP_EINVAL;
   if (payload != EP_BF16 && payload != EP_FP8_E4M3) return EP_EINVAL;
-  if (mode != EP_CMD_PER_TOKEN && mode != EP_CMD_CHUNK32 && mode != EP_CMD_NONE) return EP_EINVAL;
+  if (mode != EP_CMD_PER_TOKEN && mode != EP_CMD_CHUNK32 && mode != EP_CMD_NONE && mode != EP_CMD_CHUNK32_ORDERED)
+    return EP_EINVAL;
+  if (mode == EP_CMD_CHUNK32_ORDERED) {
+    if (cmd_mode & EP_CMD_ATOMICS_FIRST) return EP_EINVAL;
+    cmd_mode |= EP_CMD_DRAIN;
+  }
   if (cmd_mode & ~(EP_CMD_MODE_MASK | EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN)) return EP_EINVAL;
   if (recv_rows < 0 || recv_rows > c.heap_rows) return EP_EINVAL;
   if (T > 0 && (!d_x || !d_topk_idx || !d_dst_row || !d_recv)) return EP_EINVAL;
@@ -560,10 +659,14 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
   a.chunk_cnt = h->chunk_cnt;
   a.expert_done = h->expert_done;
   a.waves_done = h->waves_done;
+  a.ht_seq = h->ht_seq;
+  a.R = c.num_ranks;
   a.ring = h->ring;
   if (mode != EP_CMD_NONE) {
     if (((uint64_t)T * a.row_bytes) >> 4 > 0xFFFFFFFFull) return EP_EINVAL;
-    if (T > 0)
+    if (mode == EP_CMD_CHUNK32_ORDERED)
+      h->expected_drains.fetch_add(c.num_channels, std::memory_order_relaxed);
+    else
       h->expected_atomics.fetch_add(dst_rank_filter < 0 ? c.num_experts : h->E_loc, std::memory_order_relaxed);
   }
   if (T == 0) {
@@ -685,9 +788,16 @@ int ep_wait(ep_handle *h) {
   for (;;) {
     if (int e = dev_err(h)) return e;
     if (int e = h->proxy_error.load(std::memory_order_relaxed)) return e;
-    int64_t applied = 0;
-    for (int i = 0; i < h->nthreads; ++i) applied += (int64_t)h->threads[i].applied.load(std::memory_order_acquire);
-    if (applied >= h->expected_atomics.load(std::memory_order_relaxed)) return EP_OK;
+    int64_t applied = 0, drained = 0;
+    for (int i = 0; i < h->nthreads; ++i) {
+      applied += (int64_t)h->threads[i].applied.load(std::memory_order_acquire);
+      drained += (int64_t)h->threads[i].drains.load(std::memory_order_acquire);
+    }
+    if (applied >= h->expected_atomics.load(std::memory_order_relaxed) &&
+        drained >= h->expected_drains.load(std::memory_order_relaxed)) {
+      if (int e = h->proxy_error.load(std::memory_order_relaxed)) return e;
+      return EP_OK;
+    }
     if ((++spins & 1023) == 0) {
       if (now_ns() - t0 > h->timeout_ns) return EP_ETIMEOUT;
       std::this_thread::yield();
@@ -701,6 +811,12 @@ int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv
   if (!h || !recv_count) return EP_EINVAL;
   *recv_count = h->recv_count;
   if (d_recv_count) *d_recv_count = (const int32_t *)h->d_recv_count;
+  return EP_OK;
+}
+
+int ep_tail_counters(ep_handle *h, const int32_t **recv_tail) {
+  if (!h || !recv_tail) return EP_EINVAL;
+  *recv_tail = h->recv_tail;
   return EP_OK;
 }
 
@@ -719,6 +835,7 @@ int ep_stats(ep_handle *h, ep_stats_t *out) {
     out->write_rows += P.write_rows.load();
     out->atomics_applied += P.applied.load();
     out->atomics_deferred += P.deferred.load();
+    out->ordered_parked += P.ordered_parked.load();
     out->rejected += P.rejected.load();
     const uint64_t f = P.first_poll_ns.load(), l = P.last_apply_ns.load();
     if (f && (!out->first_poll_ns || f < out->first_poll_ns)) out->first_poll_ns = f;
@@ -744,13 +861,15 @@ int ep_reset_stats(ep_handle *h) {
   for (int i = 0; i < h->nthreads; ++i) {
     ProxyThread &P = h->threads[i];
     for (auto *a : {&P.cmds, &P.writes, &P.atomics, &P.drains, &P.write_bytes, &P.write_rows, &P.applied,
-                    &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns})
+                    &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns, &P.ordered_parked})
       a->store(0);
     std::lock_guard<std::mutex> g(P.log_mu);
     P.cmd_log.clear();
     P.event_log.clear();
   }
   h->expected_atomics.store(0);
+  h->expected_drains.store(0);
+  memset(h->recv_tail, 0, (size_t)h->cfg.num_src * h->cfg.num_ranks * 4);
   memset(h->recv_count, 0, (size_t)h->cfg.num_src * h->cfg.num_experts * 4);
   memset(h->recv_flag, 0, (size_t)h->cfg.num_src * h->cfg.num_experts * 4);
   if (h->host_only) {

@@ -71,6 +71,8 @@ struct DispatchArgs {
   int32_t *chunk_cnt;      // scratch [E * chunks_per_expert], zero between calls
   int32_t *expert_done;    // scratch [E], zero between calls
   unsigned *waves_done;    // scratch, zero between calls
+  unsigned *ht_seq;        // scratch [S*R]: next sequence number of each communication channel
+  int32_t R;
   RingDev ring;
 };
 

@@ -411,6 +411,19 @@ EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
       __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const unsigned long long off = (unsigned long long)(a.base[e] + (j << 5)) * a.row_bytes;
       const unsigned len = (unsigned)csize * a.row_bytes;
+      if (mode == EP_CMD_CHUNK32_ORDERED) {
+        // High-throughput style: the chunk's Write and the Atomic that advances the receiver's tail
+        // take two consecutive sequence numbers of the communication channel (source, destination
+        // rank) and travel through that channel's FIFO; the receiver re-establishes the order.
+        const unsigned seq = __hip_atomic_fetch_add(a.ht_seq + (size_t)a.src * a.R + dr, 2u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned och = dr % a.ring.channels;
+        ring_push(a.ring, och, cmd_w0(EP_OP_ORDERED_WRITE, a.src, dr, le),
+                  ((unsigned)(csize - 1) << 26) | (len >> 4), seq, (unsigned)(off >> 4));
+        ring_push(a.ring, och, cmd_w0(EP_OP_ORDERED_ATOMIC, a.src, dr, 0), (unsigned)csize, seq + 1u,
+                  (unsigned)(a.src * a.R) + dr);
+        return;
+      }
       ring_push(a.ring, ch, cmd_w0(EP_OP_WRITE, a.src, dr, le), ((unsigned)(csize - 1) << 26) | (len >> 4),
                 (unsigned)(off >> 4), (unsigned)(off >> 4));
       finished_rows = csize;
@@ -455,7 +468,8 @@ __global__ void dispatch_bf16_kernel(DispatchArgs a) {
   const int part = wave % a.parts;
   const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
   const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
-  if (ring_on && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
+  const bool ordered = (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_CHUNK32_ORDERED;
+  if (ring_on && !ordered && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
 
   const TokenMeta m = load_meta(a, t, lane);
   unsigned long long vmask = __ballot(m.valid);
@@ -508,7 +522,8 @@ __global__ void dispatch_fp8_kernel(DispatchArgs a) {
   const int part = wave % a.parts;
   const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
   const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
-  if (ring_on && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
+  const bool ordered = (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_CHUNK32_ORDERED;
+  if (ring_on && !ordered && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
 
   const TokenMeta m = load_meta(a, t, lane);
   unsigned long long vmask = __ballot(m.valid);

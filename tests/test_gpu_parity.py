@@ -641,3 +641,61 @@ def test_ht_round_trip(epmod, oracle, cid, G, T, mask, mode):
         oracle.check_fence_trace(epmod.ep_event_log(rg.h), lay_g["count"])
         st = rg.stats()
         assert st["write_rows"] == rows_g <= rows and st["device_error"] == 0 and r.stats()["device_error"] == 0
+
+
+# --------------------------------- high-throughput style commands: per-channel sequence order
+@pytest.mark.parametrize("cid,T,mask,window,payload", [(1, None, 0.0, 0, "bf16"), (1, None, 0.2, 6, "bf16"),
+                                                       (4, 700, 0.0, 32, "bf16"), (5, 600, 0.1, 3, "fp8"),
+                                                       (4, 4096, 0.0, 100, "bf16")])
+def test_dispatch_ordered_chunks(epmod, oracle, cid, T, mask, window, payload):
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    cfg = g.config(cid, S=1)
+    idx, _ = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=53)
+    T = idx.shape[1]
+    x = g.activations(cfg, 0, T=T)
+    rows = int((idx >= 0).sum())
+    want = oracle.layout(idx, cfg.E, cfg.R)
+    rb = oracle.row_bytes(cfg.H, payload)
+    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    with _runner(epmod, cfg, T, flags=flags, reorder_window=window, reorder_seed=2) as r:
+        d_idx, d_x = _dev(idx), bits_to_bf16(x)
+        lay = r.layout(d_idx)
+        first_cmd, first_ev = None, None
+        ncmd = nev = 0
+        for rnd in range(2):                                    # the second dispatch continues the numbering
+            if payload == "bf16":
+                recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+                r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_CHUNK32_ORDERED)
+            else:
+                recv = torch.zeros((rows, cfg.H), dtype=torch.uint8, device="cuda")
+                rs = torch.zeros((rows, cfg.H // 128), dtype=torch.float32, device="cuda")
+                r.dispatch(d_x, d_idx[0], lay, recv, rs, payload=epmod.EP_FP8_E4M3,
+                           cmd_mode=epmod.EP_CMD_CHUNK32_ORDERED)
+            r.wait()
+            torch.cuda.synchronize()
+            if payload == "bf16":
+                wrecv, _ = oracle.dispatch_bf16(x, idx[0], want["dst_row"][0], cfg.E_loc, rows, fill=0)
+                assert np.array_equal(bf16_to_bits(recv), wrecv)
+            else:
+                wq, ws, _ = oracle.dispatch_fp8(x, idx[0], want["dst_row"][0], cfg.E_loc, rows, fill=0)
+                assert np.array_equal(recv.cpu().numpy(), wq) and np.array_equal(rs.cpu().numpy(), ws)
+            cmds, evs = epmod.ep_cmd_log(r.h), epmod.ep_event_log(r.h)
+            # logs are kept thread by thread: split each thread's part into this round's tail
+            st = r.stats()
+            nchunks = int(np.ceil(want["count"][0] / 32).sum())
+            assert st["writes"] == nchunks * (rnd + 1) and st["atomics"] == nchunks * (rnd + 1)
+            assert st["drains"] == 8 * (rnd + 1) and st["rejected"] == 0 and st["proxy_error"] == 0
+            assert st["atomics_applied"] == 0                   # no per-expert count atomics in this mode
+            per_rank = want["count"][0].reshape(cfg.R, cfg.E_loc).sum(1)
+            assert np.array_equal(epmod.ep_tail_counters(r.h, 1, cfg.R)[0], per_rank * (rnd + 1))
+            res = oracle.check_order_trace(evs)                 # both rounds together: one run per channel
+            assert res["applied"] == 2 * nchunks * (rnd + 1) and res["waited"] == st["ordered_parked"]
+            if rnd == 0:
+                nxt = oracle.check_ordered_cmds(cmds, want, 0, cfg.E_loc, rb)
+            else:
+                seqs = cmds[np.isin((cmds[:, 0] >> 28) & 7, (5, 6))]
+                second = seqs[[int(w[2]) >= nxt[int((w[0] >> 12) & 0xFF)] for w in seqs]]
+                oracle.check_ordered_cmds(second, want, 0, cfg.E_loc, rb, first_seq=nxt)
+        assert st["device_error"] == 0

@@ -294,3 +294,101 @@ def test_reset_stats_and_repeat(ep):
             assert ep.ep_stats(h)["cmds"] == 0 and ep.ep_counters(h, 1, 16).sum() == 0
     finally:
         ep.ep_proxy_stop(h)
+
+
+# ------------------------------------------ high-throughput style: per-channel sequence order
+def _owrite(ep, h, ch, src, dr, seq, rows, rb, row0):
+    return ep.ep_host_push(h, ch, _w0(5, src, dr, 0), ((rows - 1) << 26) | ((rows * rb) >> 4), seq, (row0 * rb) >> 4)
+
+
+def _oatomic(ep, h, ch, src, dr, seq, value, R):
+    return ep.ep_host_push(h, ch, _w0(6, src, dr, 0), value, seq, src * R + dr)
+
+
+def _drain_all(ep, h, C):
+    ids = [ep.ep_host_push(h, c, _w0(3, 0, 0, 0), 0, 0, 0) for c in range(C)]
+    deadline = time.time() + 5
+    for c, i in enumerate(ids):
+        while not ep.ep_host_check_completion(h, c, i):
+            assert time.time() < deadline
+            time.sleep(0.0005)
+
+
+@pytest.mark.parametrize("window", [0, 5, 200])
+def test_partial_ordering_per_communication_channel(ep, oracle, window):
+    """Messages of one communication channel (source -> destination rank) are pushed in a
+    scrambled order and additionally reordered in flight; the receiver applies them strictly by
+    sequence number, channel by channel, and the tail counters end at the rows announced."""
+    R, C, rb = 4, 4, 2048
+    rng = np.random.default_rng(window)
+    h = _start(ep, reorder_window=window, reorder_seed=7, num_src=2)
+    try:
+        want_tail = np.zeros((2, R), np.int64)
+        msgs = []
+        for s in range(2):
+            for dr in range(R):
+                n = int(rng.integers(1, 40))
+                row = 0
+                for i in range(n):
+                    rows = int(rng.integers(1, 33))
+                    msgs.append(("w", s, dr, 2 * i, rows, row))
+                    msgs.append(("a", s, dr, 2 * i + 1, rows))
+                    row += rows
+                    want_tail[s, dr] += rows
+        # scramble within a sliding window so the FIFO order differs from the sequence order
+        order = np.arange(len(msgs))
+        for i in range(0, len(order) - 6, 3):
+            rng.shuffle(order[i:i + 6])
+        for j in order:
+            m = msgs[j]
+            if m[0] == "w":
+                _owrite(ep, h, m[2] % C, m[1], m[2], m[3], m[4], rb, m[5])
+            else:
+                _oatomic(ep, h, m[2] % C, m[1], m[2], m[3], m[4], R)
+        _drain_all(ep, h, C)
+        st = ep.ep_stats(h)
+        assert st["rejected"] == 0 and st["proxy_error"] == 0 and st["drains"] == C
+        assert np.array_equal(ep.ep_tail_counters(h, 2, R), want_tail)
+        res = oracle.check_order_trace(ep.ep_event_log(h))
+        assert res["applied"] == len(msgs) and res["waited"] == st["ordered_parked"] and res["waited"] > 0
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_partial_ordering_sequence_gap_is_reported(ep, oracle):
+    """If a sequence number never arrives, everything behind it on that channel stays in the
+    control buffer; the Drain reports the gap, other channels are unaffected."""
+    R, C = 4, 4
+    h = _start(ep, num_src=1, spin_timeout_ms=300)
+    try:
+        _owrite(ep, h, 1, 0, 1, 0, 4, 2048, 0)
+        _oatomic(ep, h, 1, 0, 1, 1, 4, R)
+        _oatomic(ep, h, 1, 0, 1, 3, 9, R)                        # 2 is missing
+        _owrite(ep, h, 2, 0, 2, 0, 7, 2048, 0)
+        _oatomic(ep, h, 2, 0, 2, 1, 7, R)
+        _drain_all(ep, h, C)
+        tails = ep.ep_tail_counters(h, 1, R)
+        assert tails[0].tolist() == [0, 4, 7, 0]                 # the 9 rows behind the gap were never announced
+        assert ep.ep_stats(h)["proxy_error"] == ep.EP_ESTATE
+        with pytest.raises(ep.EPError):
+            ep.ep_wait(h)
+        with pytest.raises(AssertionError, match="never applied"):
+            oracle.check_order_trace(ep.ep_event_log(h))
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_partial_ordering_sequence_numbers_wrap_16_bits(ep, oracle):
+    """The immediate carries 16 bits of the number; the receiver rebuilds the full value."""
+    R = 4
+    h = _start(ep, num_src=1, reorder_window=16, reorder_seed=3, flags=ep.EP_FLAG_HOST_ONLY)
+    try:
+        n = 70000
+        for q in range(0, n, 2):
+            _owrite(ep, h, 3, 0, 3, q, 1, 2048, 0)
+            _oatomic(ep, h, 3, 0, 3, q + 1, 1, R)
+        _drain_all(ep, h, 4)
+        assert ep.ep_tail_counters(h, 1, R)[0, 3] == n // 2
+        assert ep.ep_stats(h)["proxy_error"] == 0
+    finally:
+        ep.ep_proxy_stop(h)

@@ -127,3 +127,60 @@ def test_fence_checker_accepts_valid_and_catches_planted_violations(oracle):
     two = [_ev(W, 0, 1, 1, thr=0), _ev(A, 0, 1, 1, thr=1)]
     with pytest.raises(AssertionError, match="two threads"):
         oracle.check_fence_trace(np.array(two, np.uint32), count)
+
+
+def test_order_trace_checker_accepts_valid_and_catches_planted_violations(oracle):
+    WI, AI, WA, AA = (oracle.EV_ORD_WRITE_IN, oracle.EV_ORD_ATOMIC_IN, oracle.EV_ORD_WRITE_APPLIED,
+                      oracle.EV_ORD_ATOMIC_APPLIED)
+    # channel (0,1): atomic 1 arrives before write 0; channel (0,2) in order and independent
+    good = [_ev(AI, 0, 1, 1), _ev(WI, 0, 2, 0), _ev(WA, 0, 2, 0), _ev(WI, 0, 1, 0), _ev(WA, 0, 1, 0),
+            _ev(AA, 0, 1, 1), _ev(AI, 0, 2, 1), _ev(AA, 0, 2, 1)]
+    assert oracle.check_order_trace(np.array(good, np.uint32)) == dict(applied=4, waited=1)
+    # an atomic applied while an earlier message of its channel is still missing
+    early = [_ev(AI, 0, 1, 1), _ev(AA, 0, 1, 1), _ev(WI, 0, 1, 0), _ev(WA, 0, 1, 0)]
+    with pytest.raises(AssertionError, match="out of order"):
+        oracle.check_order_trace(np.array(early, np.uint32))
+    with pytest.raises(AssertionError, match="before it was delivered"):
+        oracle.check_order_trace(np.array([_ev(WA, 0, 1, 0)], np.uint32))
+    with pytest.raises(AssertionError, match="never applied"):
+        oracle.check_order_trace(np.array(good[:5], np.uint32))
+    with pytest.raises(AssertionError, match="delivered twice"):
+        oracle.check_order_trace(np.array([_ev(WI, 0, 1, 0), _ev(WI, 0, 1, 0)], np.uint32))
+    with pytest.raises(AssertionError, match="wrong kind"):
+        oracle.check_order_trace(np.array([_ev(WI, 0, 1, 0), _ev(AA, 0, 1, 0)], np.uint32))
+    # a run that starts later (second dispatch on the same handle)
+    later = [_ev(WI, 0, 1, 6), _ev(WA, 0, 1, 6)]
+    assert oracle.check_order_trace(np.array(later, np.uint32), {(0, 1): 6})["applied"] == 1
+    with pytest.raises(AssertionError):
+        oracle.check_order_trace(np.array(later, np.uint32))
+
+
+def test_ordered_command_checker(oracle):
+    cfg = g.config(1)
+    idx, _ = g.routing(cfg)
+    lay = oracle.layout(idx, cfg.E, cfg.R)
+    rb = oracle.row_bytes(cfg.H, "bf16")
+    log, seq = [], {r: 0 for r in range(cfg.R)}
+    for e in range(cfg.E):
+        c, b = int(lay["count"][0, e]), int(lay["base"][0, e])
+        dr, le = e // cfg.E_loc, e % cfg.E_loc
+        for j in range(0, c, 32):
+            n = min(32, c - j)
+            q = seq[dr]
+            seq[dr] += 2
+            log.append([(1 << 31) | (5 << 28) | (dr << 12) | le, ((n - 1) << 26) | ((n * rb) >> 4), q,
+                        (1 << 31) | (((b + j) * rb) >> 4)])
+            log.append([(1 << 31) | (6 << 28) | (dr << 12), n, q + 1, (1 << 31) | dr])
+    log = np.array(log, np.uint32)
+    assert oracle.check_ordered_cmds(log, lay, 0, cfg.E_loc, rb) == seq
+    bad = log.copy()
+    bad[1, 1] += 1                                               # atomic value != rows of its write
+    with pytest.raises(AssertionError):
+        oracle.check_ordered_cmds(bad, lay, 0, cfg.E_loc, rb)
+    with pytest.raises(AssertionError):
+        oracle.check_ordered_cmds(np.delete(log, [2, 3], axis=0), lay, 0, cfg.E_loc, rb)   # a chunk is missing
+    bad = log.copy()
+    bad[0, 2], bad[2, 2] = bad[2, 2], bad[0, 2]                  # still a permutation of the numbers: allowed
+    if (bad[0, 0] >> 12) & 0xFF == (bad[2, 0] >> 12) & 0xFF:
+        with pytest.raises(AssertionError):                      # ...but then write n is no longer followed by atomic n+1
+            oracle.check_ordered_cmds(bad, lay, 0, cfg.E_loc, rb)
