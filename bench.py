@@ -51,7 +51,7 @@ def read_traffic(kernel_key: str):
 
 
 def run_suite(args) -> int:
-    """Per-call timings of all five workloads (the measurement table of the design doc): layout, dispatch
+    """Per-call timings of all five workloads : layout, dispatch
     with the ring off / per-token / chunk32, FP8 where the workload names it, combine, the command
     rate the proxy sustains with 1 and 4 threads, warm and (small workloads) cold caches."""
     import numpy as np
