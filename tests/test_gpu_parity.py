@@ -699,3 +699,64 @@ def test_dispatch_ordered_chunks(epmod, oracle, cid, T, mask, window, payload):
                 second = seqs[[int(w[2]) >= nxt[int((w[0] >> 12) & 0xFF)] for w in seqs]]
                 oracle.check_ordered_cmds(second, want, 0, cfg.E_loc, rb, first_seq=nxt)
         assert st["device_error"] == 0
+
+
+# ------------------------------------------------------------- limits of the configuration
+@pytest.mark.parametrize("S,T,K,E,R,H", [(1, 100, 64, 1024, 256, 128),      # widest routing the handle accepts
+                                         (2, 37, 16, 1024, 4, 256),
+                                         (1, 5, 2, 4, 2, 65536),            # widest row
+                                         (1, 3, 1, 1, 1, 128),              # smallest everything
+                                         (1, 300000, 1, 8, 8, 128),         # many tokens (4688 tiles)
+                                         (3, 1, 3, 6, 3, 1152)])
+def test_limits_round_trip(epmod, oracle, S, T, K, E, R, H):
+    """Extreme shapes through layout, bf16 and FP8 dispatch (per-token commands), combine."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    cfg = g.EPConfig("limits", T=T, H=H, E=E, K=K, R=R, S=S, seed=777)
+    rng = np.random.default_rng(S * 1000 + K)
+    if K * 4 > E or T > 10000:
+        keys = rng.random((S, T, E)) if T * E < 5e7 else None
+        if keys is None:
+            idx = rng.integers(0, E, size=(S, T, K)).astype(np.int32)         # K = 1: any draw is distinct
+        else:
+            idx = np.argsort(keys, axis=2)[:, :, :K].astype(np.int32)
+        w = rng.random((S, T, K)).astype(np.float32)
+    else:
+        idx, w = g.routing_all(cfg)
+    idx = g.mask_random(idx, 0.05, seed=9)
+    g.validate_routing(idx, E)
+    rows = int((idx >= 0).sum())
+    x = g.f32_to_bf16_bits(rng.normal(0, 1, (T, H)).astype(np.float32))
+    want = oracle.layout(idx, E, R)
+    oracle.set_threads(min(16, oracle.max_threads()))
+    try:
+        with EPRunner(R, E, K, H, T, S=S, spin_timeout_ms=10000, num_channels=64 if T > 10000 else 8,
+                      heap_rows=S * T * K + 1) as r:
+            d_idx, d_x = _dev(idx), bits_to_bf16(x)
+            lay = r.layout(d_idx)
+            recv = torch.zeros((rows + 1, H), dtype=torch.bfloat16, device="cuda")
+            rq = torch.zeros((rows + 1, H), dtype=torch.uint8, device="cuda")
+            rs = torch.zeros((rows + 1, H // 128), dtype=torch.float32, device="cuda")
+            src = S - 1
+            r.dispatch(d_x, d_idx[src], lay, recv, src=src, cmd_mode=epmod.EP_CMD_PER_TOKEN)
+            r.dispatch(d_x, d_idx[src], lay, rq, rs, src=src, payload=epmod.EP_FP8_E4M3,
+                       cmd_mode=epmod.EP_CMD_CHUNK32)
+            out = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+            r.combine(recv, _dev(w[src]), lay.dst_row[src], out)
+            r.wait()
+            torch.cuda.synchronize()
+            got = lay.numpy()
+            for name, v in want.items():
+                assert np.array_equal(got[name], v), name
+            wrecv, _ = oracle.dispatch_bf16(x, idx[src], want["dst_row"][src], E // R, rows + 1, fill=0)
+            assert np.array_equal(bf16_to_bits(recv), wrecv)
+            wq, ws, _ = oracle.dispatch_fp8(x, idx[src], want["dst_row"][src], E // R, rows + 1, fill=0,
+                                            recv_scale=np.zeros((rows + 1, H // 128), np.float32))
+            assert np.array_equal(rq.cpu().numpy(), wq) and np.array_equal(rs.cpu().numpy(), ws)
+            wout = oracle.combine(wrecv, w[src], want["dst_row"][src])
+            assert np.array_equal(bf16_to_bits(out), wout)
+            st = r.stats()
+            assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+            assert st["atomics_applied"] == 2 * E
+            assert np.array_equal(r.counters()[src], want["count"][src])
+    finally:
+        oracle.set_threads(1)
