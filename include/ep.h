@@ -100,12 +100,13 @@ typedef struct ep_config {
   uint64_t reorder_seed;
   int64_t heap_rows;         /* rows of the registered receive heap; 0 = S * max_tokens * K */
   int32_t flags;             /* ep_flags                                               */
-  int32_t reserved;
+  int32_t barrier_peers;     /* processes that take part in Barrier commands (0 or 1: only this one)   */
+  char barrier_name[48];     /* name of the shared-memory barrier the peers of one node agree on; "" = private */
 } ep_config;
 
 typedef struct ep_stats_t {
   uint64_t cmds;             /* commands polled by all proxy threads                   */
-  uint64_t writes, atomics, drains;
+  uint64_t writes, atomics, drains, barriers;
   uint64_t write_bytes;      /* sum of Write lengths                                   */
   uint64_t write_rows;       /* sum of rows carried by Writes                          */
   uint64_t atomics_applied;
@@ -217,6 +218,16 @@ int ep_gather_index(ep_handle *h, const int32_t *d_dst_row, const int32_t *d_dst
 int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, const int32_t *d_dst_row,
                        const int32_t *d_first_k, const int32_t *d_dst_row_g, int32_t T, int64_t y_rows,
                        int64_t rows_g, void *d_partial, void *stream);
+
+/* ep_barrier - enqueues a one-wave kernel that pushes a Barrier command
+ * (Section 3.1, "Types of TransferCmd") and blocks `stream` on
+ * Check-completion of it.  The proxy pops the command only when all
+ * barrier_peers processes that share barrier_name have pushed theirs (the
+ * intra-node level of the paper's barrier: peers meet in shared memory), or
+ * after spin_timeout_ms, in which case the proxy error becomes EP_ETIMEOUT.
+ * The cross-node level (leaders exchanging immediates) needs a network and is
+ * not part of this library. */
+int ep_barrier(ep_handle *h, void *stream);
 
 /* ep_recv_wait - the receiving side's wait, on the GPU (Section 4.1: the GPU
  * observes the host-allocated counters and uses them for control decisions).

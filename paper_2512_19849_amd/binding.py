@@ -43,11 +43,12 @@ class ep_config(C.Structure):
                 ("max_tokens", C.c_int32), ("num_src", C.c_int32), ("self_rank", C.c_int32),
                 ("num_channels", C.c_int32), ("ring_entries", C.c_int32), ("num_proxy_threads", C.c_int32),
                 ("reorder_window", C.c_int32), ("spin_timeout_ms", C.c_int32), ("reorder_seed", C.c_uint64),
-                ("heap_rows", C.c_int64), ("flags", C.c_int32), ("reserved", C.c_int32)]
+                ("heap_rows", C.c_int64), ("flags", C.c_int32), ("barrier_peers", C.c_int32),
+                ("barrier_name", C.c_char * 48)]
 
 
 class ep_stats_t(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in ("cmds", "writes", "atomics", "drains", "write_bytes", "write_rows",
+    _fields_ = [(n, C.c_uint64) for n in ("cmds", "writes", "atomics", "drains", "barriers", "write_bytes", "write_rows",
                                           "atomics_applied", "atomics_deferred", "ordered_parked", "rejected",
                                           "gpu_ring_full",
                                           "first_poll_ns", "last_apply_ns")] + \
@@ -60,7 +61,7 @@ class ep_stats_t(C.Structure):
 
 
 EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
-           "ep_counters", "ep_tail_counters", "ep_dedup", "ep_gather_index", "ep_combine_partial",
+           "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error"]
 
@@ -94,6 +95,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_dispatch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp]
     L.ep_combine.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
     L.ep_wait.argtypes = [vp]
+    L.ep_barrier.argtypes = [vp, vp]
     L.ep_dedup.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     L.ep_gather_index.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
     L.ep_combine_partial.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, vp, vp]
@@ -141,11 +143,11 @@ def _stream(stream) -> Optional[int]:
 def ep_proxy_start(num_ranks: int, num_experts: int, top_k: int, hidden: int, max_tokens: int, num_src: int = 1,
                    self_rank: int = 0, num_channels: int = 8, ring_entries: int = 4096, num_proxy_threads: int = 4,
                    reorder_window: int = 0, reorder_seed: int = 0, spin_timeout_ms: int = 0, heap_rows: int = 0,
-                   flags: int = 0) -> int:
+                   flags: int = 0, barrier_peers: int = 0, barrier_name: str = "") -> int:
     """Returns the opaque handle (an integer address)."""
     cfg = ep_config(num_ranks, num_experts, top_k, hidden, max_tokens, num_src, self_rank, num_channels,
                     ring_entries, num_proxy_threads, reorder_window, spin_timeout_ms, reorder_seed, heap_rows,
-                    flags, 0)
+                    flags, barrier_peers, barrier_name.encode())
     h = C.c_void_p()
     _check("ep_proxy_start", load_library().ep_proxy_start(C.byref(cfg), C.byref(h)))
     return h.value
@@ -189,6 +191,10 @@ def ep_combine_partial(h: int, y, topk_w, dst_row, first_k, dst_row_g, T: int, y
     _check("ep_combine_partial", load_library().ep_combine_partial(h, _ptr(y), _ptr(topk_w), _ptr(dst_row),
                                                                    _ptr(first_k), _ptr(dst_row_g), T, y_rows,
                                                                    rows_g, _ptr(partial), _stream(stream)))
+
+
+def ep_barrier(h: int, stream=None) -> None:
+    _check("ep_barrier", load_library().ep_barrier(h, _stream(stream)))
 
 
 def ep_recv_wait(h: int, src_rank: int, dst_rank_filter: int, counts_out, stream=None) -> None:

@@ -2,6 +2,10 @@
 // multithreaded CPU proxy (sender half + receiver half in one process, since
 // the peer ranks are partitions of this GPU's memory) and the C ABI.
 #include <hip/hip_runtime_api.h>
+#include <fcntl.h>
+#include <sys/mman.h>
+#include <sys/stat.h>
+#include <unistd.h>
 #include <immintrin.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -76,7 +80,7 @@ struct alignas(64) ProxyThread {
   uint64_t rng = 0;
   // statistics (written by the owner thread only, read racy-but-atomically)
   std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
-      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0};
+      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0}, barriers{0};
   std::mutex log_mu;
   std::vector<uint32_t> cmd_log, event_log;
 };
@@ -99,6 +103,15 @@ struct ep_handle {
   int *recv_flag = nullptr;  // posted count + 1, cleared by the GPU-side wait
   int32_t *recv_tail = nullptr;  // [S, R] rows announced per communication channel (ordered mode)
   std::atomic<int64_t> expected_drains{0};
+  // Barrier: a counter and a generation shared by the peer processes of one node
+  struct SharedBarrier {
+    std::atomic<uint32_t> arrived;
+    std::atomic<uint32_t> generation;
+  };
+  SharedBarrier *barrier = nullptr;
+  SharedBarrier private_barrier{};
+  bool barrier_is_shm = false;
+  char barrier_path[64] = "";
   void *d_recv_flag = nullptr;
   int *dev_error = nullptr;
   void *d_recv_count = nullptr;
@@ -340,7 +353,36 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       P.drains.store(P.drains.load(std::memory_order_relaxed) + 1, std::memory_order_release);
       break;
     }
-    default:  // Barrier needs peer processes; not part of this single-GPU build
+    case EP_OP_BARRIER: {
+      // All-peer barrier, intra-node level: peers meet at a counter in shared memory; the one that
+      // completes the count opens the next generation.  The command is popped (and the GPU's
+      // Check-completion turns true) only after the barrier is established.
+      const uint32_t peers = c.barrier_peers > 1 ? (uint32_t)c.barrier_peers : 1u;
+      ep_handle::SharedBarrier *b = h->barrier;
+      const uint32_t gen = b->generation.load(std::memory_order_acquire);
+      if (b->arrived.fetch_add(1, std::memory_order_acq_rel) + 1 == peers) {
+        b->arrived.store(0, std::memory_order_relaxed);
+        b->generation.fetch_add(1, std::memory_order_release);
+      } else {
+        const uint64_t t0 = now_ns();
+        uint64_t spins = 0;
+        while (b->generation.load(std::memory_order_acquire) == gen) {
+          if ((++spins & 255) == 0) {
+            if (now_ns() - t0 > h->timeout_ns || h->stop.load(std::memory_order_relaxed)) {
+              int zero = 0;
+              h->proxy_error.compare_exchange_strong(zero, EP_ETIMEOUT);
+              break;
+            }
+            std::this_thread::yield();
+          } else {
+            _mm_pause();
+          }
+        }
+      }
+      bump(P.barriers, 1);
+      break;
+    }
+    default:
       reject(h, P);
       break;
   }
@@ -411,6 +453,11 @@ int validate(const ep_config &c) {
   if (c.reorder_window < 0 || c.reorder_window > 65536) return EP_EINVAL;
   if (c.spin_timeout_ms < 0 || c.spin_timeout_ms > 60000) return EP_EINVAL;
   if (c.heap_rows < 0) return EP_EINVAL;
+  if (c.barrier_peers < 0 || c.barrier_peers > 1024) return EP_EINVAL;
+  if (memchr(c.barrier_name, 0, sizeof(c.barrier_name)) == nullptr) return EP_EINVAL;
+  for (const char *p = c.barrier_name; *p; ++p)
+    if (*p == '/') return EP_EINVAL;
+  if (c.barrier_peers > 1 && !c.barrier_name[0]) return EP_EINVAL;
   return EP_OK;
 }
 
@@ -434,6 +481,10 @@ void free_all(ep_handle *h) {
                    h->chunk_cnt, h->expert_done, h->ticket, h->waves_done, h->ht_seq};
     for (void *p : dev)
       if (p) (void)hipFree(p);
+  }
+  if (h->barrier_is_shm && h->barrier) {
+    munmap(h->barrier, sizeof(ep_handle::SharedBarrier));
+    shm_unlink(h->barrier_path);  // the name goes; peers that still map the segment keep it
   }
   delete[] h->threads;
   delete h;
@@ -536,6 +587,22 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     return rc;
   }
 
+  h->barrier = &h->private_barrier;
+  if (cfg->barrier_peers > 1) {
+    snprintf(h->barrier_path, sizeof(h->barrier_path), "/ep_barrier_%s", cfg->barrier_name);
+    const int fd = shm_open(h->barrier_path, O_CREAT | O_RDWR, 0600);
+    void *m = MAP_FAILED;
+    if (fd >= 0 && ftruncate(fd, 64) == 0)  // a fresh segment is zero-filled: count 0, generation 0
+      m = mmap(nullptr, sizeof(ep_handle::SharedBarrier), PROT_READ | PROT_WRITE, MAP_SHARED, fd, 0);
+    if (fd >= 0) close(fd);
+    if (m == MAP_FAILED) {
+      snprintf(g_last_error, sizeof(g_last_error), "shared-memory barrier %s could not be mapped", h->barrier_path);
+      free_all(h);
+      return EP_ENOMEM;
+    }
+    h->barrier = (ep_handle::SharedBarrier *)m;
+    h->barrier_is_shm = true;
+  }
   h->nthreads = cfg->num_proxy_threads;
   h->threads = new (std::nothrow) ProxyThread[h->nthreads > 0 ? h->nthreads : 1];
   if (!h->threads) {
@@ -763,6 +830,14 @@ int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, con
   return HIP_OK((hipError_t)launch_combine_partial(a, stream)) ? EP_OK : EP_EHIP;
 }
 
+int ep_barrier(ep_handle *h, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (h->nthreads < 1) return EP_ESTATE;  // nobody would ever pop the command
+  if (int e = dev_err(h)) return e;
+  return HIP_OK((hipError_t)launch_barrier(h->ring, stream)) ? EP_OK : EP_EHIP;
+}
+
 int ep_recv_wait(ep_handle *h, int32_t src_rank, int32_t dst_rank_filter, int32_t *d_counts_out, void *stream) {
   if (!h) return EP_EINVAL;
   if (h->host_only) return EP_ESTATE;
@@ -831,6 +906,7 @@ int ep_stats(ep_handle *h, ep_stats_t *out) {
     out->writes += P.writes.load();
     out->atomics += P.atomics.load();
     out->drains += P.drains.load();
+    out->barriers += P.barriers.load();
     out->write_bytes += P.write_bytes.load();
     out->write_rows += P.write_rows.load();
     out->atomics_applied += P.applied.load();
@@ -861,7 +937,7 @@ int ep_reset_stats(ep_handle *h) {
   for (int i = 0; i < h->nthreads; ++i) {
     ProxyThread &P = h->threads[i];
     for (auto *a : {&P.cmds, &P.writes, &P.atomics, &P.drains, &P.write_bytes, &P.write_rows, &P.applied,
-                    &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns, &P.ordered_parked})
+                    &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns, &P.ordered_parked, &P.barriers})
       a->store(0);
     std::lock_guard<std::mutex> g(P.log_mu);
     P.cmd_log.clear();

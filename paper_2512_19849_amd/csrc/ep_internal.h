@@ -125,6 +125,7 @@ int launch_layout(const LayoutArgs &a, void *stream);
 int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
 int launch_combine(const CombineArgs &a, void *stream);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
+int launch_barrier(const RingDev &ring, void *stream);
 int launch_dedup(const DedupArgs &a, void *stream);
 int launch_gather_index(const GatherIndexArgs &a, void *stream);
 int launch_combine_partial(const CombinePartialArgs &a, void *stream);

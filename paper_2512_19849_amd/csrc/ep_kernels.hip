@@ -972,6 +972,20 @@ int launch_combine_partial(const CombinePartialArgs &a0, void *stream) {
   return (int)hipGetLastError();
 }
 
+// ---------------------------------------------------------------- barrier
+// One lane pushes a Barrier on channel 0 and blocks on Check-completion: the proxy pops it only
+// when every peer process has entered (Section 3.1: Barrier is blocking on the GPU side).
+__global__ void barrier_kernel(RingDev ring) {
+  if (threadIdx.x != 0) return;
+  const unsigned long long idx = ring_push(ring, 0, cmd_w0(EP_OP_BARRIER, 0, 0, 0), 0u, 0u, 0u);
+  if (idx != ~0ull) ring_wait_completion(ring, 0, idx);
+}
+
+int launch_barrier(const RingDev &ring, void *stream) {
+  hipLaunchKernelGGL(barrier_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, ring);
+  return (int)hipGetLastError();
+}
+
 // ------------------------------------------------------------ receive wait
 // One thread per expert polls its arrival flag in pinned host memory with
 // system-scope loads (each poll is a PCIe read, so lanes sleep between polls),

@@ -42,7 +42,7 @@ class EPRunner:
     def __init__(self, R: int, E: int, K: int, H: int, max_tokens: int, S: int = 1, self_rank: int = 0,
                  num_channels: int = 8, ring_entries: int = 4096, num_proxy_threads: int = 4,
                  reorder_window: int = 0, reorder_seed: int = 0, spin_timeout_ms: int = 0, heap_rows: int = 0,
-                 flags: int = 0, device: str = "cuda"):
+                 flags: int = 0, device: str = "cuda", barrier_peers: int = 0, barrier_name: str = ""):
         if not torch.cuda.is_available():
             raise RuntimeError("EPRunner needs a HIP device; there is no CPU path")
         self.R, self.E, self.K, self.H, self.S, self.T_cap = R, E, K, H, S, max_tokens
@@ -51,7 +51,7 @@ class EPRunner:
         self.heap_rows = heap_rows or S * max_tokens * K
         self.h = ep.ep_proxy_start(R, E, K, H, max_tokens, S, self_rank, num_channels, ring_entries,
                                    num_proxy_threads, reorder_window, reorder_seed, spin_timeout_ms, heap_rows,
-                                   flags)
+                                   flags, barrier_peers, barrier_name)
         i32 = dict(dtype=torch.int32, device=self.dev)
         self.lay = LayoutOut(
             count=torch.zeros((S, E), **i32), expert_total=torch.zeros(E, **i32), rank_total=torch.zeros(R, **i32),

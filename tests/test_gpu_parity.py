@@ -760,3 +760,57 @@ def test_limits_round_trip(epmod, oracle, S, T, K, E, R, H):
             assert np.array_equal(r.counters()[src], want["count"][src])
     finally:
         oracle.set_threads(1)
+
+
+# ---------------------------------------------------------------------------- Barrier
+def _cpu_barrier_peer(name, delay, q):
+    import time as _t
+    import paper_2512_19849_amd as ep_
+    h = ep_.ep_proxy_start(4, 16, 2, 1024, 64, num_channels=1, ring_entries=8, num_proxy_threads=1,
+                           spin_timeout_ms=20000, flags=ep_.EP_FLAG_HOST_ONLY, barrier_peers=2, barrier_name=name)
+    try:
+        q.put("ready")
+        _t.sleep(delay)
+        t_push = _t.time()
+        i = ep_.ep_host_push(h, 0, 4 << 28, 0, 0, 0)
+        while not ep_.ep_host_check_completion(h, 0, i):
+            _t.sleep(0.0005)
+        q.put((t_push, _t.time(), ep_.ep_stats(h)["proxy_error"]))
+    finally:
+        ep_.ep_proxy_stop(h)
+
+
+def test_barrier_kernel_waits_for_a_peer_process(epmod):
+    """ep_barrier on the GPU: the stream is held until a second process (a CPU-side
+    peer with its own proxy) has pushed its Barrier too."""
+    import multiprocessing as mp
+    import os
+    import time
+    from paper_2512_19849_amd.runner import EPRunner
+    with EPRunner(4, 16, 2, 1024, 64, spin_timeout_ms=3000) as r:         # alone: completes at once
+        epmod.ep_barrier(r.h)
+        torch.cuda.synchronize()
+        st = r.stats()
+        assert st["barriers"] == 1 and st["device_error"] == 0 and st["proxy_error"] == 0
+    ctx = mp.get_context("spawn")
+    name = f"g{os.getpid()}"
+    q = ctx.Queue()
+    child = ctx.Process(target=_cpu_barrier_peer, args=(name, 0.3, q))
+    child.start()
+    try:
+        with EPRunner(4, 16, 2, 1024, 64, spin_timeout_ms=20000, barrier_peers=2, barrier_name=name) as r:
+            assert q.get(timeout=60) == "ready"
+            torch.cuda.synchronize()
+            t0 = time.time()
+            epmod.ep_barrier(r.h)
+            torch.cuda.synchronize()
+            t1 = time.time()
+            p_push, p_done, p_err = q.get(timeout=30)
+            assert p_err == 0 and t1 >= p_push - 1e-3 and t1 - t0 > 0.15   # held until the peer arrived
+            st = r.stats()
+            assert st["barriers"] == 1 and st["device_error"] == 0 and st["proxy_error"] == 0
+        child.join(timeout=30)
+        assert child.exitcode == 0
+    finally:
+        if child.is_alive():
+            child.terminate()

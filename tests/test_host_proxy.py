@@ -186,7 +186,7 @@ def test_bounds_check_rejects_bad_commands(ep):
             (_w0(1, 0, 0, 4), 2048 >> 4, 0, 0),                           # local expert 4 of 4
             (_w0(2, 0, 1, 2), 5, 0, 3),                                   # atomic whose counter index is not src*E_loc+le
             (_w0(2, 0, 1, 2), 1 << 19, 0, 2),                             # atomic value too large for the immediate
-            (_w0(4, 0, 0, 0), 0, 0, 0),                                   # Barrier: no peers in this build
+            (_w0(7, 0, 0, 0), 0, 0, 0),                                   # no such command type
         ]
         for w in bad:
             ep.ep_host_push(h, 0, *w)
@@ -392,3 +392,91 @@ def test_partial_ordering_sequence_numbers_wrap_16_bits(ep, oracle):
         assert ep.ep_stats(h)["proxy_error"] == 0
     finally:
         ep.ep_proxy_stop(h)
+
+
+# ------------------------------------------------------------------- Barrier across processes
+def _barrier_peer(name, delay, rounds, q):
+    """Child process: its own handle and proxy; pushes `rounds` Barrier commands."""
+    import time as _t
+    import paper_2512_19849_amd as ep_
+    h = ep_.ep_proxy_start(4, 16, 2, 1024, 64, num_channels=1, ring_entries=8, num_proxy_threads=1,
+                           spin_timeout_ms=5000, flags=ep_.EP_FLAG_HOST_ONLY, barrier_peers=2, barrier_name=name)
+    out = []
+    try:
+        for r in range(rounds):
+            _t.sleep(delay)
+            t_push = _t.time()
+            i = ep_.ep_host_push(h, 0, 4 << 28, 0, 0, 0)
+            while not ep_.ep_host_check_completion(h, 0, i):
+                _t.sleep(0.0005)
+            out.append((t_push, _t.time()))
+        st = ep_.ep_stats(h)
+        q.put((out, st["barriers"], st["proxy_error"]))
+    finally:
+        ep_.ep_proxy_stop(h)
+
+
+def test_barrier_releases_only_when_every_peer_process_has_entered(ep):
+    """Two processes share a named barrier: a Barrier command is popped only after
+    both proxies have received one; three generations in a row."""
+    import multiprocessing as mp
+    ctx = mp.get_context("spawn")
+    name = f"t{os.getpid()}"
+    q = ctx.Queue()
+    rounds, delay = 3, 0.25
+    child = ctx.Process(target=_barrier_peer, args=(name, delay, rounds, q))
+    child.start()
+    h = _start(ep, num_channels=1, num_proxy_threads=1, num_src=1, barrier_peers=2, barrier_name=name,
+               spin_timeout_ms=20000)
+    try:
+        mine = []
+        for r in range(rounds):
+            t_push = time.time()
+            i = ep.ep_host_push(h, 0, _w0(4, 0, 0, 0), 0, 0, 0)
+            time.sleep(0.05)
+            deadline = time.time() + 20
+            while not ep.ep_host_check_completion(h, 0, i):
+                assert time.time() < deadline
+                time.sleep(0.0005)
+            mine.append((t_push, time.time()))
+        theirs, nbar, perr = q.get(timeout=30)
+        child.join(timeout=30)
+        assert child.exitcode == 0 and nbar == rounds and perr == 0
+        st = ep.ep_stats(h)
+        assert st["barriers"] == rounds and st["proxy_error"] == 0
+        for (p0, d0), (p1, d1) in zip(mine, theirs):
+            # nobody leaves before the later of the two pushes
+            assert min(d0, d1) >= max(p0, p1) - 1e-3
+        # the parent always pushes first and must have been held for about the child's delay
+        assert all(d - p > 0.1 for p, d in mine[1:])
+    finally:
+        ep.ep_proxy_stop(h)
+        if child.is_alive():
+            child.terminate()
+
+
+def test_barrier_alone_and_timeout(ep):
+    h = _start(ep, num_channels=1, num_proxy_threads=1, num_src=1)          # no peers: trivially satisfied
+    try:
+        i = ep.ep_host_push(h, 0, _w0(4, 0, 0, 0), 0, 0, 0)
+        deadline = time.time() + 5
+        while not ep.ep_host_check_completion(h, 0, i):
+            assert time.time() < deadline
+        assert ep.ep_stats(h)["barriers"] == 1
+    finally:
+        ep.ep_proxy_stop(h)
+    h = _start(ep, num_channels=1, num_proxy_threads=1, num_src=1, barrier_peers=2,
+               barrier_name=f"lonely{os.getpid()}", spin_timeout_ms=100)
+    try:
+        t0 = time.time()
+        i = ep.ep_host_push(h, 0, _w0(4, 0, 0, 0), 0, 0, 0)
+        while not ep.ep_host_check_completion(h, 0, i):
+            assert time.time() - t0 < 5
+        assert time.time() - t0 >= 0.09                                    # held for the bound, then given up
+        assert ep.ep_stats(h)["proxy_error"] == ep.EP_ETIMEOUT
+    finally:
+        ep.ep_proxy_stop(h)
+    with pytest.raises(ep.EPError):
+        _start(ep, barrier_peers=2, barrier_name="")                       # peers need a name
+    with pytest.raises(ep.EPError):
+        _start(ep, barrier_peers=2, barrier_name="a/b")
