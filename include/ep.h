@@ -284,6 +284,13 @@ int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx);
  * (ep_dispatch does this itself for its own). */
 int ep_host_expect_atomics(ep_handle *h, int32_t n);
 
+/* ep_bw_probe - plain streaming kernels for measuring this device's bandwidth
+ * ceilings next to the path's kernels (no part of the method): kind 0 reads
+ * `bytes` from d_src (16-byte non-temporal loads, one per lane), kind 1 writes
+ * `bytes` to d_dst, kind 2 copies d_src to d_dst.  bytes must be a multiple of
+ * 16; buffers are caller-owned device memory.  Needs no handle. */
+int ep_bw_probe(int32_t kind, const void *d_src, void *d_dst, int64_t bytes, void *stream);
+
 /* ep_last_error - text describing the most recent failed HIP runtime call made
  * by the library on the calling thread ("" if none).  Static storage. */
 const char *ep_last_error(void);

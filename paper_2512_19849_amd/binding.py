@@ -63,7 +63,7 @@ class ep_stats_t(C.Structure):
 EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
-           "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error"]
+           "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe"]
 
 _lib = None
 
@@ -109,6 +109,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_host_push.argtypes = [vp, i32, u32, u32, u32, u32, C.POINTER(u64)]
     L.ep_host_check_completion.argtypes = [vp, i32, u64]
     L.ep_host_expect_atomics.argtypes = [vp, i32]
+    L.ep_bw_probe.argtypes = [i32, vp, vp, i64, vp]
     for name in EXPORTS:
         getattr(L, name).restype = C.c_int
     L.ep_last_error.argtypes = []
@@ -263,6 +264,11 @@ def ep_host_check_completion(h: int, channel: int, idx: int) -> bool:
     if rc < 0:
         raise EPError("ep_host_check_completion", rc)
     return bool(rc)
+
+
+def ep_bw_probe(kind: int, src, dst, nbytes: int, stream=None) -> None:
+    """kind 0 read src, 1 write dst, 2 copy src -> dst (plain streaming kernels, for ceilings)."""
+    _check("ep_bw_probe", load_library().ep_bw_probe(kind, _ptr(src), _ptr(dst), nbytes, _stream(stream)))
 
 
 def ep_last_error() -> str:

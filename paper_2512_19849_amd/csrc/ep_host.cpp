@@ -1014,6 +1014,14 @@ int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx) {
 
 const char *ep_last_error(void) { return g_last_error; }
 
+int ep_bw_probe(int32_t kind, const void *d_src, void *d_dst, int64_t bytes, void *stream) {
+  if (kind < 0 || kind > 2 || bytes < 0 || (bytes & 15)) return EP_EINVAL;
+  if (bytes >> 36) return EP_EINVAL;  // grid index range
+  if ((kind != 1 && !d_src) || !d_dst) return EP_EINVAL;  // kind 0 uses d_dst as a 16-byte sink
+  if (((uintptr_t)d_src | (uintptr_t)d_dst) & 15) return EP_EINVAL;
+  return HIP_OK((hipError_t)launch_bw_probe(kind, d_src, d_dst, bytes, stream)) ? EP_OK : EP_EHIP;
+}
+
 int ep_host_expect_atomics(ep_handle *h, int32_t n) {
   if (!h || n < 0) return EP_EINVAL;
   h->expected_atomics.fetch_add(n, std::memory_order_relaxed);

@@ -130,6 +130,7 @@ int launch_dedup(const DedupArgs &a, void *stream);
 int launch_gather_index(const GatherIndexArgs &a, void *stream);
 int launch_combine_partial(const CombinePartialArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
+int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void *stream);
 
 // Tunables (read once from the environment, for sweeps): vectors per lane.
 int tuned_dispatch_vpl(int H, int T);

@@ -1026,6 +1026,33 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, long long n) {
   if (i < n) p[i] = v;
 }
 
+// Bandwidth probes: one 16-byte access per lane, one short wave per KiB (measured best shape).
+__global__ __launch_bounds__(256) void bw_read_kernel(const u32x4 *p, long long n, u32x4 *sink) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const u32x4 v = __builtin_nontemporal_load(p + i);
+  if (v[0] == 0x9E3779B9u && v[1] == 0x7F4A7C15u && v[2] == 0xBF58476Du && v[3] == 0x1CE4E5B9u) *sink = v;
+}
+__global__ __launch_bounds__(256) void bw_write_kernel(u32x4 *p, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = u32x4{1u, 2u, 3u, (unsigned)i};
+}
+__global__ __launch_bounds__(256) void bw_copy_kernel(const u32x4 *s, u32x4 *d, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) d[i] = __builtin_nontemporal_load(s + i);
+}
+
+int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void *stream) {
+  const long long n = bytes / 16;
+  if (n <= 0) return 0;
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  hipStream_t st = (hipStream_t)stream;
+  if (kind == 0) hipLaunchKernelGGL(bw_read_kernel, grid, block, 0, st, (const u32x4 *)src, n, (u32x4 *)dst);
+  else if (kind == 1) hipLaunchKernelGGL(bw_write_kernel, grid, block, 0, st, (u32x4 *)dst, n);
+  else hipLaunchKernelGGL(bw_copy_kernel, grid, block, 0, st, (const u32x4 *)src, (u32x4 *)dst, n);
+  return (int)hipGetLastError();
+}
+
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream) {
   if (n <= 0) return 0;
   hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, p, v, n);
