@@ -377,7 +377,7 @@ EP_DEV void emit_leading_atomics(const DispatchArgs &a, int lane) {
 }
 
 // Called by the lanes holding a dispatched (t,k) after the token's rows are
-// stored and released at device scope.  LL granularity: one Write per row.
+// stored and acknowledged (write-through, so they are in memory).  LL granularity: one Write per row.
 // Chunk granularity: the lane that completes a run of <= 32 consecutive rows of
 // an expert pushes the Write for the run.  Whoever completes the expert pushes
 // its count Atomic (Section 3.3: the receiver holds it until that many rows
