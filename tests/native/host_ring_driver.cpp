@@ -1,0 +1,63 @@
+// Stand-alone driver for the host side of the library (ring + proxy threads) with several
+// producer threads, built with ThreadSanitizer / AddressSanitizer by tests/test_host_sanitizers.py.
+// The kernel launchers are stubbed: a host-only handle never calls them.
+#include "../../include/ep.h"
+#include "../../paper_2512_19849_amd/csrc/ep_internal.h"
+#include <cstdio>
+#include <thread>
+#include <vector>
+namespace ep {
+int launch_layout(const LayoutArgs&, void*) { return 0; }
+int launch_dispatch(const DispatchArgs&, int, void*) { return 0; }
+int launch_combine(const CombineArgs&, void*) { return 0; }
+int launch_fill_u32(uint32_t*, uint32_t, long long, void*) { return 0; }
+int tuned_dispatch_vpl(int, int) { return 1; }
+int tuned_combine_vpl(int) { return 1; }
+int launch_recv_wait(const RecvWaitArgs&, void*) { return 0; }
+int launch_barrier(const RingDev&, void*) { return 0; }
+int launch_dedup(const DedupArgs&, void*) { return 0; }
+int launch_gather_index(const GatherIndexArgs&, void*) { return 0; }
+int launch_combine_partial(const CombinePartialArgs&, void*) { return 0; }
+int launch_bw_probe(int, const void*, void*, long long, void*) { return 0; }
+}
+static uint32_t w0(uint32_t op, uint32_t src, uint32_t dr, uint32_t le) { return (op << 28) | (src << 20) | (dr << 12) | le; }
+int main() {
+  ep_config c{}; c.num_ranks = 4; c.num_experts = 16; c.top_k = 2; c.hidden = 1024; c.max_tokens = 4096; c.num_src = 1;
+  c.num_channels = 4; c.ring_entries = 16; c.num_proxy_threads = 2; c.reorder_window = 8; c.reorder_seed = 3;
+  c.spin_timeout_ms = 5000; c.flags = EP_FLAG_HOST_ONLY | EP_FLAG_LOG_CMDS | EP_FLAG_LOG_EVENTS;
+  ep_handle* h = nullptr;
+  if (ep_proxy_start(&c, &h)) { printf("start failed\n"); return 1; }
+  const int per = 500;
+  for (int rep = 0; rep < 3; ++rep) {
+    ep_host_expect_atomics(h, 16);
+    std::vector<std::thread> ts;
+    for (int p = 0; p < 4; ++p) ts.emplace_back([&, p] {
+      for (int e = p; e < 16; e += 4) {
+        uint32_t dr = e / 4, le = e % 4; uint64_t idx;
+        ep_host_push(h, e % 4, w0(2, 0, dr, le), per, 0, le, &idx);
+        for (int i = 0; i < per; ++i) ep_host_push(h, e % 4, w0(1, 0, dr, le), 2048 >> 4, 0, i * 128, &idx);
+      }
+    });
+    for (auto& t : ts) t.join();
+    // sequenced messages of one communication channel pushed by two threads in interleaved order
+    std::thread o1([&] { for (uint32_t q = 0; q < 400; q += 4) { uint64_t i; ep_host_push(h, 1, w0(5, 0, 1, 0), 2048 >> 4, rep * 400 + q, 0, &i); ep_host_push(h, 1, w0(6, 0, 1, 0), 1, rep * 400 + q + 1, 1, &i); } });
+    std::thread o2([&] { for (uint32_t q = 2; q < 400; q += 4) { uint64_t i; ep_host_push(h, 1, w0(5, 0, 1, 0), 2048 >> 4, rep * 400 + q, 0, &i); ep_host_push(h, 1, w0(6, 0, 1, 0), 1, rep * 400 + q + 1, 1, &i); } });
+    o1.join(); o2.join();
+    uint64_t di[4];
+    for (int c2 = 0; c2 < 4; ++c2) ep_host_push(h, c2, w0(3, 0, 0, 0), 0, 0, 0, &di[c2]);
+    uint64_t bi; ep_host_push(h, 0, w0(4, 0, 0, 0), 0, 0, 0, &bi);
+    while (!ep_host_check_completion(h, 0, bi)) std::this_thread::yield();
+    for (int c2 = 0; c2 < 4; ++c2) while (!ep_host_check_completion(h, c2, di[c2])) std::this_thread::yield();
+    int rc = ep_wait(h);
+    ep_stats_t st; ep_stats(h, &st);
+    size_t n = 0; ep_cmd_log(h, nullptr, 0, &n);
+    const int32_t *tails = nullptr; ep_tail_counters(h, &tails);
+    printf("rep %d rc %d cmds %lu applied %lu deferred %lu parked %lu barriers %lu tail %d log %zu\n", rep, rc,
+           (unsigned long)st.cmds, (unsigned long)st.atomics_applied, (unsigned long)st.atomics_deferred,
+           (unsigned long)st.ordered_parked, (unsigned long)st.barriers, tails[1], n);
+    if (rc != 0 || st.atomics_applied != 16 || tails[1] != 200 || st.proxy_error != 0) return 2;
+    ep_reset_stats(h);
+  }
+  ep_proxy_stop(h);
+  return 0;
+}
