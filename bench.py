@@ -152,6 +152,28 @@ def run_suite(args) -> int:
                         rr[f"dispatch_fp8_{mode}_us"] = timed(
                             lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3, cmd_mode=cm),
                             after=r.wait)
+                if threads == 4:
+                    # the proxy performs the writes (registered heaps): per token straight out of x,
+                    # chunks out of a packed send heap; host clock from launch to the last counter
+                    send = torch.zeros((rows, H), dtype=torch.bfloat16, device="cuda")
+                    for mode, src_heap, tgt, flag in (("per_token", d_x, recv, ep.EP_CMD_NO_PLACEMENT),
+                                                      ("chunk32", send, send, 0),
+                                                      ("chunk32_ordered", send, send, 0)):
+                        r.register_heaps(src_heap, recv)
+                        cm = ep.CMD_MODES[mode] | flag
+                        e2e = []
+                        for _ in range(13):
+                            torch.cuda.synchronize()
+                            t0 = time.perf_counter()
+                            r.dispatch(d_x, d_idx[0], lay, tgt, cmd_mode=cm)
+                            r.wait()
+                            e2e.append((time.perf_counter() - t0) * 1e6)
+                        e2e = sorted(e2e[3:])
+                        rr[f"proxy_writes_{mode}_launch_to_last_counter_us"] = round(e2e[len(e2e) // 2], 1)
+                    st = r.stats()
+                    rr["proxy_writes_copy_batches_per_dispatch"] = round(st["copy_batches"] / 39, 1)
+                    r.register_heaps(None, None)
+                    del send
                 res[key] = rr
         if cid in (4, 5):
             # high-throughput mode: one copy per (token, group), partial reduce per group, final reduce

@@ -75,7 +75,10 @@ enum ep_cmd_mode {
                                  Always ends with a Drain on every FIFO (EP_CMD_DRAIN is implied).          */
   EP_CMD_MODE_MASK = 0xFF,
   EP_CMD_ATOMICS_FIRST = 0x100, /* push every count Atomic before any Write (forces the fence path) */
-  EP_CMD_DRAIN = 0x200          /* last wave pushes Drain on every channel and blocks on Check-completion */
+  EP_CMD_DRAIN = 0x200,         /* last wave pushes Drain on every channel and blocks on Check-completion */
+  EP_CMD_NO_PLACEMENT = 0x400   /* EP_CMD_PER_TOKEN + EP_BF16 only: the kernel stores no payload, it only pushes
+                                   the commands; the proxy moves the rows (needs ep_register_heaps with the
+                                   source heap = d_x).  The low-latency mode as the paper runs it. */
 };
 
 enum ep_flags {
@@ -113,6 +116,8 @@ typedef struct ep_stats_t {
   uint64_t atomics_deferred; /* atomics that had to wait in the control buffer         */
   uint64_t ordered_parked;   /* sequenced messages that arrived ahead of their turn    */
   uint64_t rejected;         /* commands that failed offset translation / bounds check */
+  uint64_t copy_batches;     /* batched copy launches made by the proxy (registered heaps) */
+  uint64_t copied_bytes;     /* bytes the proxy moved                                   */
   uint64_t gpu_ring_full;    /* times a GPU push saw "full" in its cached head and re-read the head over PCIe */
   uint64_t first_poll_ns;    /* CLOCK_MONOTONIC of the first command seen since ep_reset_stats */
   uint64_t last_apply_ns;    /* ... and of the last atomic applied                     */
@@ -218,6 +223,22 @@ int ep_gather_index(ep_handle *h, const int32_t *d_dst_row, const int32_t *d_dst
 int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, const int32_t *d_dst_row,
                        const int32_t *d_first_k, const int32_t *d_dst_row_g, int32_t T, int64_t y_rows,
                        int64_t rows_g, void *d_partial, void *stream);
+
+/* ep_register_heaps - symmetric-memory registration (Section 3.2): gives the
+ * proxy the device base addresses and sizes of the source-side heap (what Write
+ * commands' source offsets are relative to) and of the destination-side receive
+ * heap.  While heaps are registered the proxy PERFORMS every Write command it
+ * polls: after translating and bounds-checking the offsets it copies `length`
+ * bytes from source heap + source offset to destination heap + destination
+ * offset (batched copy kernels on the proxy thread's own stream, standing in
+ * for the RDMA writes), and only when a batch has completed does it hand the
+ * writes' immediates to the receiver half.  Count Atomics keep flowing at once,
+ * so they regularly overtake their data and wait in the control buffer.
+ *   chunk modes : ep_dispatch packs rows into the source heap (pass it as
+ *                 d_recv); a chunk's source offset equals its destination offset.
+ *   per-token   : with EP_CMD_NO_PLACEMENT the source heap is d_x itself.
+ * Call it only while no dispatch is in flight; NULL bases unregister. */
+int ep_register_heaps(ep_handle *h, const void *d_src_base, int64_t src_bytes, void *d_dst_base, int64_t dst_bytes);
 
 /* ep_barrier - enqueues a one-wave kernel that pushes a Barrier command
  * (Section 3.1, "Types of TransferCmd") and blocks `stream` on

@@ -18,7 +18,7 @@ from . import build as _build
 EP_OK, EP_EINVAL, EP_ENOMEM, EP_ESTATE, EP_EHIP, EP_ETIMEOUT, EP_EBOUNDS = 0, -1, -2, -3, -4, -5, -6
 EP_BF16, EP_FP8_E4M3 = 0, 1
 EP_CMD_PER_TOKEN, EP_CMD_CHUNK32, EP_CMD_NONE, EP_CMD_CHUNK32_ORDERED = 0, 1, 2, 3
-EP_CMD_ATOMICS_FIRST, EP_CMD_DRAIN = 0x100, 0x200
+EP_CMD_ATOMICS_FIRST, EP_CMD_DRAIN, EP_CMD_NO_PLACEMENT = 0x100, 0x200, 0x400
 EP_FLAG_LOG_CMDS, EP_FLAG_LOG_EVENTS, EP_FLAG_HOST_ONLY = 1, 2, 4
 EP_OP_WRITE, EP_OP_ATOMIC, EP_OP_DRAIN, EP_OP_BARRIER, EP_OP_ORDERED_WRITE, EP_OP_ORDERED_ATOMIC = 1, 2, 3, 4, 5, 6
 
@@ -50,7 +50,7 @@ class ep_config(C.Structure):
 class ep_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("cmds", "writes", "atomics", "drains", "barriers", "write_bytes", "write_rows",
                                           "atomics_applied", "atomics_deferred", "ordered_parked", "rejected",
-                                          "gpu_ring_full",
+                                          "copy_batches", "copied_bytes", "gpu_ring_full",
                                           "first_poll_ns", "last_apply_ns")] + \
                [("per_thread_cmds", C.c_uint64 * 16), ("device_error", C.c_int32), ("proxy_error", C.c_int32)]
 
@@ -63,7 +63,8 @@ class ep_stats_t(C.Structure):
 EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
-           "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe"]
+           "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
+           "ep_register_heaps"]
 
 _lib = None
 
@@ -110,6 +111,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_host_check_completion.argtypes = [vp, i32, u64]
     L.ep_host_expect_atomics.argtypes = [vp, i32]
     L.ep_bw_probe.argtypes = [i32, vp, vp, i64, vp]
+    L.ep_register_heaps.argtypes = [vp, vp, i64, vp, i64]
     for name in EXPORTS:
         getattr(L, name).restype = C.c_int
     L.ep_last_error.argtypes = []
@@ -192,6 +194,12 @@ def ep_combine_partial(h: int, y, topk_w, dst_row, first_k, dst_row_g, T: int, y
     _check("ep_combine_partial", load_library().ep_combine_partial(h, _ptr(y), _ptr(topk_w), _ptr(dst_row),
                                                                    _ptr(first_k), _ptr(dst_row_g), T, y_rows,
                                                                    rows_g, _ptr(partial), _stream(stream)))
+
+
+def ep_register_heaps(h: int, src, dst) -> None:
+    """src/dst: device tensors spanning the source-side and destination-side heaps, or None/None to unregister."""
+    nbytes = lambda t: 0 if t is None else t.numel() * t.element_size()
+    _check("ep_register_heaps", load_library().ep_register_heaps(h, _ptr(src), nbytes(src), _ptr(dst), nbytes(dst)))
 
 
 def ep_barrier(h: int, stream=None) -> None:

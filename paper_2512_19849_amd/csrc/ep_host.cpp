@@ -74,13 +74,28 @@ struct alignas(64) ProxyThread {
   std::vector<int32_t> seen;
   std::vector<std::deque<int32_t>> parked;  // the control buffer
   std::vector<WireEvent> window;            // in-flight immediates (reordering hook)
+  // proxy-performed peer writes (registered heaps): descriptors of the batch being filled, and the
+  // batches in flight with the arrival notices they will release when their copy kernel is done
+  static constexpr int kBatchSlots = 32;
+  hipStream_t stream = nullptr;
+  hipEvent_t events[kBatchSlots] = {};
+  CopyBatchArgs cur{};
+  struct Batch {
+    int slot;
+    std::vector<WireEvent> notices;
+  };
+  std::deque<Batch> inflight;
+  std::vector<WireEvent> cur_notices;
+  int cur_slot = 0;
+  bool gpu_ready = false;
   // ordered (high-throughput) channels: next sequence number and early arrivals per (source, destination rank)
   std::vector<uint32_t> next_seq;
   std::vector<std::map<uint32_t, WireEvent>> early;
   uint64_t rng = 0;
   // statistics (written by the owner thread only, read racy-but-atomically)
   std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
-      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0}, barriers{0};
+      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0}, barriers{0},
+      copy_batches{0}, copied_bytes{0};
   std::mutex log_mu;
   std::vector<uint32_t> cmd_log, event_log;
 };
@@ -103,6 +118,11 @@ struct ep_handle {
   int *recv_flag = nullptr;  // posted count + 1, cleared by the GPU-side wait
   int32_t *recv_tail = nullptr;  // [S, R] rows announced per communication channel (ordered mode)
   std::atomic<int64_t> expected_drains{0};
+  // registered heaps (symmetric memory): when set, the proxy performs the Writes
+  std::atomic<const char *> src_base{nullptr};
+  std::atomic<char *> dst_base{nullptr};
+  uint64_t src_bytes = 0, dst_bytes = 0;
+  int device = 0;
   // Barrier: a counter and a generation shared by the peer processes of one node
   struct SharedBarrier {
     std::atomic<uint32_t> arrived;
@@ -264,6 +284,57 @@ void flush_window(ep_handle *h, ProxyThread &P) {
   }
 }
 
+// ---- peer writes performed by the proxy ------------------------------------------------------
+void fail_hip(ep_handle *h) {
+  int zero = 0;
+  h->proxy_error.compare_exchange_strong(zero, EP_EHIP);
+}
+
+// Hands the batch being filled to the device: one copy kernel on this thread's stream, an event
+// behind it.  Its notices stay with the batch until the event has fired.
+void launch_batch(ep_handle *h, ProxyThread &P) {
+  if (P.cur.n == 0) return;
+  if (launch_copy_batch(P.cur, P.stream) != 0 ||
+      hipEventRecord(P.events[P.cur_slot], P.stream) != hipSuccess)
+    fail_hip(h);
+  bump(P.copy_batches, 1);
+  P.inflight.push_back(ProxyThread::Batch{P.cur_slot, std::move(P.cur_notices)});
+  P.cur_notices.clear();
+  P.cur.n = 0;
+  P.cur.max_len16 = 0;
+  P.cur_slot = (P.cur_slot + 1) % ProxyThread::kBatchSlots;
+}
+
+// Completion polling (the stand-in for polling the send completion queue): batches finish in
+// order; a finished batch releases its arrival notices to the receiver half.
+enum ReapMode { kReapReady, kReapOne, kReapAll };
+void reap_batches(ep_handle *h, ProxyThread &P, ReapMode mode) {
+  while (!P.inflight.empty()) {
+    ProxyThread::Batch &b = P.inflight.front();
+    hipError_t e = mode == kReapReady ? hipEventQuery(P.events[b.slot]) : hipEventSynchronize(P.events[b.slot]);
+    if (e == hipErrorNotReady) return;
+    if (e != hipSuccess) fail_hip(h);
+    for (const WireEvent &ev : b.notices) transmit(h, P, ev);
+    P.inflight.pop_front();
+    if (mode == kReapOne) return;
+  }
+}
+
+// Offsets and length are bytes relative to the registered heaps, multiples of 16 below 64 GiB.
+void queue_copy(ep_handle *h, ProxyThread &P, const char *sbase, char *dbase, uint64_t so, uint64_t dof,
+                uint64_t len, const WireEvent &notice) {
+  if (P.cur.n && (P.cur.src_base != sbase || P.cur.dst_base != dbase)) launch_batch(h, P);  // re-registered
+  // the event about to be used must not belong to a batch still in flight
+  while (P.cur.n == 0 && (int)P.inflight.size() >= ProxyThread::kBatchSlots - 1) reap_batches(h, P, kReapOne);
+  P.cur.src_base = sbase;
+  P.cur.dst_base = dbase;
+  P.cur.d[P.cur.n] = CopyBatchArgs::Desc{(unsigned)(so >> 4), (unsigned)(dof >> 4), (unsigned)(len >> 4)};
+  P.cur_notices.push_back(notice);
+  if ((unsigned)(len >> 4) > P.cur.max_len16) P.cur.max_len16 = (unsigned)(len >> 4);
+  bump(P.copied_bytes, len);
+  if (++P.cur.n == kCopyBatchMax) launch_batch(h, P);
+}
+
 void reject(ep_handle *h, ProxyThread &P) {
   bump(P.rejected, 1);
   int zero = 0;
@@ -289,18 +360,27 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       const uint64_t len = (uint64_t)(w1 & 0x3FFFFFFu) << 4;
       const uint32_t rows = (w1 >> 26) + 1;
       const uint64_t so = (uint64_t)w2 << 4, dof = (uint64_t)(w3 & 0x7FFFFFFFu) << 4;
+      char *const dbase = h->dst_base.load(std::memory_order_acquire);
+      const char *const sbase = h->src_base.load(std::memory_order_relaxed);
+      const uint64_t slimit = dbase ? h->src_bytes : h->heap_bytes, dlimit = dbase ? h->dst_bytes : h->heap_bytes;
       if ((int)src >= c.num_src || (int)dr >= c.num_ranks || (int)le >= h->E_loc || len == 0 ||
-          so + len > h->heap_bytes || dof + len > h->heap_bytes) {
+          so + len > slimit || dof + len > dlimit) {
         reject(h, P);
         return;
       }
       bump(P.writes, 1);
       bump(P.write_bytes, len);
       bump(P.write_rows, rows);
-      // The payload already sits in the destination partition (the kernel stored it);
-      // what remains of the peer write is its arrival notice.
-      transmit(h, P, WireEvent{(le << 19) | ((rows - 1) << 13) | (uint32_t)((dof >> 4) & 0x1FFFu), (uint16_t)src,
-                               (uint8_t)dr, 0});
+      const WireEvent notice{(le << 19) | ((rows - 1) << 13) | (uint32_t)((dof >> 4) & 0x1FFFu), (uint16_t)src,
+                             (uint8_t)dr, 0};
+      if (dbase) {
+        // registered heaps: this thread performs the write; the notice follows its completion
+        queue_copy(h, P, sbase, dbase, so, dof, len, notice);
+      } else {
+        // The payload already sits in the destination partition (the kernel stored it);
+        // what remains of the peer write is its arrival notice.
+        transmit(h, P, notice);
+      }
       break;
     }
     case EP_OP_ATOMIC: {
@@ -318,15 +398,22 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       const uint64_t len = (uint64_t)(w1 & 0x3FFFFFFu) << 4;
       const uint32_t rows = (w1 >> 26) + 1;
       const uint64_t dof = (uint64_t)w3 << 4;
+      char *const dbase = h->dst_base.load(std::memory_order_acquire);
+      const char *const sbase = h->src_base.load(std::memory_order_relaxed);
+      const uint64_t limit = dbase ? (h->src_bytes < h->dst_bytes ? h->src_bytes : h->dst_bytes) : h->heap_bytes;
       if ((int)src >= c.num_src || (int)dr >= c.num_ranks || (int)le >= h->E_loc || len == 0 ||
-          dof + len > h->heap_bytes) {
+          dof + len > limit) {
         reject(h, P);
         return;
       }
       bump(P.writes, 1);
       bump(P.write_bytes, len);
       bump(P.write_rows, rows);
-      transmit(h, P, WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 1});
+      const WireEvent notice{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 1};
+      if (dbase)
+        queue_copy(h, P, sbase, dbase, dof, dof, len, notice);  // packed chunk: same offset on both sides
+      else
+        transmit(h, P, notice);
       break;
     }
     case EP_OP_ORDERED_ATOMIC: {
@@ -341,6 +428,8 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
     }
     case EP_OP_DRAIN: {
       // everything this thread handed to the transport must have completed
+      launch_batch(h, P);
+      reap_batches(h, P, kReapAll);
       flush_window(h, P);
       // communication channels that travel through this FIFO (destination rank mod C == fifo) must
       // have nothing left waiting: a leftover means a sequence number never arrived
@@ -391,6 +480,7 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
 void proxy_main(ep_handle *h, ProxyThread *Pp) {
   ProxyThread &P = *Pp;
   const uint32_t mask = h->entries - 1;
+  if (!h->host_only && hipSetDevice(h->device) != hipSuccess) fail_hip(h);
   uint64_t idle = 0;
   uint64_t idle_since = 0;
   while (!h->stop.load(std::memory_order_acquire)) {
@@ -417,6 +507,13 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
         __atomic_store_n(&h->head[(size_t)ch * kHeadStride], hd, __ATOMIC_RELEASE);
         any = true;
       }
+    }
+    // what this sweep collected goes out as one batch of peer writes; finished batches release
+    // their arrival notices
+    if (P.cur.n) launch_batch(h, P);
+    if (!P.inflight.empty()) {
+      reap_batches(h, P, kReapReady);
+      any = true;
     }
     if (any) {
       idle = 0;
@@ -477,7 +574,7 @@ void free_all(ep_handle *h) {
     if (h->recv_flag) (void)hipHostFree(h->recv_flag);
     if (h->recv_tail) (void)hipHostFree(h->recv_tail);
     if (h->dev_error) (void)hipHostFree(h->dev_error);
-    void *dev[] = {h->ring.tail, h->ring.cached_head, h->ring.stalls, h->tile_hist, h->tile_base,
+    void *dev[] = {h->ring.tail, h->ring.cached_head, h->ring.stalls, h->ring.refresh_lock, h->tile_hist, h->tile_base,
                    h->chunk_cnt, h->expert_done, h->ticket, h->waves_done, h->ht_seq};
     for (void *p : dev)
       if (p) (void)hipFree(p);
@@ -542,7 +639,7 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
 
   if (!h->host_only) {
     int ndev = 0;
-    if (!HIP_OK(hipGetDeviceCount(&ndev)) || ndev < 1) {
+    if (!HIP_OK(hipGetDeviceCount(&ndev)) || ndev < 1 || !HIP_OK(hipGetDevice(&h->device))) {
       delete h;
       return EP_EHIP;
     }
@@ -560,6 +657,7 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     rc = dev_alloc_zero(&h->ring.tail, (size_t)C * 8);
     if (!rc) rc = dev_alloc_zero(&h->ring.cached_head, (size_t)C * 8);
     if (!rc) rc = dev_alloc_zero(&h->ring.stalls, 8);
+    if (!rc) rc = dev_alloc_zero(&h->ring.refresh_lock, (size_t)C * 4);
     if (!rc) rc = dev_alloc_zero(&h->tile_hist, hist);
     if (!rc) rc = dev_alloc_zero(&h->tile_base, hist);
     if (!rc) rc = dev_alloc_zero(&h->chunk_cnt, (size_t)E * h->chunks_per_expert * 4);
@@ -634,8 +732,45 @@ int ep_proxy_stop(ep_handle *h) {
   h->stop.store(true, std::memory_order_release);
   for (int i = 0; i < h->nthreads; ++i)
     if (h->threads[i].th.joinable()) h->threads[i].th.join();
+  for (int i = 0; i < h->nthreads; ++i) {
+    ProxyThread &P = h->threads[i];
+    if (!P.gpu_ready) continue;
+    for (hipEvent_t &e : P.events)
+      if (e) (void)hipEventDestroy(e);
+    if (P.stream) (void)hipStreamDestroy(P.stream);
+  }
   free_all(h);
   return rc;
+}
+
+int ep_register_heaps(ep_handle *h, const void *d_src_base, int64_t src_bytes, void *d_dst_base,
+                      int64_t dst_bytes) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (!d_src_base != !d_dst_base) return EP_EINVAL;
+  if (!d_dst_base) {
+    h->dst_base.store(nullptr, std::memory_order_release);
+    h->src_base.store(nullptr, std::memory_order_release);
+    return EP_OK;
+  }
+  if (src_bytes <= 0 || dst_bytes <= 0 || (((uintptr_t)d_src_base | (uintptr_t)d_dst_base) & 15)) return EP_EINVAL;
+  if (src_bytes > (1ll << 36) || dst_bytes > (1ll << 36)) return EP_EINVAL;  // offsets travel as 32-bit counts of 16 bytes
+  if (h->nthreads < 1) return EP_EINVAL;
+  // what a proxy thread needs to issue the writes: a stream of its own (default priority) and
+  // completion events; made once, on first registration
+  for (int i = 0; i < h->nthreads; ++i) {
+    ProxyThread &P = h->threads[i];
+    if (P.gpu_ready) continue;
+    if (!HIP_OK(hipStreamCreateWithFlags(&P.stream, hipStreamNonBlocking))) return EP_EHIP;
+    for (hipEvent_t &e : P.events)
+      if (!HIP_OK(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return EP_EHIP;
+    P.gpu_ready = true;
+  }
+  h->src_bytes = (uint64_t)src_bytes;
+  h->dst_bytes = (uint64_t)dst_bytes;
+  h->src_base.store((const char *)d_src_base, std::memory_order_release);
+  h->dst_base.store((char *)d_dst_base, std::memory_order_release);
+  return EP_OK;
 }
 
 int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t *d_count, int32_t *d_expert_total,
@@ -691,7 +826,21 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
     if (cmd_mode & EP_CMD_ATOMICS_FIRST) return EP_EINVAL;
     cmd_mode |= EP_CMD_DRAIN;
   }
-  if (cmd_mode & ~(EP_CMD_MODE_MASK | EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN)) return EP_EINVAL;
+  if (cmd_mode & ~(EP_CMD_MODE_MASK | EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN | EP_CMD_NO_PLACEMENT)) return EP_EINVAL;
+  if (const char *dbase = h->dst_base.load(std::memory_order_acquire)) {
+    // the proxy performs the writes: rows travel as 16-bit words only, and the offsets the kernel
+    // is about to put into its commands must be relative to the registered source heap
+    if (mode != EP_CMD_NONE) {
+      if (payload != EP_BF16) return EP_EINVAL;
+      const bool chunked = mode != EP_CMD_PER_TOKEN;
+      if (chunked && ((cmd_mode & EP_CMD_NO_PLACEMENT) || d_recv != (const void *)h->src_base.load())) return EP_EINVAL;
+      if (!chunked && (!(cmd_mode & EP_CMD_NO_PLACEMENT) || d_x != (const void *)h->src_base.load())) return EP_EINVAL;
+      if (!chunked && (uint64_t)recv_rows * 2u * (uint64_t)c.hidden > h->dst_bytes) return EP_EINVAL;
+    }
+    (void)dbase;
+  } else if (cmd_mode & EP_CMD_NO_PLACEMENT) {
+    return EP_EINVAL;
+  }
   if (recv_rows < 0 || recv_rows > c.heap_rows) return EP_EINVAL;
   if (T > 0 && (!d_x || !d_topk_idx || !d_dst_row || !d_recv)) return EP_EINVAL;
   if ((payload == EP_FP8_E4M3) != (d_recv_scale != nullptr)) return EP_EINVAL;
@@ -913,6 +1062,8 @@ int ep_stats(ep_handle *h, ep_stats_t *out) {
     out->atomics_deferred += P.deferred.load();
     out->ordered_parked += P.ordered_parked.load();
     out->rejected += P.rejected.load();
+    out->copy_batches += P.copy_batches.load();
+    out->copied_bytes += P.copied_bytes.load();
     const uint64_t f = P.first_poll_ns.load(), l = P.last_apply_ns.load();
     if (f && (!out->first_poll_ns || f < out->first_poll_ns)) out->first_poll_ns = f;
     if (l > out->last_apply_ns) out->last_apply_ns = l;
@@ -937,7 +1088,8 @@ int ep_reset_stats(ep_handle *h) {
   for (int i = 0; i < h->nthreads; ++i) {
     ProxyThread &P = h->threads[i];
     for (auto *a : {&P.cmds, &P.writes, &P.atomics, &P.drains, &P.write_bytes, &P.write_rows, &P.applied,
-                    &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns, &P.ordered_parked, &P.barriers})
+                    &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns, &P.ordered_parked, &P.barriers,
+                    &P.copy_batches, &P.copied_bytes})
       a->store(0);
     std::lock_guard<std::mutex> g(P.log_mu);
     P.cmd_log.clear();

@@ -36,6 +36,7 @@ struct RingDev {
   unsigned long long *cached_head;   // [channels], device: last head value fetched over PCIe
   int *error;                        // pinned host sticky error word
   unsigned long long *stalls;        // device: times a push found the channel full
+  unsigned *refresh_lock;            // [channels], device: held by the one lane re-reading a channel's head
   unsigned entries, log2_entries, channels;
   unsigned long long timeout_ticks;  // wall_clock64 ticks (100 MHz)
 };
@@ -112,6 +113,20 @@ struct CombinePartialArgs {
   int *error;
 };
 
+// A batch of peer writes the proxy performs on behalf of the GPU (registered heaps).  The whole
+// batch travels as the kernel's argument block (reads of descriptors left in host memory cost a
+// PCIe round trip per workgroup), hence offsets and lengths in 16-byte units.
+constexpr int kCopyBatchMax = 256;
+struct CopyBatchArgs {
+  const char *src_base;
+  char *dst_base;
+  int n;
+  unsigned max_len16;
+  struct Desc {
+    unsigned src16, dst16, len16;
+  } d[kCopyBatchMax];
+};
+
 struct RecvWaitArgs {
   int *flags;        // pinned host [S*E]: 0 = not arrived, else posted count + 1 (written by the proxy)
   int32_t *out;      // device [E] or null
@@ -126,6 +141,7 @@ int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
 int launch_combine(const CombineArgs &a, void *stream);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
 int launch_barrier(const RingDev &ring, void *stream);
+int launch_copy_batch(const CopyBatchArgs &b, void *stream);
 int launch_dedup(const DedupArgs &a, void *stream);
 int launch_gather_index(const GatherIndexArgs &a, void *stream);
 int launch_combine_partial(const CombinePartialArgs &a, void *stream);

@@ -38,9 +38,18 @@ EP_DEV unsigned long long ring_push(const RingDev &r, unsigned c, unsigned w0, u
       __hip_atomic_load(&r.cached_head[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (idx - head >= r.entries) {
     __hip_atomic_fetch_add(r.stalls, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // Full: wait for the proxy to pop.  Thousands of lanes can be waiting on one channel, and
+    // each re-read of the head is a PCIe round trip, so only the lane that holds the channel's
+    // refresh lock goes to host memory; everyone else watches the device-side copy it updates.
     const unsigned long long t0 = wall_clock64();
     for (;;) {
-      head = __hip_atomic_load(&r.head[c * kHeadStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (__hip_atomic_exchange(&r.refresh_lock[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+        const unsigned long long h =
+            __hip_atomic_load(&r.head[c * kHeadStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_fetch_max(&r.cached_head[c], h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&r.refresh_lock[c], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      head = __hip_atomic_load(&r.cached_head[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (idx - head < r.entries) break;
       if (wall_clock64() - t0 > r.timeout_ticks) {
         dev_set_error(r.error, EP_ETIMEOUT);
@@ -48,7 +57,6 @@ EP_DEV unsigned long long ring_push(const RingDev &r, unsigned c, unsigned w0, u
       }
       __builtin_amdgcn_s_sleep(32);
     }
-    __hip_atomic_fetch_max(&r.cached_head[c], head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   const unsigned gen = (((unsigned)(idx >> r.log2_entries)) & 1u) ^ 1u;
   u32x4 v = {w0 | (gen << 31), w1, w2, w3 | (gen << 31)};
@@ -475,7 +483,7 @@ __global__ void dispatch_bf16_kernel(DispatchArgs a) {
   unsigned long long vmask = __ballot(m.valid);
   const int nvec = a.H >> 3;
   const int v0 = part * VPL * 64 + lane;
-  if (vmask) {
+  if (vmask && !(a.cmd_mode & EP_CMD_NO_PLACEMENT)) {
     const u32x4 *src = (const u32x4 *)a.x + (size_t)t * nvec;
     u32x4 v[VPL];
 #pragma unroll
@@ -969,6 +977,25 @@ int launch_combine_partial(const CombinePartialArgs &a0, void *stream) {
     case 8: hipLaunchKernelGGL(combine_partial_kernel<8>, dim3(grid), dim3(256), 0, st, a); break;
     default: hipLaunchKernelGGL(combine_partial_kernel<0>, dim3(grid), dim3(256), 0, st, a); break;
   }
+  return (int)hipGetLastError();
+}
+
+// ------------------------------------------------- proxy-issued peer writes
+// blockIdx.y = descriptor, blockIdx.x strides over its 16-byte vectors.
+__global__ __launch_bounds__(256) void copy_batch_kernel(const CopyBatchArgs b) {
+  const CopyBatchArgs::Desc d = b.d[blockIdx.y];
+  const u32x4 *s = (const u32x4 *)b.src_base + d.src16;
+  u32x4 *o = (u32x4 *)b.dst_base + d.dst16;
+  for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < d.len16; i += gridDim.x * 256)
+    o[i] = __builtin_nontemporal_load(s + i);
+}
+
+int launch_copy_batch(const CopyBatchArgs &b, void *stream) {
+  if (b.n <= 0) return 0;
+  unsigned gx = (b.max_len16 + 255) / 256;
+  if (gx < 1) gx = 1;
+  if (gx > 64) gx = 64;  // 64 x 4 KiB per pass and descriptor, grid-stride beyond
+  hipLaunchKernelGGL(copy_batch_kernel, dim3(gx, (unsigned)b.n), dim3(256), 0, (hipStream_t)stream, b);
   return (int)hipGetLastError();
 }
 

@@ -94,6 +94,9 @@ class EPRunner:
     def combine(self, y: torch.Tensor, topk_w_s: torch.Tensor, dst_row_s: torch.Tensor, out: torch.Tensor) -> None:
         ep.ep_combine(self.h, y, topk_w_s, dst_row_s, out.shape[0], y.shape[0], out)
 
+    def register_heaps(self, src: Optional[torch.Tensor], dst: Optional[torch.Tensor]) -> None:
+        ep.ep_register_heaps(self.h, src, dst)
+
     def recv_wait(self, counts_out: Optional[torch.Tensor] = None, src: int = 0, rank_filter: int = -1) -> None:
         ep.ep_recv_wait(self.h, src, rank_filter, counts_out)
 

@@ -73,7 +73,8 @@ def test_layout_special_shapes(epmod, oracle):
 
 
 # ---------------------------------------------------------- dispatch bf16
-def _dispatch_case(epmod, oracle, cfg, T, mask, cmd_mode, rank_filter=-1, src=0, extra_rows=3, **kw):
+def _dispatch_case(epmod, oracle, cfg, T, mask, cmd_mode, rank_filter=-1, src=0, extra_rows=3, proxy_writes=False,
+                   **kw):
     idx, w = g.routing_all(cfg, T)
     if mask:
         idx = g.mask_random(idx, mask, seed=23)
@@ -86,7 +87,17 @@ def _dispatch_case(epmod, oracle, cfg, T, mask, cmd_mode, rank_filter=-1, src=0,
         lay = r.layout(d_idx)
         recv = torch.full((rows, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")     # sentinel 0xBFC0
         from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
-        r.dispatch(bits_to_bf16(x), d_idx[src], lay, recv, src=src, rank_filter=rank_filter, cmd_mode=cmd_mode)
+        d_x = bits_to_bf16(x)
+        target = recv
+        if proxy_writes:
+            # the proxy moves the rows: per token straight out of x, chunks out of a packed send heap
+            if (cmd_mode & 0xFF) == epmod.EP_CMD_PER_TOKEN:
+                cmd_mode |= epmod.EP_CMD_NO_PLACEMENT
+                r.register_heaps(d_x, recv)
+            else:
+                target = torch.full((rows, cfg.H), 2.5, dtype=torch.bfloat16, device="cuda")
+                r.register_heaps(target, recv)
+        r.dispatch(d_x, d_idx[src], lay, target, src=src, rank_filter=rank_filter, cmd_mode=cmd_mode)
         if (cmd_mode & 0xFF) != epmod.EP_CMD_NONE:
             r.wait()
         torch.cuda.synchronize()
@@ -98,6 +109,10 @@ def _dispatch_case(epmod, oracle, cfg, T, mask, cmd_mode, rank_filter=-1, src=0,
         assert np.array_equal(got, want)
         st = r.stats()
         assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        if proxy_writes:
+            assert st["copied_bytes"] == st["write_bytes"] > 0 and 1 <= st["copy_batches"] <= st["writes"]
+        else:
+            assert st["copied_bytes"] == 0 and st["copy_batches"] == 0
         return dict(stats=st, cmds=epmod.ep_cmd_log(r.h), events=epmod.ep_event_log(r.h), lay=want_lay, idx=idx,
                     counters=r.counters().copy(), x=x, recv=got)
 
@@ -164,6 +179,99 @@ def test_dispatch_chunk32_commands(epmod, oracle, cid, T, mask, window):
     out = _dispatch_case(epmod, oracle, cfg, T, mask, epmod.EP_CMD_CHUNK32, reorder_window=window, reorder_seed=9)
     _check_commands(epmod, oracle, cfg, out, "chunk32")
     oracle.check_chunk_cover(out["cmds"], out["lay"], 0, cfg.E_loc, oracle.row_bytes(cfg.H, "bf16"))
+
+
+# -------------------------------------------- writes performed by the proxy
+@pytest.mark.parametrize("cid,T,mask,window,threads", [(1, None, 0.0, 0, 4), (1, 50, 0.25, 5, 1), (2, 128, 0.0, 0, 2),
+                                                       (4, 300, 0.05, 16, 4), (5, 700, 0.0, 0, 3)])
+def test_proxy_performs_per_token_writes(epmod, oracle, cid, T, mask, window, threads):
+    cfg = g.config(cid, S=1)
+    out = _dispatch_case(epmod, oracle, cfg, T, mask, epmod.EP_CMD_PER_TOKEN, proxy_writes=True,
+                         reorder_window=window, reorder_seed=3, num_proxy_threads=threads)
+    _check_commands(epmod, oracle, cfg, out, "per_token")
+
+
+@pytest.mark.parametrize("cid,T,mask,window,mode", [(1, None, 0.0, 0, "chunk32"), (4, 700, 0.1, 16, "chunk32"),
+                                                    (5, 1000, 0.0, 0, "chunk32"), (1, None, 0.2, 6, "ordered"),
+                                                    (4, 500, 0.0, 0, "ordered")])
+def test_proxy_performs_chunk_writes(epmod, oracle, cid, T, mask, window, mode):
+    cfg = g.config(cid, S=1)
+    if mode == "chunk32":
+        out = _dispatch_case(epmod, oracle, cfg, T, mask, epmod.EP_CMD_CHUNK32, proxy_writes=True,
+                             reorder_window=window, reorder_seed=11)
+        _check_commands(epmod, oracle, cfg, out, "chunk32")
+    else:
+        out = _dispatch_case(epmod, oracle, cfg, T, mask, epmod.EP_CMD_CHUNK32_ORDERED, proxy_writes=True,
+                             reorder_window=window, reorder_seed=11)
+        oracle.check_order_trace(out["events"])
+        assert out["stats"]["drains"] == 8
+
+
+def test_proxy_writes_follow_new_data_and_atomics_wait_for_them(epmod, oracle):
+    """Three dispatches through the same registered heaps with different activations: each receive
+    buffer holds that call's rows (nothing stale is forwarded), and count atomics, which do not wait for
+    the copies, get ahead of their rows and are held back by the fence."""
+    cfg = g.config(4, S=1)
+    T = 600
+    idx, _ = g.routing_all(cfg, T)
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    rows = idx.size
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    with _runner(epmod, cfg, T, num_channels=1, num_proxy_threads=1) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        send = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+        recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+        r.register_heaps(send, recv)
+        for it in range(3):
+            x = g.activations(cfg, it, T=T)
+            r.dispatch(bits_to_bf16(x), d_idx[0], lay, send, cmd_mode=epmod.EP_CMD_CHUNK32 | epmod.EP_CMD_ATOMICS_FIRST)
+            r.wait()
+            torch.cuda.synchronize()
+            want, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+            assert np.array_equal(bf16_to_bits(recv), want), it
+        st = r.stats()
+        assert st["atomics_deferred"] >= 1 and st["proxy_error"] == 0 and st["device_error"] == 0
+        # unregistering returns to the mode in which the kernel places the rows itself
+        r.register_heaps(None, None)
+        recv2 = torch.zeros_like(recv)
+        r.dispatch(bits_to_bf16(x), d_idx[0], lay, recv2, cmd_mode=epmod.EP_CMD_PER_TOKEN)
+        r.wait()
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_to_bits(recv2), want)
+        assert r.stats()["copied_bytes"] == st["copied_bytes"]
+
+
+def test_registered_heaps_argument_errors(epmod):
+    cfg = g.config(1)
+    with _runner(epmod, cfg) as r:
+        x = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        recv = torch.zeros((cfg.T * cfg.K, cfg.H), dtype=torch.bfloat16, device="cuda")
+        sc = torch.zeros((cfg.T * cfg.K, cfg.H // 128), dtype=torch.float32, device="cuda")
+        idx = _dev(g.routing_all(cfg)[0])
+        lay = r.layout(idx)
+
+        def rc_of(fn):
+            with pytest.raises(epmod.EPError) as ei:
+                fn()
+            return ei.value.rc
+        # the flag needs registered heaps
+        assert rc_of(lambda: r.dispatch(x, idx[0], lay, recv, cmd_mode=epmod.EP_CMD_PER_TOKEN |
+                                        epmod.EP_CMD_NO_PLACEMENT)) == epmod.EP_EINVAL
+        assert rc_of(lambda: r.register_heaps(x, None)) == epmod.EP_EINVAL
+        r.register_heaps(x, recv)
+        # per token: needs the flag, and x must be the registered source
+        assert rc_of(lambda: r.dispatch(x, idx[0], lay, recv, cmd_mode=epmod.EP_CMD_PER_TOKEN)) == epmod.EP_EINVAL
+        assert rc_of(lambda: r.dispatch(x.clone(), idx[0], lay, recv, cmd_mode=epmod.EP_CMD_PER_TOKEN |
+                                        epmod.EP_CMD_NO_PLACEMENT)) == epmod.EP_EINVAL
+        # chunks: must be packed into the registered source heap; FP8 rows are not forwarded
+        assert rc_of(lambda: r.dispatch(x, idx[0], lay, recv, cmd_mode=epmod.EP_CMD_CHUNK32)) == epmod.EP_EINVAL
+        assert rc_of(lambda: r.dispatch(x, idx[0], lay, x, recv_scale=sc, payload=epmod.EP_FP8_E4M3,
+                                        cmd_mode=epmod.EP_CMD_CHUNK32)) == epmod.EP_EINVAL
+        # ring-off dispatch is unaffected
+        r.dispatch(x, idx[0], lay, recv, cmd_mode=epmod.EP_CMD_NONE)
+        torch.cuda.synchronize()
+        assert r.stats()["cmds"] == 0
 
 
 def test_atomics_first_forces_the_fence_path(epmod, oracle):
