@@ -205,6 +205,26 @@ def run_suite(args) -> int:
                     hh["combine_final_us"] = timed(lambda: rg.combine(partial, ones, Lg.dst_row[0], o))
                     res[f"ht_ranks_per_group{G}"] = hh
                     del recv_g, partial
+            # ring-buffer channels: sender -> ring slot -> receiver -> packed buffer, head/tail through the proxy
+            for slices, W in ((128, 2), (128, 4), (256, 2)):
+                with EPRunner(R, E, K, H, T, num_proxy_threads=4, spin_timeout_ms=10000, ht_slices=slices,
+                              ht_ring_slots=W) as rr_:
+                    Lr = rr_.layout(d_idx)
+                    ring = torch.zeros(rr_.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+                    e2e = []
+                    for _ in range(13):
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        rr_.ht_dispatch(d_x, d_idx[0], Lr, ring, recv)
+                        rr_.wait()
+                        e2e.append((time.perf_counter() - t0) * 1e6)
+                    e2e = sorted(e2e[3:])
+                    st = rr_.stats()
+                    res[f"ht_ring_slices{slices}_slots{W}"] = {
+                        "launch_to_drained_us": round(e2e[len(e2e) // 2], 1), "cmds_per_dispatch": st["cmds"] // 13,
+                        "ring_MiB": rr_.ht_ring_bytes() >> 20,
+                        "GBs_rows_delivered": round(my_rows * H * 2 / e2e[len(e2e) // 2] / 1e3, 1)}
+                    del ring
         out[cfg.name] = res
         del recv, rq, rs, d_x, o
         torch.cuda.empty_cache()

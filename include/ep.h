@@ -105,6 +105,8 @@ typedef struct ep_config {
   int32_t flags;             /* ep_flags                                               */
   int32_t barrier_peers;     /* processes that take part in Barrier commands (0 or 1: only this one)   */
   char barrier_name[48];     /* name of the shared-memory barrier the peers of one node agree on; "" = private */
+  int32_t ht_slices;         /* ring-buffer channels: token slices per source (0 = ep_ht_dispatch unavailable), <= 4096 */
+  int32_t ht_ring_slots;     /* ... chunk slots per channel ring (W); num_ranks * W <= 4096                           */
 } ep_config;
 
 typedef struct ep_stats_t {
@@ -230,7 +232,7 @@ int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, con
  * heap.  While heaps are registered the proxy PERFORMS every Write command it
  * polls: after translating and bounds-checking the offsets it copies `length`
  * bytes from source heap + source offset to destination heap + destination
- * offset (batched copy kernels on the proxy thread's own stream, standing in
+ * offset (batched copy kernels on a stream of the proxy's own, standing in
  * for the RDMA writes), and only when a batch has completed does it hand the
  * writes' immediates to the receiver half.  Count Atomics keep flowing at once,
  * so they regularly overtake their data and wait in the control buffer.
@@ -268,6 +270,42 @@ int ep_recv_wait(ep_handle *h, int32_t src_rank, int32_t dst_rank_filter, int32_
  * an Atomic (Section 4.1: host-allocated counters the GPU may also read).
  * *d_recv_count (may be NULL) receives the same memory's device address. */
 int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv_count);
+
+/* ep_ht_dispatch - high-throughput-mode dispatch through ring-buffer
+ * communication channels (Section 3.3, "partial ordering"; Section 3.3's
+ * description of the HT kernel: rings of chunk slots, head and tail values).
+ * The T tokens are cut into ht_slices slices of ceil(T/ht_slices) consecutive
+ * tokens; a channel is (source, slice, destination rank) and owns a ring of
+ * ht_ring_slots slots in d_ring.  One launch runs, per slice, a sender
+ * workgroup and a receiver workgroup:
+ *   sender   - copies each valid (token, k) row into the next free row of its
+ *              channel's current chunk (slot = chunk number mod W, a 128-byte
+ *              header of int32 destination rows, then 32 rows); it may use a slot
+ *              only when the head counter says chunk n - W was consumed; a full (or
+ *              the last, partial) chunk is announced with a sequenced Write and a
+ *              sequenced Atomic that adds its rows to the channel's tail;
+ *   receiver - polls the tails, copies the rows of every announced chunk from the
+ *              ring to their destination rows in d_recv (the packed receive buffer
+ *              of ep_dispatch), then releases the slot with a sequenced Atomic that
+ *              adds the rows to the channel's head (a channel in the other direction).
+ * All three message kinds travel through the command rings and the proxy, which
+ * applies each channel's messages strictly in sequence whatever order they were
+ * delivered in; tail and head counters live in pinned host memory
+ * (ep_ring_counters).  The launch ends with a Drain on every FIFO; ep_wait
+ * returns when those are through.
+ *   d_x [T,H] bf16, d_topk_idx / d_dst_row int32 [T,K] of source src_rank
+ *   d_ring   device, ring_bytes >= ht_slices * R * W * (128 + 32 * 2H), 16-byte aligned
+ *   d_recv   device bf16 [recv_rows, H]
+ * Needs ht_slices > 0 and proxy threads; one ep_ht_dispatch per source at a time
+ * (wait with ep_wait before the next one of the same source).  Every wait in the
+ * kernel is bounded by spin_timeout_ms (EP_ETIMEOUT in the sticky device error). */
+int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const int32_t *d_dst_row, int32_t T,
+                   int32_t src_rank, void *d_ring, int64_t ring_bytes, void *d_recv, int64_t recv_rows,
+                   void *stream);
+
+/* ep_ring_counters - pinned-host int32 [S, ht_slices, R] each: rows announced
+ * (tail) and rows released (head) per ring-buffer channel, running totals. */
+int ep_ring_counters(ep_handle *h, const int32_t **ring_tail, const int32_t **ring_head);
 
 /* ep_tail_counters - *recv_tail points at pinned-host int32 [S, R]: rows
  * announced so far on the communication channel (source, destination rank) by
@@ -333,8 +371,15 @@ enum ep_cmd_op {
   /* Sequenced variants used by EP_CMD_CHUNK32_ORDERED: w2 carries the 32-bit sequence number of the
    * communication channel (source rank, destination rank); an ordered Write's source offset equals its
    * destination offset; an ordered Atomic ADDS w1 to the tail counter w3 = source * R + destination rank. */
-  EP_OP_ORDERED_WRITE = 5, EP_OP_ORDERED_ATOMIC = 6
+  EP_OP_ORDERED_WRITE = 5, EP_OP_ORDERED_ATOMIC = 6,
+  /* Messages of the ring-buffer channels (ep_ht_dispatch).  w0's local-expert field carries the slice, so
+   * the channel is (source, slice, destination rank); w1[31:30] is the kind, w2 the channel's sequence number:
+   *   kind 0 Write       w1[29:24] rows - 1, w1[23:0] length / 16 (header + rows), w3 = slot offset in the ring / 16
+   *   kind 1 Atomic tail w1[29:0] rows to add to the channel's tail   (sender -> receiver, numbered with the Writes)
+   *   kind 2 Atomic head w1[29:0] rows to add to the channel's head   (receiver -> sender, numbered on its own) */
+  EP_OP_RING = 7
 };
+enum ep_ring_kind { EP_RING_WRITE = 0, EP_RING_TAIL = 1, EP_RING_HEAD = 2 };
 
 #ifdef __cplusplus
 }

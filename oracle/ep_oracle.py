@@ -548,3 +548,173 @@ def check_fence_trace(events: np.ndarray, count: np.ndarray) -> Dict[str, int]:
     for (src, e), val in applied.items():
         assert int(count[src, e]) == val, f"counter ({src},{e}) = {val}, layout says {int(count[src, e])}"
     return dict(waited=waited, applied=len(applied))
+
+
+# ---------------------------------------------------------------------------
+# High-throughput mode through ring-buffer channels (Section 3.3, "partial
+# ordering": ring buffers as communication channels, head and tail values,
+# chunks of typically 32 tokens).  The paper fixes neither the split into
+# channels nor the message fields; the reading used:
+#   * the T tokens of a source are cut into C slices of slice_len = ceil(T/C)
+#     consecutive tokens; a communication channel is (source, slice, destination
+#     rank) and owns a ring of W slots at the receiver;
+#   * a slot holds one chunk: a 128-byte header (the destination row of each of
+#     its <= 32 rows in the packed receive buffer, int32) followed by the rows;
+#     slot (c, r, w) starts at ((c*R + r)*W + w) * (128 + 32*row_bytes);
+#   * the n-th chunk of a channel (n from 0 within one dispatch) goes to slot
+#     n mod W and carries min(32, rows - 32n) rows; the sender may write it only
+#     when chunk n - W has been consumed (head), the receiver may read it only
+#     when the tail covers it;
+#   * messages (op 7; w0 as for every command with the slice in the local-expert
+#     field; w1[31:30] kind; w2 = sequence number):
+#       kind 0 Write       w1 = (rows-1) << 24 | bytes/16, w3 = slot offset/16,
+#                          sequence base + 2n            (sender -> receiver)
+#       kind 1 Atomic tail w1 = rows, sequence base + 2n + 1
+#       kind 2 Atomic head w1 = rows, sequence rbase + n (receiver -> sender,
+#                          a channel of its own in the other direction)
+OP_RING = 7
+RING_WRITE, RING_TAIL, RING_HEAD = 0, 1, 2
+RING_HEADER_BYTES = 128
+
+
+def ring_slot_bytes(H: int) -> int:
+    return RING_HEADER_BYTES + CHUNK_ROWS * row_bytes(H, "bf16")
+
+
+def ring_bytes(H: int, R: int, slices: int, W: int) -> int:
+    return slices * R * W * ring_slot_bytes(H)
+
+
+def ring_channel_rows(idx_s: np.ndarray, E_loc: int, R: int, slices: int) -> np.ndarray:
+    """rows[c][r]: valid (token, k) entries of slice c whose expert lives on rank r."""
+    idx_s = np.asarray(idx_s)
+    T = idx_s.shape[0]
+    out = np.zeros((slices, R), np.int64)
+    if T == 0:
+        return out
+    slice_len = -(-T // slices)
+    for t in range(T):
+        for e in idx_s[t]:
+            if e >= 0:
+                out[t // slice_len, int(e) // E_loc] += 1
+    return out
+
+
+def decode_ring_cmd(words: Iterable[int]) -> Dict[str, int]:
+    w0, w1, w2, w3 = (int(v) & 0xFFFFFFFF for v in words)
+    kind = w1 >> 30
+    d = dict(op=(w0 >> 28) & 7, src=(w0 >> 20) & 0xFF, dst_rank=(w0 >> 12) & 0xFF, slice=w0 & 0xFFF,
+             kind=kind, seq=w2, gen=w0 >> 31, gen_hi=w3 >> 31)
+    if kind == RING_WRITE:
+        d.update(rows=((w1 >> 24) & 0x3F) + 1, nbytes=(w1 & 0xFFFFFF) << 4, dst_off=(w3 & 0x7FFFFFFF) << 4)
+    else:
+        d.update(rows=w1 & 0x3FFFFFFF, nbytes=0, dst_off=0)
+    return d
+
+
+def expected_ring_cmds(idx_s: np.ndarray, s: int, E_loc: int, R: int, H: int, slices: int, W: int,
+                       seq_base: Optional[np.ndarray] = None, rseq_base: Optional[np.ndarray] = None) -> Counter:
+    """Multiset of the ring-mode messages of one dispatch of source s; seq_base / rseq_base [slices, R]
+    are the channels' sequence numbers before the dispatch (they keep running across dispatches)."""
+    rows = ring_channel_rows(idx_s, E_loc, R, slices)
+    rb, sb = row_bytes(H, "bf16"), ring_slot_bytes(H)
+    out: Counter = Counter()
+    for c in range(slices):
+        for r in range(R):
+            b = int(seq_base[c, r]) if seq_base is not None else 0
+            rbase = int(rseq_base[c, r]) if rseq_base is not None else 0
+            n, left = 0, int(rows[c, r])
+            while left > 0:
+                m = min(CHUNK_ROWS, left)
+                off = ((c * R + r) * W + n % W) * sb
+                out[(RING_WRITE, s, r, c, b + 2 * n, m, RING_HEADER_BYTES + m * rb, off)] += 1
+                out[(RING_TAIL, s, r, c, b + 2 * n + 1, m, 0, 0)] += 1
+                out[(RING_HEAD, s, r, c, rbase + n, m, 0, 0)] += 1
+                left -= m
+                n += 1
+    return out
+
+
+def ring_cmd_multiset(log_words: np.ndarray) -> Counter:
+    out: Counter = Counter()
+    for w in np.asarray(log_words, np.uint32).reshape(-1, 4):
+        d = decode_ring_cmd(w)
+        if d["op"] != OP_RING:
+            continue
+        assert d["gen"] == d["gen_hi"]
+        out[(d["kind"], d["src"], d["dst_rank"], d["slice"], d["seq"], d["rows"], d["nbytes"], d["dst_off"])] += 1
+    return out
+
+
+# Receiver-side events of the ring mode: [0] kind | thread << 8, [1] source,
+# [2] slice << 8 | destination rank, [3] sequence number.
+EV_RING_WRITE_IN, EV_RING_TAIL_IN, EV_RING_HEAD_IN = 8, 9, 10
+EV_RING_WRITE_APPLIED, EV_RING_TAIL_APPLIED, EV_RING_HEAD_APPLIED = 11, 12, 13
+
+
+def check_ring_trace(events: np.ndarray, W: int, first_seq: Optional[Dict[Tuple[int, int, int], int]] = None,
+                     first_rseq: Optional[Dict[Tuple[int, int, int], int]] = None) -> Dict[str, int]:
+    """What the ring-buffer protocol needs from the proxy, checked on the receiving thread's own log:
+      * both directions of a channel are handled by one thread;
+      * forward messages (Write 2n, tail Atomic 2n+1) are applied in sequence order, each once and only
+        after it was delivered; likewise the head Atomics of the reverse direction;
+      * no overwrite: when the Write of chunk n is delivered, the head Atomic of chunk n - W has been
+        applied (the sender could not have known the slot was free otherwise);
+      * no stale read: the head Atomic of chunk n is delivered only after the tail Atomic of chunk n was
+        applied (the receiver consumed a chunk it had been told about);
+      * nothing delivered stays unapplied.
+    Sequence numbers are taken relative to first_seq / first_rseq of the channel (default 0)."""
+    ev = np.asarray(events, np.uint32).reshape(-1, 4)
+    fwd_in: Dict[Tuple[int, int, int], set] = {}
+    rev_in: Dict[Tuple[int, int, int], set] = {}
+    fwd_next: Dict[Tuple[int, int, int], int] = {}
+    rev_next: Dict[Tuple[int, int, int], int] = {}
+    owner: Dict[Tuple[int, int, int], int] = {}
+    waited = applied = 0
+    for kind_thr, src, cr, seq in ev.tolist():
+        kind, thr = kind_thr & 0xFF, kind_thr >> 8
+        if kind < EV_RING_WRITE_IN or kind > EV_RING_HEAD_APPLIED:
+            continue
+        key = (src, cr >> 8, cr & 0xFF)
+        assert owner.setdefault(key, thr) == thr, f"channel {key} handled by two threads"
+        f0 = (first_seq or {}).get(key, 0)
+        r0 = (first_rseq or {}).get(key, 0)
+        fwd_next.setdefault(key, 0)
+        rev_next.setdefault(key, 0)
+        if kind in (EV_RING_WRITE_IN, EV_RING_TAIL_IN):
+            n = seq - f0
+            assert n >= 0 and n not in fwd_in.setdefault(key, set()), f"{key}: forward {seq} delivered twice"
+            assert (n % 2 == 0) == (kind == EV_RING_WRITE_IN), f"{key}: forward {seq} has the wrong kind"
+            fwd_in[key].add(n)
+            if n != fwd_next[key]:
+                waited += 1
+            if kind == EV_RING_WRITE_IN:
+                chunk = n // 2
+                assert rev_next[key] >= chunk - W + 1, (
+                    f"{key}: chunk {chunk} written while chunk {chunk - W} was not yet released (overwrite)")
+        elif kind == EV_RING_HEAD_IN:
+            n = seq - r0
+            assert n >= 0 and n not in rev_in.setdefault(key, set()), f"{key}: head {seq} delivered twice"
+            rev_in[key].add(n)
+            if n != rev_next[key]:
+                waited += 1
+            assert fwd_next[key] >= 2 * n + 2, f"{key}: chunk {n} released before its tail update was applied"
+        elif kind in (EV_RING_WRITE_APPLIED, EV_RING_TAIL_APPLIED):
+            n = seq - f0
+            assert n in fwd_in.get(key, set()), f"{key}: forward {seq} applied before it was delivered"
+            assert (n % 2 == 0) == (kind == EV_RING_WRITE_APPLIED), f"{key}: forward {seq} applied as the wrong kind"
+            assert n == fwd_next[key], f"{key}: forward {seq} applied out of order (next {fwd_next[key] + f0})"
+            fwd_next[key] = n + 1
+            applied += 1
+        else:
+            n = seq - r0
+            assert n in rev_in.get(key, set()), f"{key}: head {seq} applied before it was delivered"
+            assert n == rev_next[key], f"{key}: head {seq} applied out of order (next {rev_next[key] + r0})"
+            rev_next[key] = n + 1
+            applied += 1
+    for key, got in fwd_in.items():
+        assert fwd_next[key] == len(got), f"{key}: forward messages delivered but never applied"
+    for key, got in rev_in.items():
+        assert rev_next[key] == len(got), f"{key}: head updates delivered but never applied"
+    return dict(applied=applied, waited=waited,
+                chunks={k: v // 2 for k, v in fwd_next.items()}, released=dict(rev_next))

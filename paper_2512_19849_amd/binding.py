@@ -21,6 +21,8 @@ EP_CMD_PER_TOKEN, EP_CMD_CHUNK32, EP_CMD_NONE, EP_CMD_CHUNK32_ORDERED = 0, 1, 2,
 EP_CMD_ATOMICS_FIRST, EP_CMD_DRAIN, EP_CMD_NO_PLACEMENT = 0x100, 0x200, 0x400
 EP_FLAG_LOG_CMDS, EP_FLAG_LOG_EVENTS, EP_FLAG_HOST_ONLY = 1, 2, 4
 EP_OP_WRITE, EP_OP_ATOMIC, EP_OP_DRAIN, EP_OP_BARRIER, EP_OP_ORDERED_WRITE, EP_OP_ORDERED_ATOMIC = 1, 2, 3, 4, 5, 6
+EP_OP_RING = 7
+EP_RING_WRITE, EP_RING_TAIL, EP_RING_HEAD = 0, 1, 2
 
 _STATUS = {0: "EP_OK", -1: "EP_EINVAL", -2: "EP_ENOMEM", -3: "EP_ESTATE", -4: "EP_EHIP", -5: "EP_ETIMEOUT",
            -6: "EP_EBOUNDS"}
@@ -44,7 +46,7 @@ class ep_config(C.Structure):
                 ("num_channels", C.c_int32), ("ring_entries", C.c_int32), ("num_proxy_threads", C.c_int32),
                 ("reorder_window", C.c_int32), ("spin_timeout_ms", C.c_int32), ("reorder_seed", C.c_uint64),
                 ("heap_rows", C.c_int64), ("flags", C.c_int32), ("barrier_peers", C.c_int32),
-                ("barrier_name", C.c_char * 48)]
+                ("barrier_name", C.c_char * 48), ("ht_slices", C.c_int32), ("ht_ring_slots", C.c_int32)]
 
 
 class ep_stats_t(C.Structure):
@@ -64,7 +66,7 @@ EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_co
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
-           "ep_register_heaps"]
+           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters"]
 
 _lib = None
 
@@ -112,6 +114,8 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_host_expect_atomics.argtypes = [vp, i32]
     L.ep_bw_probe.argtypes = [i32, vp, vp, i64, vp]
     L.ep_register_heaps.argtypes = [vp, vp, i64, vp, i64]
+    L.ep_ht_dispatch.argtypes = [vp, vp, vp, vp, i32, i32, vp, i64, vp, i64, vp]
+    L.ep_ring_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     for name in EXPORTS:
         getattr(L, name).restype = C.c_int
     L.ep_last_error.argtypes = []
@@ -146,11 +150,12 @@ def _stream(stream) -> Optional[int]:
 def ep_proxy_start(num_ranks: int, num_experts: int, top_k: int, hidden: int, max_tokens: int, num_src: int = 1,
                    self_rank: int = 0, num_channels: int = 8, ring_entries: int = 4096, num_proxy_threads: int = 4,
                    reorder_window: int = 0, reorder_seed: int = 0, spin_timeout_ms: int = 0, heap_rows: int = 0,
-                   flags: int = 0, barrier_peers: int = 0, barrier_name: str = "") -> int:
+                   flags: int = 0, barrier_peers: int = 0, barrier_name: str = "", ht_slices: int = 0,
+                   ht_ring_slots: int = 0) -> int:
     """Returns the opaque handle (an integer address)."""
     cfg = ep_config(num_ranks, num_experts, top_k, hidden, max_tokens, num_src, self_rank, num_channels,
                     ring_entries, num_proxy_threads, reorder_window, spin_timeout_ms, reorder_seed, heap_rows,
-                    flags, barrier_peers, barrier_name.encode())
+                    flags, barrier_peers, barrier_name.encode(), ht_slices, ht_ring_slots)
     h = C.c_void_p()
     _check("ep_proxy_start", load_library().ep_proxy_start(C.byref(cfg), C.byref(h)))
     return h.value
@@ -221,6 +226,22 @@ def ep_counters(h: int, S: int, E: int) -> np.ndarray:
     _check("ep_counters", load_library().ep_counters(h, C.byref(host), C.byref(dev)))
     buf = (C.c_int32 * (S * E)).from_address(host.value)
     return np.frombuffer(buf, dtype=np.int32).reshape(S, E)
+
+
+def ep_ht_dispatch(h: int, x, topk_idx, dst_row, T: int, src_rank: int, ring, recv, recv_rows: int,
+                   stream=None) -> None:
+    _check("ep_ht_dispatch", load_library().ep_ht_dispatch(h, _ptr(x), _ptr(topk_idx), _ptr(dst_row), T, src_rank,
+                                                           _ptr(ring), ring.numel() * ring.element_size(),
+                                                           _ptr(recv), recv_rows, _stream(stream)))
+
+
+def ep_ring_counters(h: int, S: int, slices: int, R: int):
+    """numpy views (no copy) of the pinned-host tail and head counters [S, slices, R] of the ring-buffer channels."""
+    tail, head = C.c_void_p(), C.c_void_p()
+    _check("ep_ring_counters", load_library().ep_ring_counters(h, C.byref(tail), C.byref(head)))
+    n = S * slices * R
+    return tuple(np.frombuffer((C.c_int32 * n).from_address(p.value), dtype=np.int32).reshape(S, slices, R)
+                 for p in (tail, head))
 
 
 def ep_tail_counters(h: int, S: int, R: int) -> np.ndarray:

@@ -62,7 +62,9 @@ struct WireEvent {
   uint32_t imm;
   uint16_t src;       // connection = source rank
   uint8_t dst_rank;   // the receiving rank (whose proxy this event reaches)
-  uint8_t ordered;    // sequenced message of the high-throughput mode
+  uint8_t ordered;    // 0 plain; 1 sequenced message of the chunked high-throughput mode;
+                      // 2 / 3 ring-buffer channel, sender -> receiver / receiver -> sender
+  uint16_t slice;     // ring-buffer channels: the token slice (part of the connection's identity)
 };
 
 struct alignas(64) ProxyThread {
@@ -77,7 +79,6 @@ struct alignas(64) ProxyThread {
   // proxy-performed peer writes (registered heaps): descriptors of the batch being filled, and the
   // batches in flight with the arrival notices they will release when their copy kernel is done
   static constexpr int kBatchSlots = 32;
-  hipStream_t stream = nullptr;
   hipEvent_t events[kBatchSlots] = {};
   CopyBatchArgs cur{};
   struct Batch {
@@ -91,6 +92,9 @@ struct alignas(64) ProxyThread {
   // ordered (high-throughput) channels: next sequence number and early arrivals per (source, destination rank)
   std::vector<uint32_t> next_seq;
   std::vector<std::map<uint32_t, WireEvent>> early;
+  // ring-buffer channels: the same per (source, slice, destination rank, direction)
+  std::vector<uint32_t> ring_next;
+  std::vector<std::map<uint32_t, WireEvent>> ring_early;
   uint64_t rng = 0;
   // statistics (written by the owner thread only, read racy-but-atomically)
   std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
@@ -117,12 +121,18 @@ struct ep_handle {
   int32_t *recv_count = nullptr;
   int *recv_flag = nullptr;  // posted count + 1, cleared by the GPU-side wait
   int32_t *recv_tail = nullptr;  // [S, R] rows announced per communication channel (ordered mode)
+  int32_t *ring_tail = nullptr, *ring_head = nullptr;  // [S, slices, R] rows announced / released per ring channel
+  void *d_ring_tail = nullptr, *d_ring_head = nullptr;
+  unsigned *ring_seq_fwd = nullptr, *ring_seq_rev = nullptr, *ring_cum_fwd = nullptr, *ring_cum_rev = nullptr;
+  uint64_t ring_slot_bytes = 0, ring_total_bytes = 0;
   std::atomic<int64_t> expected_drains{0};
   // registered heaps (symmetric memory): when set, the proxy performs the Writes
   std::atomic<const char *> src_base{nullptr};
   std::atomic<char *> dst_base{nullptr};
   uint64_t src_bytes = 0, dst_bytes = 0;
   int device = 0;
+  hipStream_t copy_stream = nullptr;  // the proxy's copy kernels (all threads; launches under copy_mu)
+  std::mutex copy_mu;
   // Barrier: a counter and a generation shared by the peer processes of one node
   struct SharedBarrier {
     std::atomic<uint32_t> arrived;
@@ -181,8 +191,13 @@ void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_
 // control buffer; arrivals for other experts never release it (Section 3.3,
 // "partial completion fence").
 void deliver_ordered(ep_handle *h, ProxyThread &P, const WireEvent &ev);
+void deliver_ring(ep_handle *h, ProxyThread &P, const WireEvent &ev);
 
 void deliver(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  if (ev.ordered >= 2) {
+    deliver_ring(h, P, ev);
+    return;
+  }
   if (ev.ordered) {
     deliver_ordered(h, P, ev);
     return;
@@ -254,6 +269,52 @@ void deliver_ordered(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
   }
 }
 
+// Ring-buffer channels (Section 3.3): the same in-sequence rule per channel (source, slice,
+// destination rank) and direction.  A tail Atomic adds its rows to the counter the receiving kernel
+// polls, a head Atomic to the one the sending kernel polls; a Write only takes its turn.
+inline uint32_t rebuild_seq(uint32_t next, uint32_t low16) {
+  uint32_t seq = (next & ~0xFFFFu) | low16;
+  if (seq + 0x8000u < next) seq += 0x10000u;
+  else if (seq >= next + 0x8000u && seq >= 0x10000u) seq -= 0x10000u;
+  return seq;
+}
+
+void apply_ring(ep_handle *h, ProxyThread &P, size_t chan, const WireEvent &ev, uint32_t seq) {
+  const uint32_t value = ev.imm & 0x7FFFu;
+  const uint32_t where = ((uint32_t)ev.slice << 8) | ev.dst_rank;
+  if (!(ev.imm >> 31)) {
+    log_event(h, P, 11, ev.src, where, seq);
+    return;
+  }
+  int32_t *ctr = (ev.ordered == 2 ? h->ring_tail : h->ring_head) + chan;
+  __atomic_store_n(ctr, __atomic_load_n(ctr, __ATOMIC_RELAXED) + (int32_t)value, __ATOMIC_RELEASE);
+  log_event(h, P, ev.ordered == 2 ? 12 : 13, ev.src, where, seq);
+  P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
+}
+
+void deliver_ring(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  const ep_config &c = h->cfg;
+  const size_t chan = ((size_t)ev.src * c.ht_slices + ev.slice) * c.num_ranks + ev.dst_rank;
+  const size_t dir = chan * 2 + (ev.ordered == 3);
+  uint32_t &next = P.ring_next[dir];
+  const uint32_t seq = rebuild_seq(next, (ev.imm >> 15) & 0xFFFFu);
+  const uint32_t where = ((uint32_t)ev.slice << 8) | ev.dst_rank;
+  log_event(h, P, ev.ordered == 3 ? 10 : ((ev.imm >> 31) ? 9 : 8), ev.src, where, seq);
+  if (seq != next) {
+    P.ring_early[dir].emplace(seq, ev);
+    bump(P.ordered_parked, 1);
+    return;
+  }
+  apply_ring(h, P, chan, ev, seq);
+  ++next;
+  std::map<uint32_t, WireEvent> &q = P.ring_early[dir];
+  for (auto it = q.find(next); it != q.end(); it = q.find(next)) {
+    apply_ring(h, P, chan, it->second, next);
+    q.erase(it);
+    ++next;
+  }
+}
+
 // The "network" between the two halves.  With reorder_window == 0 immediates
 // arrive in the order they were sent; otherwise up to reorder_window of them
 // are in flight and a seeded draw decides which arrives next (an unordered
@@ -294,9 +355,12 @@ void fail_hip(ep_handle *h) {
 // behind it.  Its notices stay with the batch until the event has fired.
 void launch_batch(ep_handle *h, ProxyThread &P) {
   if (P.cur.n == 0) return;
-  if (launch_copy_batch(P.cur, P.stream) != 0 ||
-      hipEventRecord(P.events[P.cur_slot], P.stream) != hipSuccess)
-    fail_hip(h);
+  {
+    std::lock_guard<std::mutex> g(h->copy_mu);  // launch and event stay adjacent in the shared stream
+    if (launch_copy_batch(P.cur, h->copy_stream) != 0 ||
+        hipEventRecord(P.events[P.cur_slot], h->copy_stream) != hipSuccess)
+      fail_hip(h);
+  }
   bump(P.copy_batches, 1);
   P.inflight.push_back(ProxyThread::Batch{P.cur_slot, std::move(P.cur_notices)});
   P.cur_notices.clear();
@@ -426,6 +490,40 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       transmit(h, P, WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | w1, (uint16_t)src, (uint8_t)dr, 1});
       break;
     }
+    case EP_OP_RING: {
+      const uint32_t kind = w1 >> 30, slice = le;
+      if (c.ht_slices <= 0 || (int)src >= c.num_src || (int)dr >= c.num_ranks || (int)slice >= c.ht_slices ||
+          kind > EP_RING_HEAD) {
+        reject(h, P);
+        return;
+      }
+      if (kind == EP_RING_WRITE) {
+        const uint32_t rows = ((w1 >> 24) & 0x3Fu) + 1;
+        const uint64_t len = (uint64_t)(w1 & 0xFFFFFFu) << 4, dof = (uint64_t)w3 << 4;
+        // the slot must be one of this channel's own, and the length what its rows need
+        const uint64_t first = ((uint64_t)slice * c.num_ranks + dr) * c.ht_ring_slots * h->ring_slot_bytes;
+        if (rows > (uint32_t)kChunkRows || len != 128u + (uint64_t)rows * 2u * c.hidden || dof < first ||
+            dof >= first + (uint64_t)c.ht_ring_slots * h->ring_slot_bytes || (dof - first) % h->ring_slot_bytes ||
+            dof + len > h->ring_total_bytes) {
+          reject(h, P);
+          return;
+        }
+        bump(P.writes, 1);
+        bump(P.write_bytes, len);
+        bump(P.write_rows, rows);
+        transmit(h, P, WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 2, (uint16_t)slice});
+      } else {
+        const uint32_t value = w1 & 0x3FFFFFFFu;
+        if (value > 0x7FFFu) {
+          reject(h, P);
+          return;
+        }
+        bump(P.atomics, 1);
+        transmit(h, P, WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | value, (uint16_t)src, (uint8_t)dr,
+                                 (uint8_t)(kind == EP_RING_TAIL ? 2 : 3), (uint16_t)slice});
+      }
+      break;
+    }
     case EP_OP_DRAIN: {
       // everything this thread handed to the transport must have completed
       launch_batch(h, P);
@@ -439,6 +537,13 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
             int zero = 0;
             h->proxy_error.compare_exchange_strong(zero, EP_ESTATE);
           }
+      // ... and the ring-buffer channels of this FIFO ((slice * R + rank) mod C == fifo), both directions
+      for (size_t ch = 0, n = P.ring_early.size() / 2; ch < n; ++ch)
+        if ((int)((ch % ((size_t)c.ht_slices * c.num_ranks)) % c.num_channels) == fifo &&
+            (!P.ring_early[2 * ch].empty() || !P.ring_early[2 * ch + 1].empty())) {
+          int zero = 0;
+          h->proxy_error.compare_exchange_strong(zero, EP_ESTATE);
+        }
       P.drains.store(P.drains.load(std::memory_order_relaxed) + 1, std::memory_order_release);
       break;
     }
@@ -555,6 +660,9 @@ int validate(const ep_config &c) {
   for (const char *p = c.barrier_name; *p; ++p)
     if (*p == '/') return EP_EINVAL;
   if (c.barrier_peers > 1 && !c.barrier_name[0]) return EP_EINVAL;
+  if (c.ht_slices < 0 || c.ht_slices > 4096 || c.ht_ring_slots < 0 || c.ht_ring_slots > 64) return EP_EINVAL;
+  if ((c.ht_slices > 0) != (c.ht_ring_slots > 0)) return EP_EINVAL;
+  if (c.ht_slices > 0 && ((int64_t)c.num_ranks * c.ht_ring_slots > 4096 || c.num_proxy_threads < 1)) return EP_EINVAL;
   return EP_OK;
 }
 
@@ -566,6 +674,8 @@ void free_all(ep_handle *h) {
     free(h->recv_count);
     free(h->recv_flag);
     free(h->recv_tail);
+    free(h->ring_tail);
+    free(h->ring_head);
     free(h->dev_error);
   } else {
     if (h->slots) (void)hipHostFree(h->slots);
@@ -573,9 +683,12 @@ void free_all(ep_handle *h) {
     if (h->recv_count) (void)hipHostFree(h->recv_count);
     if (h->recv_flag) (void)hipHostFree(h->recv_flag);
     if (h->recv_tail) (void)hipHostFree(h->recv_tail);
+    if (h->ring_tail) (void)hipHostFree(h->ring_tail);
+    if (h->ring_head) (void)hipHostFree(h->ring_head);
     if (h->dev_error) (void)hipHostFree(h->dev_error);
     void *dev[] = {h->ring.tail, h->ring.cached_head, h->ring.stalls, h->ring.refresh_lock, h->tile_hist, h->tile_base,
-                   h->chunk_cnt, h->expert_done, h->ticket, h->waves_done, h->ht_seq};
+                   h->chunk_cnt, h->expert_done, h->ticket, h->waves_done, h->ht_seq,
+                   h->ring_seq_fwd, h->ring_seq_rev, h->ring_cum_fwd, h->ring_cum_rev};
     for (void *p : dev)
       if (p) (void)hipFree(p);
   }
@@ -650,6 +763,11 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
   if (!rc) rc = pinned_alloc(h->host_only, &h->recv_flag, (size_t)S * E * 4);
   if (!rc) rc = pinned_alloc(h->host_only, &h->recv_tail, (size_t)S * cfg->num_ranks * 4);
   if (!rc) rc = pinned_alloc(h->host_only, &h->dev_error, 64);
+  const size_t nring = (size_t)S * cfg->ht_slices * cfg->num_ranks;
+  h->ring_slot_bytes = 128u + (uint64_t)kChunkRows * 2u * cfg->hidden;
+  h->ring_total_bytes = (uint64_t)cfg->ht_slices * cfg->num_ranks * cfg->ht_ring_slots * h->ring_slot_bytes;
+  if (!rc && nring) rc = pinned_alloc(h->host_only, &h->ring_tail, nring * 4);
+  if (!rc && nring) rc = pinned_alloc(h->host_only, &h->ring_head, nring * 4);
   if (!rc && !h->host_only) {
     h->ntiles_cap = (cfg->max_tokens + kLayoutTile - 1) / kLayoutTile;
     h->chunks_per_expert = (cfg->max_tokens + kChunkRows - 1) / kChunkRows;
@@ -665,6 +783,14 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     if (!rc) rc = dev_alloc_zero(&h->ticket, 4);
     if (!rc) rc = dev_alloc_zero(&h->waves_done, 4);
     if (!rc) rc = dev_alloc_zero(&h->ht_seq, (size_t)S * cfg->num_ranks * 4);
+    if (nring) {
+      if (!rc) rc = dev_alloc_zero(&h->ring_seq_fwd, nring * 4);
+      if (!rc) rc = dev_alloc_zero(&h->ring_seq_rev, nring * 4);
+      if (!rc) rc = dev_alloc_zero(&h->ring_cum_fwd, nring * 4);
+      if (!rc) rc = dev_alloc_zero(&h->ring_cum_rev, nring * 4);
+      if (!rc && !HIP_OK(hipHostGetDevicePointer(&h->d_ring_tail, h->ring_tail, 0))) rc = EP_EHIP;
+      if (!rc && !HIP_OK(hipHostGetDevicePointer(&h->d_ring_head, h->ring_head, 0))) rc = EP_EHIP;
+    }
     void *dp = nullptr;
     if (!rc && !HIP_OK(hipHostGetDevicePointer(&dp, h->slots, 0))) rc = EP_EHIP;
     h->ring.slots = dp;
@@ -718,6 +844,8 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     P.parked.resize((size_t)S * E);
     P.next_seq.assign((size_t)S * cfg->num_ranks, 0);
     P.early.resize((size_t)S * cfg->num_ranks);
+    P.ring_next.assign(nring * 2, 0);
+    P.ring_early.resize(nring * 2);
     P.rng = cfg->reorder_seed * 0x9E3779B97F4A7C15ull + (uint64_t)i;
   }
   for (int i = 0; i < h->nthreads; ++i) h->threads[i].th = std::thread(proxy_main, h, &h->threads[i]);
@@ -737,8 +865,8 @@ int ep_proxy_stop(ep_handle *h) {
     if (!P.gpu_ready) continue;
     for (hipEvent_t &e : P.events)
       if (e) (void)hipEventDestroy(e);
-    if (P.stream) (void)hipStreamDestroy(P.stream);
   }
+  if (h->copy_stream) (void)hipStreamDestroy(h->copy_stream);
   free_all(h);
   return rc;
 }
@@ -756,12 +884,17 @@ int ep_register_heaps(ep_handle *h, const void *d_src_base, int64_t src_bytes, v
   if (src_bytes <= 0 || dst_bytes <= 0 || (((uintptr_t)d_src_base | (uintptr_t)d_dst_base) & 15)) return EP_EINVAL;
   if (src_bytes > (1ll << 36) || dst_bytes > (1ll << 36)) return EP_EINVAL;  // offsets travel as 32-bit counts of 16 bytes
   if (h->nthreads < 1) return EP_EINVAL;
-  // what a proxy thread needs to issue the writes: a stream of its own (default priority) and
-  // completion events; made once, on first registration
+  // What the proxy needs to issue the writes, made once, on first registration: ONE stream (default
+  // priority) shared by all proxy threads, and completion events per thread.  One stream, because a
+  // process has few hardware queues (4 here) and streams beyond that share one: a copy kernel queued
+  // behind a dispatch kernel that is itself blocked on a Drain (which waits for that copy) would never
+  // start.  The caller's stream and this one get queues of their own as long as the process keeps
+  // fewer streams than hardware queues; if they ever do collide, the kernel's bounded wait reports
+  // EP_ETIMEOUT.
+  if (!h->copy_stream && !HIP_OK(hipStreamCreateWithFlags(&h->copy_stream, hipStreamNonBlocking))) return EP_EHIP;
   for (int i = 0; i < h->nthreads; ++i) {
     ProxyThread &P = h->threads[i];
     if (P.gpu_ready) continue;
-    if (!HIP_OK(hipStreamCreateWithFlags(&P.stream, hipStreamNonBlocking))) return EP_EHIP;
     for (hipEvent_t &e : P.events)
       if (!HIP_OK(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return EP_EHIP;
     P.gpu_ready = true;
@@ -1036,6 +1169,57 @@ int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv
   *recv_count = h->recv_count;
   if (d_recv_count) *d_recv_count = (const int32_t *)h->d_recv_count;
   return EP_OK;
+}
+
+int ep_ring_counters(ep_handle *h, const int32_t **ring_tail, const int32_t **ring_head) {
+  if (!h || !ring_tail || !ring_head) return EP_EINVAL;
+  if (h->cfg.ht_slices <= 0) return EP_ESTATE;
+  *ring_tail = h->ring_tail;
+  *ring_head = h->ring_head;
+  return EP_OK;
+}
+
+int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const int32_t *d_dst_row, int32_t T,
+                   int32_t src_rank, void *d_ring, int64_t ring_bytes, void *d_recv, int64_t recv_rows,
+                   void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only || h->cfg.ht_slices <= 0) return EP_ESTATE;
+  const ep_config &c = h->cfg;
+  if (T < 0 || T > c.max_tokens || src_rank < 0 || src_rank >= c.num_src) return EP_EINVAL;
+  if (recv_rows < 0 || recv_rows > c.heap_rows) return EP_EINVAL;
+  if (!d_ring || ring_bytes < 0 || (uint64_t)ring_bytes < h->ring_total_bytes) return EP_EINVAL;
+  if (T > 0 && (!d_x || !d_topk_idx || !d_dst_row || !d_recv)) return EP_EINVAL;
+  if (((uintptr_t)d_x | (uintptr_t)d_recv | (uintptr_t)d_ring) & 15) return EP_EINVAL;
+  if (h->ring_total_bytes >> 4 > 0x7FFFFFFFull) return EP_EINVAL;  // slot offsets travel as 31-bit counts of 16 bytes
+  if (int e = dev_err(h)) return e;
+  HtRingArgs a{};
+  a.x = d_x;
+  a.idx = d_topk_idx;
+  a.dst_row = d_dst_row;
+  a.ring_buf = d_ring;
+  a.recv = d_recv;
+  a.recv_rows = recv_rows;
+  a.T = T;
+  a.K = c.top_k;
+  a.H = c.hidden;
+  a.E_loc = h->E_loc;
+  a.R = c.num_ranks;
+  a.src = src_rank;
+  a.slices = c.ht_slices;
+  a.slice_len = T > 0 ? (T + c.ht_slices - 1) / c.ht_slices : 1;
+  a.W = c.ht_ring_slots;
+  a.slot_bytes = (unsigned)h->ring_slot_bytes;
+  const size_t first = (size_t)src_rank * c.ht_slices * c.num_ranks;
+  a.tail = (const int32_t *)h->d_ring_tail + first;
+  a.head = (const int32_t *)h->d_ring_head + first;
+  a.seq_fwd = h->ring_seq_fwd + first;
+  a.seq_rev = h->ring_seq_rev + first;
+  a.cum_fwd = h->ring_cum_fwd + first;
+  a.cum_rev = h->ring_cum_rev + first;
+  a.waves_done = h->waves_done;
+  a.fifo = h->ring;
+  h->expected_drains.fetch_add(c.num_channels, std::memory_order_relaxed);
+  return HIP_OK((hipError_t)launch_ht_ring(a, stream)) ? EP_OK : EP_EHIP;
 }
 
 int ep_tail_counters(ep_handle *h, const int32_t **recv_tail) {

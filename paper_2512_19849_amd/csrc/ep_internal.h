@@ -127,6 +127,22 @@ struct CopyBatchArgs {
   } d[kCopyBatchMax];
 };
 
+// Ring-buffer channels of the high-throughput mode: one sender and one receiver workgroup per slice.
+struct HtRingArgs {
+  const void *x;           // bf16 [T,H]
+  const int32_t *idx;      // [T,K]
+  const int32_t *dst_row;  // [T,K]
+  void *ring_buf;          // [slices][R][W] slots of slot_bytes
+  void *recv;              // bf16 [recv_rows,H]
+  long long recv_rows;
+  int32_t T, K, H, E_loc, R, src, slices, slice_len, W;
+  unsigned slot_bytes;
+  const int32_t *tail, *head;                       // pinned host [slices*R] of this source, written by the proxy
+  unsigned *seq_fwd, *seq_rev, *cum_fwd, *cum_rev;  // device [slices*R] of this source
+  unsigned *waves_done;
+  RingDev fifo;
+};
+
 struct RecvWaitArgs {
   int *flags;        // pinned host [S*E]: 0 = not arrived, else posted count + 1 (written by the proxy)
   int32_t *out;      // device [E] or null
@@ -141,6 +157,7 @@ int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
 int launch_combine(const CombineArgs &a, void *stream);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
 int launch_barrier(const RingDev &ring, void *stream);
+int launch_ht_ring(const HtRingArgs &a, void *stream);
 int launch_copy_batch(const CopyBatchArgs &b, void *stream);
 int launch_dedup(const DedupArgs &a, void *stream);
 int launch_gather_index(const GatherIndexArgs &a, void *stream);

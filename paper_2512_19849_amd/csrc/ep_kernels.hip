@@ -450,19 +450,23 @@ EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
 // Kernel epilogue with EP_CMD_DRAIN: the last wavefront of the grid pushes a
 // Drain on every channel and blocks on Check-completion for each (Section 3.1:
 // Drain and Barrier are blocking on the GPU side).
-EP_DEV void emit_drain(const DispatchArgs &a, int lane) {
+EP_DEV void drain_all_channels(const RingDev &ring, unsigned *waves_done, unsigned src, int lane) {
   const unsigned total = gridDim.x * (blockDim.x >> 6);
   unsigned done = 0;
   wait_for_own_stores();  // this wave's commands are in their rings before it reports done
   if (lane == 0)
-    done = __hip_atomic_fetch_add(a.waves_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+    done = __hip_atomic_fetch_add(waves_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
   done = __builtin_amdgcn_readfirstlane(done);
   if (done != total) return;
-  if (lane == 0) __hip_atomic_store(a.waves_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  for (unsigned c = lane; c < a.ring.channels; c += 64) {
-    const unsigned long long idx = ring_push(a.ring, c, cmd_w0(EP_OP_DRAIN, a.src, 0, 0), 0u, 0u, 0u);
-    if (idx != ~0ull) ring_wait_completion(a.ring, c, idx);
+  if (lane == 0) __hip_atomic_store(waves_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (unsigned c = lane; c < ring.channels; c += 64) {
+    const unsigned long long idx = ring_push(ring, c, cmd_w0(EP_OP_DRAIN, src, 0, 0), 0u, 0u, 0u);
+    if (idx != ~0ull) ring_wait_completion(ring, c, idx);
   }
+}
+
+EP_DEV void emit_drain(const DispatchArgs &a, int lane) {
+  drain_all_channels(a.ring, a.waves_done, (unsigned)a.src, lane);
 }
 
 // ------------------------------------------------------------ dispatch bf16
@@ -996,6 +1000,290 @@ int launch_copy_batch(const CopyBatchArgs &b, void *stream) {
   if (gx < 1) gx = 1;
   if (gx > 64) gx = 64;  // 64 x 4 KiB per pass and descriptor, grid-stride beyond
   hipLaunchKernelGGL(copy_batch_kernel, dim3(gx, (unsigned)b.n), dim3(256), 0, (hipStream_t)stream, b);
+  return (int)hipGetLastError();
+}
+
+
+// ------------------------------------------- ring-buffer channels (HT mode)
+// Section 3.3 ("partial ordering"): tokens travel through rings of chunk slots; the sender may reuse
+// a slot only after the receiver released it (head), the receiver may read it only after it was
+// announced (tail); Write, tail Atomic and head Atomic are sequenced per channel and pass through the
+// proxy.  A slice's sender and receiver workgroups are 8 apart in the grid (so that they become
+// resident together); a workgroup depends on no workgroup but its partner.
+// Every wait is bounded; after a timeout the workgroup's abort flag sends every wave to the exit.
+constexpr int kHtMaxRanks = 256, kHtMaxSlots = 4096, kHtHeader = 128;
+
+struct HtShared {
+  int total[kHtMaxRanks];      // rows of channel (slice, r) in this dispatch
+  int fill[kHtMaxRanks];       // sender: positions handed out; receiver: next chunk to consume
+  unsigned seqb[kHtMaxRanks];  // the channel's sequence number before this dispatch
+  unsigned cumb[kHtMaxRanks];  // rows the channel carried before this dispatch
+  unsigned seen[kHtMaxRanks];  // sender: rows released so far (cached head); receiver: first chunk of this sweep
+  int lock[kHtMaxRanks];       // sender: who refreshes the cached head; receiver: end chunk of this sweep
+  int done[kHtMaxSlots];       // sender: rows stored per (r, slot)
+  int abort, remaining, progress, idle;
+};
+
+#define HT_LD(p) __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
+#define HT_ST(p, v) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
+
+EP_DEV bool ht_valid(const HtRingArgs &a, int e, int row) {
+  return e >= 0 && e / a.E_loc < a.R && row >= 0 && row < a.recv_rows;
+}
+
+// A wave moves a row in pieces of B KiB: B 16-byte loads per lane in flight, then B stores.
+template <bool STREAM, int B>
+EP_DEV void ht_load_piece(u32x4 (&r)[B], const u32x4 *src, int v0, int nvec) {
+#pragma unroll
+  for (int i = 0; i < B; ++i)
+    if (v0 + i * 64 < nvec) r[i] = STREAM ? __builtin_nontemporal_load(src + v0 + i * 64) : src[v0 + i * 64];
+}
+template <bool THROUGH, int B>
+EP_DEV void ht_store_piece(const u32x4 (&r)[B], u32x4 *dst, int v0, int nvec) {
+#pragma unroll
+  for (int i = 0; i < B; ++i)
+    if (v0 + i * 64 < nvec) {
+      if (THROUGH) store_payload(dst + v0 + i * 64, r[i]);
+      else dst[v0 + i * 64] = r[i];
+    }
+}
+template <bool STREAM, bool THROUGH, int B>
+EP_DEV void ht_copy_row(u32x4 (&r)[B], u32x4 *dst, const u32x4 *src, int nvec, int lane) {
+  for (int v0 = lane; v0 < nvec; v0 += 64 * B) {
+    ht_load_piece<STREAM, B>(r, src, v0, nvec);
+    ht_store_piece<THROUGH, B>(r, dst, v0, nvec);
+  }
+}
+
+// Sender: wait until `need` rows of channel r have been released in this dispatch.
+EP_DEV bool ht_wait_head(const HtRingArgs &a, HtShared &sh, int chan, int r, unsigned need, int lane) {
+  const unsigned long long t0 = wall_clock64();
+  for (;;) {
+    if (HT_LD(&sh.abort)) return false;
+    if (HT_LD(&sh.seen[r]) >= need) return true;
+    if (lane == 0 && __hip_atomic_exchange(&sh.lock[r], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) {
+      // one PCIe read on behalf of every wave of the workgroup that waits for this channel
+      const unsigned v =
+          (unsigned)__hip_atomic_load(a.head + chan, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) - sh.cumb[r];
+      __hip_atomic_fetch_max(&sh.seen[r], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      HT_ST(&sh.lock[r], 0);
+    }
+    if (wall_clock64() - t0 > a.fifo.timeout_ticks) {
+      dev_set_error(a.fifo.error, EP_ETIMEOUT);
+      HT_ST(&sh.abort, 1);
+      return false;
+    }
+    __builtin_amdgcn_s_sleep(32);
+  }
+}
+
+// Sender bookkeeping for the rows a wave has stored but not yet counted: lane k keeps (rank, chunk)
+// of the token's k-th entry.  After one wait for the wave's stores, every such lane adds its row to
+// the chunk's count; the lane that completes a chunk announces it (Write, then the tail Atomic).
+EP_DEV void ht_count_stored(const HtRingArgs &a, HtShared &sh, int c, bool mine, int r, int n) {
+  wait_for_own_stores();
+  if (!mine) return;
+  const int w = n % a.W, sz = min(kChunkRows, sh.total[r] - (n << 5));
+  const int old = __hip_atomic_fetch_add(&sh.done[r * a.W + w], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  if (old + 1 != sz) return;
+  HT_ST(&sh.done[r * a.W + w], 0);
+  const int chan = c * a.R + r;
+  const unsigned seq = sh.seqb[r] + 2u * (unsigned)n, fifo = (unsigned)chan % a.fifo.channels;
+  const unsigned len = (unsigned)kHtHeader + (unsigned)sz * 2u * (unsigned)a.H;
+  const unsigned w0 = cmd_w0(EP_OP_RING, a.src, (unsigned)r, (unsigned)c);
+  ring_push(a.fifo, fifo, w0, ((unsigned)EP_RING_WRITE << 30) | ((unsigned)(sz - 1) << 24) | (len >> 4), seq,
+            (unsigned)((((size_t)chan * a.W + w) * a.slot_bytes) >> 4));
+  ring_push(a.fifo, fifo, w0, ((unsigned)EP_RING_TAIL << 30) | (unsigned)sz, seq + 1u, 0u);
+}
+
+EP_DEV void ht_sender(const HtRingArgs &a, HtShared &sh, int c, int t0, int t1) {
+  const int lane = lane_id(), wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  const int nvec = a.H >> 3;
+  const unsigned rb = 2u * (unsigned)a.H;
+  for (int t = t0 + wave; t < t1; t += nwaves) {
+    const u32x4 *xrow = (const u32x4 *)((const char *)a.x + (size_t)t * rb);
+    bool mine = false;  // lane k: entry k of this token is stored but not yet counted
+    int my_r = 0, my_n = 0;
+    for (int k = 0; k < a.K; ++k) {
+      const int e = a.idx[(size_t)t * a.K + k], row = a.dst_row[(size_t)t * a.K + k];
+      if (!ht_valid(a, e, row)) continue;
+      if (HT_LD(&sh.abort)) return;
+      const int r = e / a.E_loc, chan = c * a.R + r;
+      // positions are handed out in arrival order
+      int p = 0;
+      if (lane == 0) p = __hip_atomic_fetch_add(&sh.fill[r], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      p = __builtin_amdgcn_readfirstlane(p);
+      const int n = p >> 5, j = p & 31, w = n % a.W;
+      if (n >= a.W && HT_LD(&sh.seen[r]) < 32u * (unsigned)(n - a.W + 1)) {
+        // The slot is not known to be free.  Rows this wave has stored but not counted could be what
+        // another wave's chunk is waiting for, so they are counted before this wave blocks: a waiting
+        // wave then holds nothing but the position it waits for, and the rows of a channel's oldest
+        // unreleased chunk can always be written.
+        if (__any(mine)) {
+          ht_count_stored(a, sh, c, mine, my_r, my_n);
+          mine = false;
+        }
+        if (!ht_wait_head(a, sh, chan, r, 32u * (unsigned)(n - a.W + 1), lane)) return;
+      }
+      char *slot = (char *)a.ring_buf + ((size_t)chan * a.W + w) * a.slot_bytes;
+      u32x4 *dst = (u32x4 *)(slot + kHtHeader + (size_t)j * rb);
+      u32x4 regs[8];  // cached loads: the token's row comes from HBM once and from the L2 for its other k
+      ht_copy_row<false, true, 8>(regs, dst, xrow, nvec, lane);
+      if (lane == 0) __hip_atomic_store((int *)slot + j, row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (lane == (k & 63)) {
+        mine = true;
+        my_r = r;
+        my_n = n;
+      }
+      if ((k & 63) == 63 || k == a.K - 1) {  // (top-k is at most 64: one entry per lane)
+        ht_count_stored(a, sh, c, mine, my_r, my_n);
+        mine = false;
+      }
+    }
+    if (__any(mine)) ht_count_stored(a, sh, c, mine, my_r, my_n);  // the last k was masked
+  }
+}
+
+EP_DEV void ht_receiver(const HtRingArgs &a, HtShared &sh, int c) {
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const int nvec = a.H >> 3;
+  const unsigned rb = 2u * (unsigned)a.H;
+  unsigned long long last = wall_clock64();
+  for (;;) {
+    // which chunks have been announced since the last sweep (at most W per channel)
+    for (int r = tid; r < a.R; r += blockDim.x) {
+      const int tot = sh.total[r], nch = (tot + 31) >> 5, n0 = sh.fill[r];
+      int hi = n0;
+      if (n0 < nch) {
+        const unsigned avail =
+            (unsigned)__hip_atomic_load(a.tail + c * a.R + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) - sh.cumb[r];
+        while (hi < nch && hi - n0 < a.W && avail >= (unsigned)min((hi + 1) << 5, tot)) ++hi;
+      }
+      sh.seen[r] = (unsigned)n0;
+      sh.lock[r] = hi;
+    }
+    __syncthreads();
+    // move their rows to where the header says; rows are dealt out to the waves round-robin
+    int q = 0;
+    for (int r = 0; r < a.R; ++r) {
+      const int lo = (int)sh.seen[r], hi = sh.lock[r];
+      for (int n = lo; n < hi; ++n) {
+        if (q == 0) {
+          // What the tails announced was written by another workgroup, possibly into lines an L2 still
+          // holds from the slot's previous use: drop those before the first read of the sweep (the
+          // acquire that pairs with the tail; not done on idle sweeps, it empties the XCD's L2).
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
+        const int sz = min(kChunkRows, sh.total[r] - (n << 5));
+        const char *slot = (const char *)a.ring_buf + ((size_t)(c * a.R + r) * a.W + n % a.W) * a.slot_bytes;
+        for (int j = 0; j < sz; ++j, ++q) {
+          if (q % nwaves != wave) continue;
+          const int row = __builtin_nontemporal_load((const int *)slot + j);
+          if (row < 0 || row >= a.recv_rows) {
+            dev_set_error(a.fifo.error, EP_EBOUNDS);
+            continue;
+          }
+          u32x4 regs[8];
+          ht_copy_row<true, false, 8>(regs, (u32x4 *)((char *)a.recv + (size_t)row * rb),
+                                   (const u32x4 *)(slot + kHtHeader + (size_t)j * rb), nvec, lane);
+        }
+      }
+    }
+    wait_for_own_stores();  // every load of a slot has returned before the slot is released
+    __syncthreads();
+    // release the slots: one head Atomic per consumed chunk, numbered on the reverse channel
+    for (int r = tid; r < a.R; r += blockDim.x) {
+      const int lo = (int)sh.seen[r], hi = sh.lock[r];
+      for (int n = lo; n < hi; ++n) {
+        const int sz = min(kChunkRows, sh.total[r] - (n << 5));
+        ring_push(a.fifo, (unsigned)(c * a.R + r) % a.fifo.channels, cmd_w0(EP_OP_RING, a.src, (unsigned)r, (unsigned)c),
+                  ((unsigned)EP_RING_HEAD << 30) | (unsigned)sz, sh.seqb[r] + (unsigned)n, 0u);
+      }
+      if (hi > lo) {
+        sh.fill[r] = hi;
+        __hip_atomic_fetch_sub(&sh.remaining, hi - lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        HT_ST(&sh.progress, 1);
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned long long now = wall_clock64();
+      const int progressed = HT_LD(&sh.progress);
+      sh.idle = !progressed;
+      if (HT_LD(&sh.remaining) <= 0) {
+        sh.abort = 2;  // all chunks of the slice consumed
+      } else if (progressed) {
+        last = now;
+        sh.progress = 0;
+      } else if (now - last > a.fifo.timeout_ticks) {
+        dev_set_error(a.fifo.error, EP_ETIMEOUT);
+        sh.abort = 1;
+      }
+    }
+    __syncthreads();
+    if (sh.abort) break;
+    if (sh.idle) __builtin_amdgcn_s_sleep(127);
+  }
+}
+
+__global__ __launch_bounds__(1024) void ht_ring_kernel(HtRingArgs a) {
+  __shared__ HtShared sh;
+  // Workgroups are handed to the 8 XCDs round-robin.  In every run of 16 workgroups the first 8 are
+  // the senders of 8 consecutive slices and the last 8 their receivers, so both roles are spread over
+  // all XCDs (and their links to memory), and a slice's sender and receiver share an XCD and its L2.
+  const int tid = threadIdx.x;
+  const int c = ((blockIdx.x >> 4) << 3) | (blockIdx.x & 7);
+  const bool sender = !(blockIdx.x & 8);
+  const bool idle_wg = c >= a.slices;  // padding of the last run: takes part in nothing but the final count
+  const int t0 = idle_wg ? 0 : min(a.T, c * a.slice_len), t1 = idle_wg ? 0 : min(a.T, t0 + a.slice_len);
+  for (int r = tid; r < a.R; r += blockDim.x) {
+    sh.total[r] = 0;
+    sh.fill[r] = 0;
+    sh.seen[r] = 0;
+    sh.lock[r] = 0;
+    sh.seqb[r] = idle_wg ? 0u : (sender ? a.seq_fwd : a.seq_rev)[c * a.R + r];
+    sh.cumb[r] = idle_wg ? 0u : (sender ? a.cum_fwd : a.cum_rev)[c * a.R + r];
+  }
+  for (int i = tid; i < a.R * a.W; i += blockDim.x) sh.done[i] = 0;
+  if (tid == 0) sh.abort = sh.remaining = sh.progress = sh.idle = 0;
+  __syncthreads();
+  // rows per channel of this slice: both sides count them from the routing table (the count
+  // notification that precedes a high-throughput dispatch)
+  for (int i = tid; i < (t1 - t0) * a.K; i += blockDim.x) {
+    const int e = a.idx[(size_t)t0 * a.K + i], row = a.dst_row[(size_t)t0 * a.K + i];
+    if (ht_valid(a, e, row))
+      __hip_atomic_fetch_add(&sh.total[e / a.E_loc], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    else if (e >= 0)
+      dev_set_error(a.fifo.error, EP_EBOUNDS);
+  }
+  __syncthreads();
+  if (sender) {
+    ht_sender(a, sh, c, t0, t1);
+  } else {
+    for (int r = tid; r < a.R; r += blockDim.x)
+      __hip_atomic_fetch_add(&sh.remaining, (sh.total[r] + 31) >> 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __syncthreads();
+    ht_receiver(a, sh, c);
+  }
+  __syncthreads();
+  // the channels' running sequence numbers and row totals, for the next dispatch
+  for (int r = tid; r < a.R && !idle_wg; r += blockDim.x) {
+    const unsigned nch = (unsigned)(sh.total[r] + 31) >> 5;
+    if (sender) {
+      a.seq_fwd[c * a.R + r] = sh.seqb[r] + 2u * nch;
+      a.cum_fwd[c * a.R + r] = sh.cumb[r] + (unsigned)sh.total[r];
+    } else {
+      a.seq_rev[c * a.R + r] = sh.seqb[r] + nch;
+      a.cum_rev[c * a.R + r] = sh.cumb[r] + (unsigned)sh.total[r];
+    }
+  }
+  drain_all_channels(a.fifo, a.waves_done, (unsigned)a.src, lane_id());
+}
+
+int launch_ht_ring(const HtRingArgs &a, void *stream) {
+  int threads = env_int("EP_HT_THREADS", 1024);
+  if (threads < 64 || threads > 1024 || (threads & 63)) threads = 1024;
+  hipLaunchKernelGGL(ht_ring_kernel, dim3(16u * (unsigned)((a.slices + 7) / 8)), dim3((unsigned)threads), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }
 

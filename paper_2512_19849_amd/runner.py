@@ -42,7 +42,8 @@ class EPRunner:
     def __init__(self, R: int, E: int, K: int, H: int, max_tokens: int, S: int = 1, self_rank: int = 0,
                  num_channels: int = 8, ring_entries: int = 4096, num_proxy_threads: int = 4,
                  reorder_window: int = 0, reorder_seed: int = 0, spin_timeout_ms: int = 0, heap_rows: int = 0,
-                 flags: int = 0, device: str = "cuda", barrier_peers: int = 0, barrier_name: str = ""):
+                 flags: int = 0, device: str = "cuda", barrier_peers: int = 0, barrier_name: str = "",
+                 ht_slices: int = 0, ht_ring_slots: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("EPRunner needs a HIP device; there is no CPU path")
         self.R, self.E, self.K, self.H, self.S, self.T_cap = R, E, K, H, S, max_tokens
@@ -51,7 +52,8 @@ class EPRunner:
         self.heap_rows = heap_rows or S * max_tokens * K
         self.h = ep.ep_proxy_start(R, E, K, H, max_tokens, S, self_rank, num_channels, ring_entries,
                                    num_proxy_threads, reorder_window, reorder_seed, spin_timeout_ms, heap_rows,
-                                   flags, barrier_peers, barrier_name)
+                                   flags, barrier_peers, barrier_name, ht_slices, ht_ring_slots)
+        self.ht_slices, self.ht_ring_slots = ht_slices, ht_ring_slots
         i32 = dict(dtype=torch.int32, device=self.dev)
         self.lay = LayoutOut(
             count=torch.zeros((S, E), **i32), expert_total=torch.zeros(E, **i32), rank_total=torch.zeros(R, **i32),
@@ -96,6 +98,13 @@ class EPRunner:
 
     def register_heaps(self, src: Optional[torch.Tensor], dst: Optional[torch.Tensor]) -> None:
         ep.ep_register_heaps(self.h, src, dst)
+
+    def ht_ring_bytes(self) -> int:
+        return self.ht_slices * self.R * self.ht_ring_slots * (128 + 32 * 2 * self.H)
+
+    def ht_dispatch(self, x: torch.Tensor, topk_idx_s: torch.Tensor, lay: LayoutOut, ring: torch.Tensor,
+                    recv: torch.Tensor, src: int = 0) -> None:
+        ep.ep_ht_dispatch(self.h, x, topk_idx_s, lay.dst_row[src], x.shape[0], src, ring, recv, recv.shape[0])
 
     def recv_wait(self, counts_out: Optional[torch.Tensor] = None, src: int = 0, rank_filter: int = -1) -> None:
         ep.ep_recv_wait(self.h, src, rank_filter, counts_out)

@@ -871,6 +871,115 @@ def test_limits_round_trip(epmod, oracle, S, T, K, E, R, H):
 
 
 # ---------------------------------------------------------------------------- Barrier
+# ------------------------------------- ring-buffer channels (HT mode storage)
+@pytest.mark.parametrize("cid,T,mask,slices,W,window,threads", [
+    (1, None, 0.0, 4, 2, 0, 2), (1, 50, 0.3, 7, 1, 5, 1), (4, 700, 0.0, 16, 2, 16, 4), (5, 1000, 0.1, 8, 3, 0, 4),
+    (4, 700, 0.05, 2, 1, 0, 4),       # ~175 rows per channel through a single slot: every chunk waits for a release
+    (2, 128, 0.0, 3, 1, 3, 4), (1, 3, 0.0, 8, 2, 0, 2)])
+def test_ht_ring_dispatch(epmod, oracle, cid, T, mask, slices, W, window, threads):
+    """Rows travel sender workgroup -> ring slot -> receiver workgroup -> packed receive buffer, slots are
+    reused under head/tail flow control, and all three message kinds pass through the proxy.  The receive
+    buffer must equal the plain definition of dispatch; the messages the oracle's expected multiset; the
+    proxy's trace the ring protocol (in-sequence application, no overwrite, no stale read)."""
+    cfg = g.config(cid, S=1)
+    idx, _ = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=29)
+    T = idx.shape[1]
+    rows = int((idx >= 0).sum()) + 2
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    per_channel = oracle.ring_channel_rows(idx[0], cfg.E_loc, cfg.R, slices)
+    nch = -(-per_channel // 32)
+    with _runner(epmod, cfg, T, flags=flags, heap_rows=rows, ht_slices=slices, ht_ring_slots=W,
+                 reorder_window=window, reorder_seed=2, num_proxy_threads=threads) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+        assert r.ht_ring_bytes() == oracle.ring_bytes(cfg.H, cfg.R, slices, W)
+        recv = torch.empty((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+        want_cmds = None
+        for it in range(2):                      # the second call continues the channels' numbering and counters
+            x = g.activations(cfg, it, T=T)
+            recv.fill_(-1.5)
+            r.ht_dispatch(bits_to_bf16(x), d_idx[0], lay, ring, recv)
+            r.wait()
+            torch.cuda.synchronize()
+            want, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows, -1, fill=0xBFC0)
+            assert np.array_equal(bf16_to_bits(recv), want), it
+            exp = oracle.expected_ring_cmds(idx[0], 0, cfg.E_loc, cfg.R, cfg.H, slices, W, 2 * nch * it, nch * it)
+            want_cmds = exp if want_cmds is None else want_cmds + exp
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        assert st["drains"] == 2 * 8 and st["writes"] == 2 * int(nch.sum()) and st["atomics"] == 4 * int(nch.sum())
+        assert oracle.ring_cmd_multiset(epmod.ep_cmd_log(r.h)) == want_cmds
+        res = oracle.check_ring_trace(epmod.ep_event_log(r.h), W)
+        assert res["applied"] == 6 * int(nch.sum())
+        tail, head = epmod.ep_ring_counters(r.h, 1, slices, cfg.R)
+        assert np.array_equal(tail[0], 2 * per_channel) and np.array_equal(head[0], 2 * per_channel)
+
+
+@pytest.mark.parametrize("cid,slices,W", [(4, 128, 2), (5, 64, 4)])
+def test_ht_ring_dispatch_full_size(epmod, oracle, cid, slices, W):
+    """The full prefill-sized workloads through the rings, in the shape the timing suite launches."""
+    cfg = g.config(cid, S=1)
+    idx, _ = g.routing_all(cfg)
+    x = g.activations(cfg)
+    rows = idx.size
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    oracle.set_threads(oracle.max_threads())
+    try:
+        want, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+    finally:
+        oracle.set_threads(1)
+    per_channel = oracle.ring_channel_rows(idx[0], cfg.E_loc, cfg.R, slices)
+    with _runner(epmod, cfg, ht_slices=slices, ht_ring_slots=W, spin_timeout_ms=10000) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+        recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+        r.ht_dispatch(bits_to_bf16(x), d_idx[0], lay, ring, recv)
+        r.wait()
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_to_bits(recv), want)
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        assert st["write_rows"] == rows and st["writes"] == int((-(-per_channel // 32)).sum())
+        tail, head = epmod.ep_ring_counters(r.h, 1, slices, cfg.R)
+        assert np.array_equal(tail[0], per_channel) and np.array_equal(head[0], per_channel)
+
+
+def test_ht_ring_dispatch_argument_errors(epmod):
+    cfg = g.config(1)
+    x = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+    recv = torch.zeros((cfg.T * cfg.K, cfg.H), dtype=torch.bfloat16, device="cuda")
+    idx = _dev(g.routing_all(cfg)[0])
+
+    def rc_of(fn):
+        with pytest.raises(epmod.EPError) as ei:
+            fn()
+        return ei.value.rc
+    with _runner(epmod, cfg) as r:                                   # no ring channels configured
+        lay = r.layout(idx)
+        ring = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+        assert rc_of(lambda: r.ht_dispatch(x, idx[0], lay, ring, recv)) == epmod.EP_ESTATE
+    with _runner(epmod, cfg, ht_slices=2, ht_ring_slots=2) as r:
+        lay = r.layout(idx)
+        small = torch.zeros(r.ht_ring_bytes() - 16, dtype=torch.uint8, device="cuda")
+        assert rc_of(lambda: r.ht_dispatch(x, idx[0], lay, small, recv)) == epmod.EP_EINVAL
+        ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+        assert rc_of(lambda: epmod.ep_ht_dispatch(r.h, x, idx[0], lay.dst_row[0], cfg.T, 1, ring, recv,
+                                                  recv.shape[0])) == epmod.EP_EINVAL      # source 1 of 1
+        assert rc_of(lambda: epmod.ep_ht_dispatch(r.h, x, idx[0], lay.dst_row[0], cfg.T + 1, 0, ring, recv,
+                                                  recv.shape[0])) == epmod.EP_EINVAL      # beyond max_tokens
+        # T = 0: nothing travels, the drains still do
+        epmod.ep_ht_dispatch(r.h, x, idx[0], lay.dst_row[0], 0, 0, ring, recv, recv.shape[0])
+        r.wait()
+        assert r.stats()["drains"] == 8 and r.stats()["writes"] == 0
+
+
 def _cpu_barrier_peer(name, delay, q):
     import time as _t
     import paper_2512_19849_amd as ep_
