@@ -205,6 +205,24 @@ def run_suite(args) -> int:
                     hh["combine_final_us"] = timed(lambda: rg.combine(partial, ones, Lg.dst_row[0], o))
                     res[f"ht_ranks_per_group{G}"] = hh
                     del recv_g, partial
+            # sender-side policies of the proxy on the per-token stream: best-effort packing, pacing
+            for label, kw in (("pack8", dict(pack_rows=8)), ("pack8_hold50us", dict(pack_rows=8, pack_hold_us=50)),
+                              ("pace32_window256", dict(max_outstanding=32, reorder_window=256))):
+                with EPRunner(R, E, K, H, T, num_proxy_threads=4, spin_timeout_ms=10000, **kw) as rp:
+                    Lp = rp.layout(d_idx)
+                    e2e = []
+                    for _ in range(13):
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        rp.dispatch(d_x, d_idx[0], Lp, recv, cmd_mode=ep.EP_CMD_PER_TOKEN)
+                        rp.wait()
+                        e2e.append((time.perf_counter() - t0) * 1e6)
+                    e2e = sorted(e2e[3:])
+                    st = rp.stats()
+                    res[f"per_token_{label}"] = {
+                        "launch_to_last_counter_us": round(e2e[len(e2e) // 2], 1), "writes_per_dispatch": st["writes"] // 13,
+                        "messages_per_dispatch": st["write_msgs"] // 13, "paced_per_dispatch": st["paced"] // 13,
+                        "max_in_flight": st["max_in_flight"]}
             # ring-buffer channels: sender -> ring slot -> receiver -> packed buffer, head/tail through the proxy
             for slices, W in ((128, 2), (128, 4), (256, 2)):
                 with EPRunner(R, E, K, H, T, num_proxy_threads=4, spin_timeout_ms=10000, ht_slices=slices,

@@ -105,6 +105,12 @@ typedef struct ep_config {
   int32_t flags;             /* ep_flags                                               */
   int32_t barrier_peers;     /* processes that take part in Barrier commands (0 or 1: only this one)   */
   char barrier_name[48];     /* name of the shared-memory barrier the peers of one node agree on; "" = private */
+  int32_t max_outstanding;   /* pacing: messages a proxy thread may have in flight to one destination rank;
+                                further ones wait at the sender (0 = unlimited)                              */
+  int32_t pack_rows;         /* best-effort packing of per-token Writes: up to this many rows with consecutive
+                                destination offsets, polled in one sweep, leave as one message (0, 1 = off; <= 16) */
+  int32_t pack_hold_us;      /* ... and an open message may wait this long for more rows (0 = never beyond the
+                                sweep that polled its first row; <= 1000)                                    */
   int32_t ht_slices;         /* ring-buffer channels: token slices per source (0 = ep_ht_dispatch unavailable), <= 4096 */
   int32_t ht_ring_slots;     /* ... chunk slots per channel ring (W); num_ranks * W <= 4096                           */
 } ep_config;
@@ -118,6 +124,9 @@ typedef struct ep_stats_t {
   uint64_t atomics_deferred; /* atomics that had to wait in the control buffer         */
   uint64_t ordered_parked;   /* sequenced messages that arrived ahead of their turn    */
   uint64_t rejected;         /* commands that failed offset translation / bounds check */
+  uint64_t write_msgs;       /* messages that carried the Writes (fewer than writes when rows were packed) */
+  uint64_t paced;            /* messages that waited at the sender for the pacing limit  */
+  uint64_t max_in_flight;    /* most messages any thread had in flight to one rank       */
   uint64_t copy_batches;     /* batched copy launches made by the proxy (registered heaps) */
   uint64_t copied_bytes;     /* bytes the proxy moved                                   */
   uint64_t gpu_ring_full;    /* times a GPU push saw "full" in its cached head and re-read the head over PCIe */

@@ -510,6 +510,9 @@ def check_order_trace(events: np.ndarray, first_seq: Optional[Dict[Tuple[int, in
 #                            kind 3: Atomic applied   (value = X)
 #   [1] source rank   [2] global expert   [3] value
 EV_WRITE, EV_ATOMIC_IN, EV_ATOMIC_APPLIED = 1, 2, 3
+# Sender half: kind 14 = a message handed to the transport; [1] source, [2] destination rank,
+# [3] messages this thread then had in flight to that rank.
+EV_SENT = 14
 
 
 def check_fence_trace(events: np.ndarray, count: np.ndarray) -> Dict[str, int]:
@@ -526,6 +529,8 @@ def check_fence_trace(events: np.ndarray, count: np.ndarray) -> Dict[str, int]:
     waited = 0
     for kind_thr, src, e, val in ev.tolist():
         kind, thr = kind_thr & 0xFF, kind_thr >> 8
+        if EV_ORD_WRITE_IN <= kind <= EV_SENT:
+            continue                                   # records of the other protocols and of the sender half
         key = (src, e)
         assert owner.setdefault(key, thr) == thr, f"(src,expert) {key} handled by two threads"
         if kind == EV_WRITE:
@@ -718,3 +723,36 @@ def check_ring_trace(events: np.ndarray, W: int, first_seq: Optional[Dict[Tuple[
         assert rev_next[key] == len(got), f"{key}: head updates delivered but never applied"
     return dict(applied=applied, waited=waited,
                 chunks={k: v // 2 for k, v in fwd_next.items()}, released=dict(rev_next))
+
+
+def check_pacing_trace(events: np.ndarray, limit: int, E_loc: int) -> Dict[str, int]:
+    """Pacing at the sender (Section 6, congestion control by the proxy): per proxy thread and
+    destination rank, the messages handed to the transport and not yet arrived never exceed
+    `limit`; every message sent arrives.  Recomputed from the send and arrival records alone (the
+    in-flight figure the proxy logs with each send must agree).  Returns the peak seen."""
+    ev = np.asarray(events, np.uint32).reshape(-1, 4)
+    flying: Dict[Tuple[int, int], int] = {}
+    peak = sent = 0
+    for kind_thr, src, where, val in ev.tolist():
+        kind, thr = kind_thr & 0xFF, kind_thr >> 8
+        if kind == EV_SENT:
+            key = (thr, where)
+            flying[key] = flying.get(key, 0) + 1
+            assert flying[key] == val, f"thread {thr} rank {where}: proxy counted {val} in flight, the log shows {flying[key]}"
+            assert limit <= 0 or flying[key] <= limit, f"thread {thr} has {flying[key]} messages in flight to rank {where}"
+            peak = max(peak, flying[key])
+            sent += 1
+        elif kind in (EV_WRITE, EV_ATOMIC_IN):
+            key = (thr, where // E_loc)                # [2] is the global expert
+        elif kind in (EV_ORD_WRITE_IN, EV_ORD_ATOMIC_IN):
+            key = (thr, where)                         # [2] is the destination rank
+        elif kind in (EV_RING_WRITE_IN, EV_RING_TAIL_IN, EV_RING_HEAD_IN):
+            key = (thr, where & 0xFF)                  # [2] is slice << 8 | destination rank
+        else:
+            continue
+        if kind != EV_SENT:
+            assert flying.get(key, 0) > 0, f"arrival at rank {key[1]} (thread {thr}) of a message never sent"
+            flying[key] -= 1
+    left = {k: v for k, v in flying.items() if v}
+    assert not left, f"messages sent but never arrived: {left}"
+    return dict(peak=peak, sent=sent)

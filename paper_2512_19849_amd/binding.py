@@ -46,12 +46,14 @@ class ep_config(C.Structure):
                 ("num_channels", C.c_int32), ("ring_entries", C.c_int32), ("num_proxy_threads", C.c_int32),
                 ("reorder_window", C.c_int32), ("spin_timeout_ms", C.c_int32), ("reorder_seed", C.c_uint64),
                 ("heap_rows", C.c_int64), ("flags", C.c_int32), ("barrier_peers", C.c_int32),
-                ("barrier_name", C.c_char * 48), ("ht_slices", C.c_int32), ("ht_ring_slots", C.c_int32)]
+                ("barrier_name", C.c_char * 48), ("max_outstanding", C.c_int32), ("pack_rows", C.c_int32), ("pack_hold_us", C.c_int32),
+                ("ht_slices", C.c_int32), ("ht_ring_slots", C.c_int32)]
 
 
 class ep_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("cmds", "writes", "atomics", "drains", "barriers", "write_bytes", "write_rows",
                                           "atomics_applied", "atomics_deferred", "ordered_parked", "rejected",
+                                          "write_msgs", "paced", "max_in_flight",
                                           "copy_batches", "copied_bytes", "gpu_ring_full",
                                           "first_poll_ns", "last_apply_ns")] + \
                [("per_thread_cmds", C.c_uint64 * 16), ("device_error", C.c_int32), ("proxy_error", C.c_int32)]
@@ -151,11 +153,13 @@ def ep_proxy_start(num_ranks: int, num_experts: int, top_k: int, hidden: int, ma
                    self_rank: int = 0, num_channels: int = 8, ring_entries: int = 4096, num_proxy_threads: int = 4,
                    reorder_window: int = 0, reorder_seed: int = 0, spin_timeout_ms: int = 0, heap_rows: int = 0,
                    flags: int = 0, barrier_peers: int = 0, barrier_name: str = "", ht_slices: int = 0,
-                   ht_ring_slots: int = 0) -> int:
+                   ht_ring_slots: int = 0, max_outstanding: int = 0, pack_rows: int = 0,
+                   pack_hold_us: int = 0) -> int:
     """Returns the opaque handle (an integer address)."""
     cfg = ep_config(num_ranks, num_experts, top_k, hidden, max_tokens, num_src, self_rank, num_channels,
                     ring_entries, num_proxy_threads, reorder_window, spin_timeout_ms, reorder_seed, heap_rows,
-                    flags, barrier_peers, barrier_name.encode(), ht_slices, ht_ring_slots)
+                    flags, barrier_peers, barrier_name.encode(), max_outstanding, pack_rows, pack_hold_us, ht_slices,
+                    ht_ring_slots)
     h = C.c_void_p()
     _check("ep_proxy_start", load_library().ep_proxy_start(C.byref(cfg), C.byref(h)))
     return h.value

@@ -67,6 +67,21 @@ struct WireEvent {
   uint16_t slice;     // ring-buffer channels: the token slice (part of the connection's identity)
 };
 
+// A message on its way out of the sender half: the notice the receiver will get, and (registered
+// heaps) the copies that have to complete first.  Packed per-token Writes are one message with
+// several source segments of one row each and one contiguous destination.
+constexpr int kMaxPackRows = 16;
+struct Outbound {
+  WireEvent notice;
+  uint32_t nseg = 0;          // 0: nothing to copy (the kernel placed the rows, or an Atomic)
+  uint64_t seglen = 0, dof = 0;
+  uint64_t so[kMaxPackRows];
+  const char *sbase = nullptr;
+  char *dbase = nullptr;
+  uint32_t le = 0;            // packing: the open message's expert
+  uint64_t opened_ns = 0;     // packing: when its first row was polled
+};
+
 struct alignas(64) ProxyThread {
   int tid = 0;
   std::thread th;
@@ -92,6 +107,14 @@ struct alignas(64) ProxyThread {
   // ordered (high-throughput) channels: next sequence number and early arrivals per (source, destination rank)
   std::vector<uint32_t> next_seq;
   std::vector<std::map<uint32_t, WireEvent>> early;
+  // pacing: messages in flight per destination rank, and those waiting at the sender for room
+  std::vector<int32_t> in_flight;
+  std::vector<std::deque<Outbound>> held;
+  size_t held_total = 0;
+  // best-effort packing: the open (still growing) message per (source, global expert), -1 = none
+  std::vector<int32_t> open_idx;
+  std::vector<Outbound> open;
+  std::vector<uint32_t> open_key;
   // ring-buffer channels: the same per (source, slice, destination rank, direction)
   std::vector<uint32_t> ring_next;
   std::vector<std::map<uint32_t, WireEvent>> ring_early;
@@ -99,7 +122,7 @@ struct alignas(64) ProxyThread {
   // statistics (written by the owner thread only, read racy-but-atomically)
   std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
       applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0}, barriers{0},
-      copy_batches{0}, copied_bytes{0};
+      copy_batches{0}, copied_bytes{0}, write_msgs{0}, paced{0}, max_in_flight{0};
   std::mutex log_mu;
   std::vector<uint32_t> cmd_log, event_log;
 };
@@ -194,6 +217,7 @@ void deliver_ordered(ep_handle *h, ProxyThread &P, const WireEvent &ev);
 void deliver_ring(ep_handle *h, ProxyThread &P, const WireEvent &ev);
 
 void deliver(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  --P.in_flight[ev.dst_rank];  // the message has arrived: room for the next one to this rank
   if (ev.ordered >= 2) {
     deliver_ring(h, P, ev);
     return;
@@ -386,17 +410,96 @@ void reap_batches(ep_handle *h, ProxyThread &P, ReapMode mode) {
 
 // Offsets and length are bytes relative to the registered heaps, multiples of 16 below 64 GiB.
 void queue_copy(ep_handle *h, ProxyThread &P, const char *sbase, char *dbase, uint64_t so, uint64_t dof,
-                uint64_t len, const WireEvent &notice) {
+                uint64_t len, const WireEvent *notice) {
   if (P.cur.n && (P.cur.src_base != sbase || P.cur.dst_base != dbase)) launch_batch(h, P);  // re-registered
   // the event about to be used must not belong to a batch still in flight
   while (P.cur.n == 0 && (int)P.inflight.size() >= ProxyThread::kBatchSlots - 1) reap_batches(h, P, kReapOne);
   P.cur.src_base = sbase;
   P.cur.dst_base = dbase;
   P.cur.d[P.cur.n] = CopyBatchArgs::Desc{(unsigned)(so >> 4), (unsigned)(dof >> 4), (unsigned)(len >> 4)};
-  P.cur_notices.push_back(notice);
+  if (notice) P.cur_notices.push_back(*notice);
   if ((unsigned)(len >> 4) > P.cur.max_len16) P.cur.max_len16 = (unsigned)(len >> 4);
   bump(P.copied_bytes, len);
   if (++P.cur.n == kCopyBatchMax) launch_batch(h, P);
+}
+
+// ---- pacing (Section 6, "Congestion control with CPU proxy") ------------------------------------
+// The proxy tracks the requests it has outstanding per destination and keeps further ones at the
+// sender until earlier ones have arrived, so that a burst cannot pile up at one receiver.
+void launch_msg(ep_handle *h, ProxyThread &P, const Outbound &m) {
+  const uint32_t dr = m.notice.dst_rank;
+  const int32_t now = ++P.in_flight[dr];
+  if ((uint64_t)now > P.max_in_flight.load(std::memory_order_relaxed)) P.max_in_flight.store((uint64_t)now);
+  log_event(h, P, 14, m.notice.src, dr, (uint32_t)now);
+  if (m.nseg == 0) {
+    transmit(h, P, m.notice);
+    return;
+  }
+  // the notice rides on the last segment's copy: a batch completes as a whole, in order
+  for (uint32_t i = 0; i < m.nseg; ++i)
+    queue_copy(h, P, m.sbase, m.dbase, m.so[i], m.dof + i * m.seglen, m.seglen, i + 1 == m.nseg ? &m.notice : nullptr);
+}
+
+void send_msg(ep_handle *h, ProxyThread &P, const Outbound &m) {
+  const int limit = h->cfg.max_outstanding;
+  const uint32_t dr = m.notice.dst_rank;
+  if (limit > 0 && (P.in_flight[dr] >= limit || !P.held[dr].empty())) {
+    P.held[dr].push_back(m);  // keeps the order of messages to one destination
+    ++P.held_total;
+    bump(P.paced, 1);
+    return;
+  }
+  launch_msg(h, P, m);
+}
+
+// Lets waiting messages go wherever arrivals have made room.
+void pump_held(ep_handle *h, ProxyThread &P) {
+  if (!P.held_total) return;
+  const int limit = h->cfg.max_outstanding;
+  for (size_t dr = 0; dr < P.held.size(); ++dr) {
+    std::deque<Outbound> &q = P.held[dr];
+    while (!q.empty() && P.in_flight[dr] < limit) {
+      const Outbound m = q.front();
+      q.pop_front();
+      --P.held_total;
+      launch_msg(h, P, m);
+    }
+  }
+}
+
+// ---- best-effort packing of per-token Writes (Section 6, "More efficient low-latency kernel") ---
+void close_open(ep_handle *h, ProxyThread &P, size_t slot) {
+  Outbound m = P.open[slot];
+  const uint32_t key = P.open_key[slot];
+  P.open_idx[key] = -1;
+  if (slot + 1 != P.open.size()) {
+    P.open[slot] = P.open.back();
+    P.open_key[slot] = P.open_key.back();
+    P.open_idx[P.open_key[slot]] = (int32_t)slot;
+  }
+  P.open.pop_back();
+  P.open_key.pop_back();
+  const uint32_t rows = m.nseg;
+  m.notice.imm = (m.le << 19) | ((rows - 1) << 13) | (uint32_t)((m.dof >> 4) & 0x1FFFu);
+  if (!m.dbase) m.nseg = 0;  // rows already placed by the kernel: only the notice travels
+  bump(P.write_msgs, 1);
+  send_msg(h, P, m);
+}
+
+void close_all_open(ep_handle *h, ProxyThread &P) {
+  while (!P.open.empty()) close_open(h, P, P.open.size() - 1);
+}
+
+// End of a poll sweep: open messages leave, unless they may still wait for more rows.
+void close_due_open(ep_handle *h, ProxyThread &P) {
+  const uint64_t hold = (uint64_t)h->cfg.pack_hold_us * 1000ull;
+  if (!hold) {
+    close_all_open(h, P);
+    return;
+  }
+  const uint64_t now = now_ns();
+  for (size_t i = P.open.size(); i-- > 0;)
+    if (now - P.open[i].opened_ns >= hold) close_open(h, P, i);
 }
 
 void reject(ep_handle *h, ProxyThread &P) {
@@ -435,16 +538,41 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       bump(P.writes, 1);
       bump(P.write_bytes, len);
       bump(P.write_rows, rows);
-      const WireEvent notice{(le << 19) | ((rows - 1) << 13) | (uint32_t)((dof >> 4) & 0x1FFFu), (uint16_t)src,
-                             (uint8_t)dr, 0};
-      if (dbase) {
-        // registered heaps: this thread performs the write; the notice follows its completion
-        queue_copy(h, P, sbase, dbase, so, dof, len, notice);
-      } else {
-        // The payload already sits in the destination partition (the kernel stored it);
-        // what remains of the peer write is its arrival notice.
-        transmit(h, P, notice);
+      // Without registered heaps the payload already sits in the destination partition (the kernel
+      // stored it) and what remains of the peer write is its arrival notice; with them this thread
+      // performs the write and the notice follows its completion.
+      Outbound m;
+      m.notice = WireEvent{(le << 19) | ((rows - 1) << 13) | (uint32_t)((dof >> 4) & 0x1FFFu), (uint16_t)src,
+                           (uint8_t)dr, 0};
+      m.nseg = dbase ? 1 : 0;
+      m.seglen = len;
+      m.dof = dof;
+      m.so[0] = so;
+      m.sbase = sbase;
+      m.dbase = dbase;
+      m.le = le;
+      if (c.pack_rows > 1 && rows == 1) {
+        // one-row Write: extend the open message of its expert if it continues it, else open one
+        const uint32_t key = src * (uint32_t)c.num_experts + dr * (uint32_t)h->E_loc + le;
+        int32_t slot = P.open_idx[key];
+        if (slot >= 0) {
+          Outbound &o = P.open[slot];
+          if (o.dof + (uint64_t)o.nseg * o.seglen == dof && o.seglen == len && o.sbase == sbase && o.dbase == dbase) {
+            o.so[o.nseg++] = so;
+            if ((int)o.nseg == c.pack_rows) close_open(h, P, (size_t)slot);
+            break;
+          }
+          close_open(h, P, (size_t)slot);
+        }
+        m.nseg = 1;  // counts the rows while the message is open
+        if (c.pack_hold_us) m.opened_ns = now_ns();
+        P.open_idx[key] = (int32_t)P.open.size();
+        P.open.push_back(m);
+        P.open_key.push_back(key);
+        break;
       }
+      bump(P.write_msgs, 1);
+      send_msg(h, P, m);
       break;
     }
     case EP_OP_ATOMIC: {
@@ -455,7 +583,13 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
         return;
       }
       bump(P.atomics, 1);
-      transmit(h, P, WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint8_t)dr, 0});
+      if (c.pack_rows > 1) {  // rows of this expert still being packed leave before their count does
+        const int32_t slot = P.open_idx[src * (uint32_t)c.num_experts + dr * (uint32_t)h->E_loc + le];
+        if (slot >= 0) close_open(h, P, (size_t)slot);
+      }
+      Outbound m;
+      m.notice = WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint8_t)dr, 0};
+      send_msg(h, P, m);
       break;
     }
     case EP_OP_ORDERED_WRITE: {
@@ -473,11 +607,15 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       bump(P.writes, 1);
       bump(P.write_bytes, len);
       bump(P.write_rows, rows);
-      const WireEvent notice{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 1};
-      if (dbase)
-        queue_copy(h, P, sbase, dbase, dof, dof, len, notice);  // packed chunk: same offset on both sides
-      else
-        transmit(h, P, notice);
+      Outbound m;
+      m.notice = WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 1};
+      m.nseg = dbase ? 1 : 0;  // packed chunk: same offset on both sides
+      m.seglen = len;
+      m.dof = m.so[0] = dof;
+      m.sbase = sbase;
+      m.dbase = dbase;
+      bump(P.write_msgs, 1);
+      send_msg(h, P, m);
       break;
     }
     case EP_OP_ORDERED_ATOMIC: {
@@ -487,7 +625,9 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
         return;
       }
       bump(P.atomics, 1);
-      transmit(h, P, WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | w1, (uint16_t)src, (uint8_t)dr, 1});
+      Outbound m;
+      m.notice = WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | w1, (uint16_t)src, (uint8_t)dr, 1};
+      send_msg(h, P, m);
       break;
     }
     case EP_OP_RING: {
@@ -511,7 +651,10 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
         bump(P.writes, 1);
         bump(P.write_bytes, len);
         bump(P.write_rows, rows);
-        transmit(h, P, WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 2, (uint16_t)slice});
+        Outbound m;
+        m.notice = WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 2, (uint16_t)slice};
+        bump(P.write_msgs, 1);
+        send_msg(h, P, m);
       } else {
         const uint32_t value = w1 & 0x3FFFFFFFu;
         if (value > 0x7FFFu) {
@@ -519,16 +662,23 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
           return;
         }
         bump(P.atomics, 1);
-        transmit(h, P, WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | value, (uint16_t)src, (uint8_t)dr,
-                                 (uint8_t)(kind == EP_RING_TAIL ? 2 : 3), (uint16_t)slice});
+        Outbound m;
+        m.notice = WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | value, (uint16_t)src, (uint8_t)dr,
+                             (uint8_t)(kind == EP_RING_TAIL ? 2 : 3), (uint16_t)slice};
+        send_msg(h, P, m);
       }
       break;
     }
     case EP_OP_DRAIN: {
-      // everything this thread handed to the transport must have completed
-      launch_batch(h, P);
-      reap_batches(h, P, kReapAll);
-      flush_window(h, P);
+      // everything this thread has taken over must have left and arrived: open packed messages,
+      // copies in flight, messages in the transport, and those waiting for the pacing limit
+      close_all_open(h, P);
+      do {
+        launch_batch(h, P);
+        reap_batches(h, P, kReapAll);
+        flush_window(h, P);
+        pump_held(h, P);
+      } while (P.held_total || P.cur.n || !P.inflight.empty() || !P.window.empty());
       // communication channels that travel through this FIFO (destination rank mod C == fifo) must
       // have nothing left waiting: a leftover means a sequence number never arrived
       for (int ss = 0; ss < c.num_src; ++ss)
@@ -613,6 +763,11 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
         any = true;
       }
     }
+    // best-effort packing never keeps a Write beyond the sweep that polled it
+    if (!P.open.empty()) {
+      close_due_open(h, P);
+      if (!P.open.empty()) any = true;  // keep sweeping: the open messages have a deadline
+    }
     // what this sweep collected goes out as one batch of peer writes; finished batches release
     // their arrival notices
     if (P.cur.n) launch_batch(h, P);
@@ -620,11 +775,17 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
       reap_batches(h, P, kReapReady);
       any = true;
     }
+    if (P.held_total) {
+      // messages wait for room: let what is in the transport arrive, then send what fits
+      flush_window(h, P);
+      pump_held(h, P);
+    }
     if (any) {
       idle = 0;
       continue;
     }
     if (!P.window.empty()) flush_window(h, P);  // nothing new: let in-flight immediates land
+    if (P.held_total) continue;
     if (++idle < 4096) {
       _mm_pause();
     } else if (idle == 4096) {
@@ -660,6 +821,9 @@ int validate(const ep_config &c) {
   for (const char *p = c.barrier_name; *p; ++p)
     if (*p == '/') return EP_EINVAL;
   if (c.barrier_peers > 1 && !c.barrier_name[0]) return EP_EINVAL;
+  if (c.max_outstanding < 0 || c.max_outstanding > (1 << 20) || c.pack_rows < 0 || c.pack_rows > kMaxPackRows ||
+      c.pack_hold_us < 0 || c.pack_hold_us > 1000)
+    return EP_EINVAL;
   if (c.ht_slices < 0 || c.ht_slices > 4096 || c.ht_ring_slots < 0 || c.ht_ring_slots > 64) return EP_EINVAL;
   if ((c.ht_slices > 0) != (c.ht_ring_slots > 0)) return EP_EINVAL;
   if (c.ht_slices > 0 && ((int64_t)c.num_ranks * c.ht_ring_slots > 4096 || c.num_proxy_threads < 1)) return EP_EINVAL;
@@ -844,6 +1008,9 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     P.parked.resize((size_t)S * E);
     P.next_seq.assign((size_t)S * cfg->num_ranks, 0);
     P.early.resize((size_t)S * cfg->num_ranks);
+    P.in_flight.assign((size_t)cfg->num_ranks, 0);
+    P.held.resize((size_t)cfg->num_ranks);
+    if (cfg->pack_rows > 1) P.open_idx.assign((size_t)S * E, -1);
     P.ring_next.assign(nring * 2, 0);
     P.ring_early.resize(nring * 2);
     P.rng = cfg->reorder_seed * 0x9E3779B97F4A7C15ull + (uint64_t)i;
@@ -1246,6 +1413,9 @@ int ep_stats(ep_handle *h, ep_stats_t *out) {
     out->atomics_deferred += P.deferred.load();
     out->ordered_parked += P.ordered_parked.load();
     out->rejected += P.rejected.load();
+    out->write_msgs += P.write_msgs.load();
+    out->paced += P.paced.load();
+    if (P.max_in_flight.load() > out->max_in_flight) out->max_in_flight = P.max_in_flight.load();
     out->copy_batches += P.copy_batches.load();
     out->copied_bytes += P.copied_bytes.load();
     const uint64_t f = P.first_poll_ns.load(), l = P.last_apply_ns.load();
@@ -1273,7 +1443,7 @@ int ep_reset_stats(ep_handle *h) {
     ProxyThread &P = h->threads[i];
     for (auto *a : {&P.cmds, &P.writes, &P.atomics, &P.drains, &P.write_bytes, &P.write_rows, &P.applied,
                     &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns, &P.ordered_parked, &P.barriers,
-                    &P.copy_batches, &P.copied_bytes})
+                    &P.copy_batches, &P.copied_bytes, &P.write_msgs, &P.paced, &P.max_in_flight})
       a->store(0);
     std::lock_guard<std::mutex> g(P.log_mu);
     P.cmd_log.clear();

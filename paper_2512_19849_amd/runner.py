@@ -43,7 +43,8 @@ class EPRunner:
                  num_channels: int = 8, ring_entries: int = 4096, num_proxy_threads: int = 4,
                  reorder_window: int = 0, reorder_seed: int = 0, spin_timeout_ms: int = 0, heap_rows: int = 0,
                  flags: int = 0, device: str = "cuda", barrier_peers: int = 0, barrier_name: str = "",
-                 ht_slices: int = 0, ht_ring_slots: int = 0):
+                 ht_slices: int = 0, ht_ring_slots: int = 0, max_outstanding: int = 0, pack_rows: int = 0,
+                 pack_hold_us: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("EPRunner needs a HIP device; there is no CPU path")
         self.R, self.E, self.K, self.H, self.S, self.T_cap = R, E, K, H, S, max_tokens
@@ -52,7 +53,8 @@ class EPRunner:
         self.heap_rows = heap_rows or S * max_tokens * K
         self.h = ep.ep_proxy_start(R, E, K, H, max_tokens, S, self_rank, num_channels, ring_entries,
                                    num_proxy_threads, reorder_window, reorder_seed, spin_timeout_ms, heap_rows,
-                                   flags, barrier_peers, barrier_name, ht_slices, ht_ring_slots)
+                                   flags, barrier_peers, barrier_name, ht_slices, ht_ring_slots, max_outstanding,
+                                   pack_rows, pack_hold_us)
         self.ht_slices, self.ht_ring_slots = ht_slices, ht_ring_slots
         i32 = dict(dtype=torch.int32, device=self.dev)
         self.lay = LayoutOut(

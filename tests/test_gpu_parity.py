@@ -242,6 +242,28 @@ def test_proxy_writes_follow_new_data_and_atomics_wait_for_them(epmod, oracle):
         assert r.stats()["copied_bytes"] == st["copied_bytes"]
 
 
+@pytest.mark.parametrize("cid,T,window,limit,pack,proxy_writes", [
+    (4, 600, 32, 6, 0, False), (5, 500, 0, 2, 8, True), (1, None, 4, 1, 16, False), (4, 300, 16, 5, 4, True)])
+def test_pacing_and_packing_on_a_real_dispatch(epmod, oracle, cid, T, window, limit, pack, proxy_writes):
+    """Per-token dispatch with the proxy's sender-side policies on: at most `limit` messages in flight per
+    destination rank and thread, one-row Writes packed best-effort; the receive buffer, the counters and
+    the fence trace are what they are without the policies."""
+    cfg = g.config(cid, S=1)
+    out = _dispatch_case(epmod, oracle, cfg, T, 0.05, epmod.EP_CMD_PER_TOKEN, proxy_writes=proxy_writes,
+                         reorder_window=window, reorder_seed=13, max_outstanding=limit, pack_rows=pack)
+    _check_commands(epmod, oracle, cfg, out, "per_token")
+    st = out["stats"]
+    assert 1 <= st["max_in_flight"] <= limit
+    res = oracle.check_pacing_trace(out["events"], limit, cfg.E_loc)
+    assert res["peak"] == st["max_in_flight"] and res["sent"] == st["write_msgs"] + st["atomics"]
+    if pack > 1:
+        assert st["write_msgs"] <= st["writes"]
+        wr = out["events"][(out["events"][:, 0] & 0xFF) == oracle.EV_WRITE]
+        assert len(wr) == st["write_msgs"] and wr[:, 3].sum() == st["write_rows"] and wr[:, 3].max() <= pack
+    else:
+        assert st["write_msgs"] == st["writes"]
+
+
 def test_registered_heaps_argument_errors(epmod):
     cfg = g.config(1)
     with _runner(epmod, cfg) as r:

@@ -224,6 +224,7 @@ def test_drain_completes_everything_in_flight(ep, oracle):
         st = ep.ep_stats(h)
         assert st["drains"] == 1 and st["atomics_applied"] == 1
         ev = ep.ep_event_log(h)
+        ev = ev[(ev[:, 0] & 0xFF) != oracle.EV_SENT]                   # receiver-half records only
         assert len(ev) == 5 + 1 + 1
         count = np.zeros((1, 16), np.int32)
         count[0, 2 * E_loc + 1] = 5
@@ -480,3 +481,158 @@ def test_barrier_alone_and_timeout(ep):
         _start(ep, barrier_peers=2, barrier_name="")                       # peers need a name
     with pytest.raises(ep.EPError):
         _start(ep, barrier_peers=2, barrier_name="a/b")
+
+
+# ------------------------------------------------ pacing and packing (Section 6)
+class _Burst:
+    """Lets a test queue a whole burst before the proxy sees any of it: the proxy thread is parked in
+    a two-party Barrier (first command of the FIFO) that a second handle completes on release()."""
+
+    def __init__(self, ep, name, **kw):
+        self.ep = ep
+        kw.update(num_proxy_threads=1, num_channels=1, num_src=1, ring_entries=2048, barrier_peers=2,
+                  barrier_name=name, spin_timeout_ms=10000)
+        self.h = _start(ep, **kw)
+        self.peer = _start(ep, num_proxy_threads=1, num_channels=1, num_src=1, barrier_peers=2, barrier_name=name,
+                           spin_timeout_ms=10000)
+        ep.ep_host_push(self.h, 0, _w0(4, 0, 0, 0), 0, 0, 0)
+
+    def release(self):
+        self.ep.ep_host_push(self.peer, 0, _w0(4, 0, 0, 0), 0, 0, 0)
+
+    def close(self):
+        self.ep.ep_proxy_stop(self.h)
+        self.ep.ep_proxy_stop(self.peer)
+
+
+@pytest.mark.parametrize("limit,window", [(1, 0), (4, 64), (16, 1000), (3, 7)])
+def test_pacing_bounds_the_messages_in_flight_per_destination(ep, oracle, limit, window):
+    """With max_outstanding set, a proxy thread never has more than that many messages on their way to
+    one destination rank; the rest wait at the sender, in order, and everything still arrives and
+    passes the completion fence."""
+    E_loc, rb = 4, 2048
+    b = _Burst(ep, f"pace{limit}_{window}_{os.getpid()}", reorder_window=window, reorder_seed=3, max_outstanding=limit)
+    h = b.h
+    try:
+        rng = np.random.default_rng(limit)
+        count = np.zeros((1, 16), np.int64)
+        ep.ep_host_expect_atomics(h, 16)
+        for row in range(600):                                  # a burst, most of it to rank 2 (an incast)
+            e = int(rng.choice([8, 9, 10, 11])) if rng.random() < 0.7 else int(rng.integers(16))
+            _write(ep, h, 0, 0, e // E_loc, e % E_loc, 1, rb, row)
+            count[0, e] += 1
+        for e in range(16):
+            _atomic(ep, h, 0, 0, e // E_loc, e % E_loc, int(count[0, e]), E_loc)
+        b.release()
+        ep.ep_wait(h)
+        _drain_all(ep, h, 1)
+        st = ep.ep_stats(h)
+        assert st["rejected"] == 0 and st["proxy_error"] == 0 and st["atomics_applied"] == 16
+        assert st["max_in_flight"] == limit if window else st["max_in_flight"] == 1
+        assert (st["paced"] > 0) == (window > 0)
+        ev = ep.ep_event_log(h)
+        res = oracle.check_pacing_trace(ev, limit, E_loc)
+        assert res["sent"] == 600 + 16 and res["peak"] == st["max_in_flight"]
+        oracle.check_fence_trace(ev, count)
+        assert np.array_equal(ep.ep_counters(h, 1, 16), count)
+    finally:
+        b.close()
+
+
+def test_without_pacing_the_transport_fills_with_one_destination(ep, oracle):
+    """The same kind of burst without a limit: as many messages in flight to the hot rank as the
+    transport holds (what the limit is there to prevent); the checker rejects that trace for any
+    smaller limit, and notices a send record that is missing."""
+    b = _Burst(ep, f"nopace_{os.getpid()}", reorder_window=64)
+    h = b.h
+    try:
+        ep.ep_host_expect_atomics(h, 1)
+        for i in range(300):
+            _write(ep, h, 0, 0, 2, 1, 1, 2048, i)
+        _atomic(ep, h, 0, 0, 2, 1, 300, 4)
+        b.release()
+        ep.ep_wait(h)
+        _drain_all(ep, h, 1)
+        st = ep.ep_stats(h)
+        assert st["max_in_flight"] == 65 and st["paced"] == 0
+        ev = ep.ep_event_log(h)
+        assert oracle.check_pacing_trace(ev, 0, 4)["peak"] == 65
+        with pytest.raises(AssertionError, match="in flight to rank 2"):
+            oracle.check_pacing_trace(ev, 64, 4)
+        sent = np.nonzero((ev[:, 0] & 0xFF) == oracle.EV_SENT)[0]
+        with pytest.raises(AssertionError, match="never sent|proxy counted"):
+            oracle.check_pacing_trace(np.delete(ev, sent[0], axis=0), 0, 4)
+    finally:
+        b.close()
+
+
+@pytest.mark.parametrize("pack,window", [(4, 0), (16, 9), (2, 0)])
+def test_best_effort_packing_of_one_row_writes(ep, oracle, pack, window):
+    """One-row Writes to consecutive destination offsets of one expert, polled in the same sweep, leave
+    as one message of up to pack_rows rows; a gap or the expert's count Atomic closes a message, another
+    expert's rows in between do not.  Rows, bytes and the fence are unaffected; the message count drops."""
+    E_loc, rb = 4, 2048
+    b = _Burst(ep, f"pack{pack}_{window}_{os.getpid()}", reorder_window=window, pack_rows=pack)
+    h = b.h
+    try:
+        ep.ep_host_expect_atomics(h, 3)
+        # expert 5: rows 0..19 contiguous; expert 6: rows 100,101 then a gap, 103; expert 7: a single row
+        for i in range(20):
+            _write(ep, h, 0, 0, 1, 1, 1, rb, i)
+            if i == 3:
+                _write(ep, h, 0, 0, 1, 2, 1, rb, 100)
+        _write(ep, h, 0, 0, 1, 2, 1, rb, 101)
+        _write(ep, h, 0, 0, 1, 2, 1, rb, 103)
+        _write(ep, h, 0, 0, 1, 3, 1, rb, 200)
+        _atomic(ep, h, 0, 0, 1, 1, 20, E_loc)
+        _atomic(ep, h, 0, 0, 1, 2, 3, E_loc)
+        _atomic(ep, h, 0, 0, 1, 3, 1, E_loc)
+        b.release()
+        ep.ep_wait(h)
+        _drain_all(ep, h, 1)
+        st = ep.ep_stats(h)
+        assert st["writes"] == 24 and st["write_rows"] == 24 and st["write_bytes"] == 24 * rb
+        assert st["atomics_applied"] == 3 and st["rejected"] == 0 and st["proxy_error"] == 0
+        assert st["write_msgs"] == -(-20 // pack) + 2 + 1       # the whole burst is polled in one sweep
+        ev = ep.ep_event_log(h)
+        count = np.zeros((1, 16), np.int64)
+        count[0, 5], count[0, 6], count[0, 7] = 20, 3, 1
+        oracle.check_fence_trace(ev, count)
+        wr = ev[(ev[:, 0] & 0xFF) == oracle.EV_WRITE]
+        assert sorted(wr[wr[:, 2] == 5][:, 3].tolist(), reverse=True) == [pack] * (20 // pack) + ([20 % pack] if 20 % pack else [])
+        assert sorted(wr[wr[:, 2] == 6][:, 3].tolist()) == [1, 2] and wr[wr[:, 2] == 7][:, 3].tolist() == [1]
+        oracle.check_pacing_trace(ev, 0, E_loc)
+    finally:
+        b.close()
+
+
+def test_packing_hold_time_spans_poll_sweeps_and_expires(ep, oracle):
+    """With pack_hold_us an open message may wait for rows that arrive in later sweeps; once its time is
+    up it leaves although nothing else arrives."""
+    h = _start(ep, num_proxy_threads=1, num_channels=1, num_src=1, pack_rows=8, pack_hold_us=1000)
+    try:
+        for burst in range(2):
+            for i in range(8):                                   # pushed one by one: the proxy sweeps in between
+                _write(ep, h, 0, 0, 1, 1, 1, 2048, 8 * burst + i)
+            time.sleep(0.005)
+        _write(ep, h, 0, 0, 1, 1, 1, 2048, 16)                   # a lone row, nothing follows it
+        deadline = time.time() + 5
+        while ep.ep_stats(h)["write_msgs"] < 3:
+            assert time.time() < deadline, "the open message never left"
+            time.sleep(0.001)
+        ev = ep.ep_event_log(h)
+        wr = ev[(ev[:, 0] & 0xFF) == oracle.EV_WRITE]
+        assert wr[:, 3].tolist() == [8, 8, 1]
+        ep.ep_host_expect_atomics(h, 1)
+        _atomic(ep, h, 0, 0, 1, 1, 17, 4)
+        ep.ep_wait(h)
+        assert ep.ep_counters(h, 1, 16)[0, 5] == 17
+    finally:
+        ep.ep_proxy_stop(h)
+
+
+def test_pacing_and_packing_configuration_is_validated(ep):
+    for kw in (dict(max_outstanding=-1), dict(pack_rows=17), dict(pack_rows=-1), dict(pack_hold_us=1001)):
+        with pytest.raises(ep.EPError) as ei:
+            ep.ep_proxy_stop(_start(ep, **kw))
+        assert ei.value.rc == ep.EP_EINVAL
