@@ -715,7 +715,9 @@ def test_ht_dedup_parity(epmod, oracle, cid, G, T, mask):
 
 @pytest.mark.parametrize("cid,G,T,mask,mode", [(1, 1, None, 0.0, "per_token"), (1, 2, None, 0.25, "chunk32"),
                                                (4, 1, 600, 0.0, "chunk32"), (4, 8, 600, 0.1, "chunk32"),
-                                               (5, 4, 500, 0.0, "per_token"), (4, 1, 4096, 0.0, "chunk32")])
+                                               (5, 4, 500, 0.0, "per_token"), (4, 1, 4096, 0.0, "chunk32"),
+                                               (4, 8, 600, 0.1, "ring"), (4, 1, 4096, 0.0, "ring"),
+                                               (1, 2, None, 0.25, "ring")])
 def test_ht_round_trip(epmod, oracle, cid, G, T, mask, mode):
     """dedup -> group-level layout and dispatch (second handle) -> per-expert index
     list -> expert outputs -> partial reduce per group -> final reduce."""
@@ -739,15 +741,20 @@ def test_ht_round_trip(epmod, oracle, cid, G, T, mask, mode):
     wout = oracle.combine(wpartial, np.ones_like(w[0]), lay_g["dst_row"][0])
 
     flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    ring_kw = dict(ht_slices=16, ht_ring_slots=2, reorder_window=8) if mode == "ring" else {}
     with EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, T, num_proxy_threads=0, spin_timeout_ms=3000) as r, \
-            EPRunner(NG, NG, cfg.K, cfg.H, T, spin_timeout_ms=3000, flags=flags) as rg:
+            EPRunner(NG, NG, cfg.K, cfg.H, T, spin_timeout_ms=3000, flags=flags, **ring_kw) as rg:
         d_idx, d_x, d_w = _dev(idx), bits_to_bf16(x), _dev(w[0])
         gi, fk = torch.empty_like(d_idx), torch.empty_like(d_idx)
         epmod.ep_dedup(r.h, d_idx, T, G, gi, fk)
         L = r.layout(d_idx)
         Lg = rg.layout(gi)
         recv_g = torch.full((rows_g + 1, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")
-        rg.dispatch(d_x, gi[0], Lg, recv_g, cmd_mode=epmod.CMD_MODES[mode])
+        if mode == "ring":      # the deduplicated rows travel through the ring-buffer channels
+            ring = torch.zeros(rg.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+            rg.ht_dispatch(d_x, gi[0], Lg, ring, recv_g)
+        else:
+            rg.dispatch(d_x, gi[0], Lg, recv_g, cmd_mode=epmod.CMD_MODES[mode])
         index = torch.full((rows,), -1, dtype=torch.int32, device="cuda")
         epmod.ep_gather_index(r.h, L.dst_row[0], Lg.dst_row[0], fk[0], T, rows, index)
         partial = torch.ones((rows_g, cfg.H), dtype=torch.bfloat16, device="cuda")
@@ -766,9 +773,14 @@ def test_ht_round_trip(epmod, oracle, cid, G, T, mask, mode):
         assert np.array_equal(bf16_to_bits(partial), wpartial)
         assert np.array_equal(bf16_to_bits(out), wout)
         # the wire: commands of the group-level dispatch, fewer rows than one per (token, expert)
-        want_cmds = oracle.expected_cmds(wg[0], lay_g, 0, 1, cfg.H, "bf16", mode)
-        assert oracle.cmd_multiset(epmod.ep_cmd_log(rg.h)) == want_cmds
-        oracle.check_fence_trace(epmod.ep_event_log(rg.h), lay_g["count"])
+        if mode == "ring":
+            assert oracle.ring_cmd_multiset(epmod.ep_cmd_log(rg.h)) == \
+                oracle.expected_ring_cmds(wg[0], 0, 1, NG, cfg.H, 16, 2)
+            oracle.check_ring_trace(epmod.ep_event_log(rg.h), 2)
+        else:
+            want_cmds = oracle.expected_cmds(wg[0], lay_g, 0, 1, cfg.H, "bf16", mode)
+            assert oracle.cmd_multiset(epmod.ep_cmd_log(rg.h)) == want_cmds
+            oracle.check_fence_trace(epmod.ep_event_log(rg.h), lay_g["count"])
         st = rg.stats()
         assert st["write_rows"] == rows_g <= rows and st["device_error"] == 0 and r.stats()["device_error"] == 0
 
@@ -897,14 +909,25 @@ def test_limits_round_trip(epmod, oracle, S, T, K, E, R, H):
 @pytest.mark.parametrize("cid,T,mask,slices,W,window,threads", [
     (1, None, 0.0, 4, 2, 0, 2), (1, 50, 0.3, 7, 1, 5, 1), (4, 700, 0.0, 16, 2, 16, 4), (5, 1000, 0.1, 8, 3, 0, 4),
     (4, 700, 0.05, 2, 1, 0, 4),       # ~175 rows per channel through a single slot: every chunk waits for a release
-    (2, 128, 0.0, 3, 1, 3, 4), (1, 3, 0.0, 8, 2, 0, 2)])
+    (2, 128, 0.0, 3, 1, 3, 4), (1, 3, 0.0, 8, 2, 0, 2),
+    ("wide", 100, 0.0, 4, 2, 0, 4),   # 64 experts per token over 256 ranks: the widest routing the handle accepts
+    ("long", 40, 0.0, 3, 1, 0, 2)])   # rows of 128 KiB: a row is many pieces, a slot 4 MiB
 def test_ht_ring_dispatch(epmod, oracle, cid, T, mask, slices, W, window, threads):
     """Rows travel sender workgroup -> ring slot -> receiver workgroup -> packed receive buffer, slots are
     reused under head/tail flow control, and all three message kinds pass through the proxy.  The receive
     buffer must equal the plain definition of dispatch; the messages the oracle's expected multiset; the
     proxy's trace the ring protocol (in-sequence application, no overwrite, no stale read)."""
-    cfg = g.config(cid, S=1)
-    idx, _ = g.routing_all(cfg, T)
+    if cid == "wide":
+        cfg = g.EPConfig("wide", T=T, H=128, E=1024, K=64, R=256, S=1)
+        rng = np.random.default_rng(1)
+        idx = np.stack([rng.permutation(1024)[:64] for _ in range(T)]).astype(np.int32)[None]
+    elif cid == "long":
+        cfg = g.EPConfig("long", T=T, H=65536, E=8, K=2, R=4, S=1)
+        rng = np.random.default_rng(2)
+        idx = np.stack([rng.permutation(8)[:2] for _ in range(T)]).astype(np.int32)[None]
+    else:
+        cfg = g.config(cid, S=1)
+        idx, _ = g.routing_all(cfg, T)
     if mask:
         idx = g.mask_random(idx, mask, seed=29)
     T = idx.shape[1]
