@@ -1011,7 +1011,7 @@ int launch_copy_batch(const CopyBatchArgs &b, void *stream) {
 // proxy.  A slice's sender and receiver workgroups are 8 apart in the grid (so that they become
 // resident together); a workgroup depends on no workgroup but its partner.
 // Every wait is bounded; after a timeout the workgroup's abort flag sends every wave to the exit.
-constexpr int kHtMaxRanks = 256, kHtMaxSlots = 4096, kHtHeader = 128;
+constexpr int kHtMaxRanks = 256, kHtMaxSlots = 4096, kHtHeader = 128, kHtMaxOrder = 4096;
 
 struct HtShared {
   int total[kHtMaxRanks];      // rows of channel (slice, r) in this dispatch
@@ -1021,7 +1021,9 @@ struct HtShared {
   unsigned seen[kHtMaxRanks];  // sender: rows released so far (cached head); receiver: first chunk of this sweep
   int lock[kHtMaxRanks];       // sender: who refreshes the cached head; receiver: end chunk of this sweep
   int done[kHtMaxSlots];       // sender: rows stored per (r, slot)
-  int abort, remaining, progress, idle;
+  int order[kHtMaxOrder];      // sender: the slice's valid entries ((t - t0) * K + k), rank-major
+  int start[kHtMaxRanks];      // sender: where rank r's entries begin in the order list
+  int abort, remaining, progress, idle, sorted, nentries;
 };
 
 #define HT_LD(p) __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
@@ -1096,51 +1098,85 @@ EP_DEV void ht_count_stored(const HtRingArgs &a, HtShared &sh, int c, bool mine,
   ring_push(a.fifo, fifo, w0, ((unsigned)EP_RING_TAIL << 30) | (unsigned)sz, seq + 1u, 0u);
 }
 
-EP_DEV void ht_sender(const HtRingArgs &a, HtShared &sh, int c, int t0, int t1) {
-  const int lane = lane_id(), wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+// One (token, k) entry: claim the next position of its channel, wait for the slot if need be, store
+// row and header.  Lane j of the wave remembers (rank, chunk) until the rows are counted.  Returns
+// false when the workgroup is aborting.
+struct HtPending {
+  bool mine;
+  int r, n;
+};
+EP_DEV bool ht_send_entry(const HtRingArgs &a, HtShared &sh, int c, int t, int k, int j, HtPending &pd, int lane) {
+  const int e = a.idx[(size_t)t * a.K + k], row = a.dst_row[(size_t)t * a.K + k];
+  if (!ht_valid(a, e, row)) return true;
+  if (HT_LD(&sh.abort)) return false;
   const int nvec = a.H >> 3;
   const unsigned rb = 2u * (unsigned)a.H;
-  for (int t = t0 + wave; t < t1; t += nwaves) {
-    const u32x4 *xrow = (const u32x4 *)((const char *)a.x + (size_t)t * rb);
-    bool mine = false;  // lane k: entry k of this token is stored but not yet counted
-    int my_r = 0, my_n = 0;
-    for (int k = 0; k < a.K; ++k) {
-      const int e = a.idx[(size_t)t * a.K + k], row = a.dst_row[(size_t)t * a.K + k];
-      if (!ht_valid(a, e, row)) continue;
-      if (HT_LD(&sh.abort)) return;
-      const int r = e / a.E_loc, chan = c * a.R + r;
-      // positions are handed out in arrival order
-      int p = 0;
-      if (lane == 0) p = __hip_atomic_fetch_add(&sh.fill[r], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      p = __builtin_amdgcn_readfirstlane(p);
-      const int n = p >> 5, j = p & 31, w = n % a.W;
-      if (n >= a.W && HT_LD(&sh.seen[r]) < 32u * (unsigned)(n - a.W + 1)) {
-        // The slot is not known to be free.  Rows this wave has stored but not counted could be what
-        // another wave's chunk is waiting for, so they are counted before this wave blocks: a waiting
-        // wave then holds nothing but the position it waits for, and the rows of a channel's oldest
-        // unreleased chunk can always be written.
-        if (__any(mine)) {
-          ht_count_stored(a, sh, c, mine, my_r, my_n);
-          mine = false;
-        }
-        if (!ht_wait_head(a, sh, chan, r, 32u * (unsigned)(n - a.W + 1), lane)) return;
+  const int r = e / a.E_loc, chan = c * a.R + r;
+  // positions are handed out in arrival order
+  int p = 0;
+  if (lane == 0) p = __hip_atomic_fetch_add(&sh.fill[r], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  p = __builtin_amdgcn_readfirstlane(p);
+  const int n = p >> 5, slot_row = p & 31, w = n % a.W;
+  if (n >= a.W && HT_LD(&sh.seen[r]) < 32u * (unsigned)(n - a.W + 1)) {
+    // The slot is not known to be free.  Rows this wave has stored but not counted could be what
+    // another wave's chunk is waiting for, so they are counted before this wave blocks: a waiting
+    // wave then holds nothing but the position it waits for, and the rows of a channel's oldest
+    // unreleased chunk can always be written.
+    if (__any(pd.mine)) {
+      ht_count_stored(a, sh, c, pd.mine, pd.r, pd.n);
+      pd.mine = false;
+    }
+    if (!ht_wait_head(a, sh, chan, r, 32u * (unsigned)(n - a.W + 1), lane)) return false;
+  }
+  char *slot = (char *)a.ring_buf + ((size_t)chan * a.W + w) * a.slot_bytes;
+  u32x4 regs[8];  // cached loads: the token's row comes from HBM once and from a cache for its other k
+  ht_copy_row<false, true, 8>(regs, (u32x4 *)(slot + kHtHeader + (size_t)slot_row * rb),
+                              (const u32x4 *)((const char *)a.x + (size_t)t * rb), nvec, lane);
+  if (lane == 0) __hip_atomic_store((int *)slot + slot_row, row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  if (lane == j) {
+    pd.mine = true;
+    pd.r = r;
+    pd.n = n;
+  }
+  return true;
+}
+
+EP_DEV void ht_sender(const HtRingArgs &a, HtShared &sh, int c, int t0, int t1) {
+  const int lane = lane_id(), wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  HtPending pd{false, 0, 0};
+  if (sh.sorted) {
+    // Entries in rank-major order (the order list), dealt to the waves round-robin, 8 per wave between
+    // two waits for its stores: the chunks of the first ranks are complete after the first round, so
+    // the receiver works while the sender is still busy with the later ranks.
+    constexpr int G = 8;
+    const int total = sh.nentries;
+    for (int first = 0; first < total; first += G * nwaves) {
+      for (int j = 0; j < G; ++j) {
+        const int i = first + j * nwaves + wave;
+        if (i >= total) break;
+        const int ent = sh.order[i];
+        if (!ht_send_entry(a, sh, c, t0 + ent / a.K, ent % a.K, j, pd, lane)) return;
       }
-      char *slot = (char *)a.ring_buf + ((size_t)chan * a.W + w) * a.slot_bytes;
-      u32x4 *dst = (u32x4 *)(slot + kHtHeader + (size_t)j * rb);
-      u32x4 regs[8];  // cached loads: the token's row comes from HBM once and from the L2 for its other k
-      ht_copy_row<false, true, 8>(regs, dst, xrow, nvec, lane);
-      if (lane == 0) __hip_atomic_store((int *)slot + j, row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-      if (lane == (k & 63)) {
-        mine = true;
-        my_r = r;
-        my_n = n;
-      }
-      if ((k & 63) == 63 || k == a.K - 1) {  // (top-k is at most 64: one entry per lane)
-        ht_count_stored(a, sh, c, mine, my_r, my_n);
-        mine = false;
+      if (__any(pd.mine)) {
+        ht_count_stored(a, sh, c, pd.mine, pd.r, pd.n);
+        pd.mine = false;
       }
     }
-    if (__any(mine)) ht_count_stored(a, sh, c, mine, my_r, my_n);  // the last k was masked
+    return;
+  }
+  // slices too long for the order list: token by token, all k of a token between two waits
+  for (int t = t0 + wave; t < t1; t += nwaves) {
+    for (int k = 0; k < a.K; ++k) {
+      if (!ht_send_entry(a, sh, c, t, k, k & 63, pd, lane)) return;
+      if (((k & 63) == 63 || k == a.K - 1) && __any(pd.mine)) {  // (top-k is at most 64: one entry per lane)
+        ht_count_stored(a, sh, c, pd.mine, pd.r, pd.n);
+        pd.mine = false;
+      }
+    }
+    if (__any(pd.mine)) {
+      ht_count_stored(a, sh, c, pd.mine, pd.r, pd.n);
+      pd.mine = false;
+    }
   }
 }
 
@@ -1258,6 +1294,30 @@ __global__ __launch_bounds__(1024) void ht_ring_kernel(HtRingArgs a) {
   }
   __syncthreads();
   if (sender) {
+    // rank-major list of the slice's entries, starting with rank c mod R so that the slices do not
+    // all begin with the same destination
+    if (tid == 0) {
+      int acc = 0;
+      for (int i = 0; i < a.R; ++i) {
+        const int r = (c + i) % a.R;
+        sh.start[r] = acc;
+        acc += sh.total[r];
+      }
+      sh.nentries = acc;
+      sh.sorted = (t1 - t0) * a.K <= kHtMaxOrder;
+    }
+    __syncthreads();
+    if (sh.sorted)
+      for (int i = tid; i < (t1 - t0) * a.K; i += blockDim.x) {
+        const int e = a.idx[(size_t)t0 * a.K + i], row = a.dst_row[(size_t)t0 * a.K + i];
+        if (ht_valid(a, e, row)) {
+          const int r = e / a.E_loc;
+          sh.order[sh.start[r] + __hip_atomic_fetch_add(&sh.lock[r], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)] = i;
+        }
+      }
+    __syncthreads();
+    for (int r = tid; r < a.R; r += blockDim.x) sh.lock[r] = 0;  // from here on: the head-refresh locks
+    __syncthreads();
     ht_sender(a, sh, c, t0, t1);
   } else {
     for (int r = tid; r < a.R; r += blockDim.x)
