@@ -965,6 +965,43 @@ def test_ht_ring_dispatch(epmod, oracle, cid, T, mask, slices, W, window, thread
         assert np.array_equal(tail[0], 2 * per_channel) and np.array_equal(head[0], 2 * per_channel)
 
 
+def test_ht_ring_dispatch_of_several_sources(epmod, oracle):
+    """Config 2's 32 routing tables: sources 0, 7 and 31 each send their tokens through their own set of
+    channels (counters, sequence numbers and proxy state are per source) into the one receive buffer."""
+    cfg = g.config(2)
+    idx, _ = g.routing_all(cfg)
+    rows = idx.size
+    slices, W = 5, 2
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    want = np.full((rows, cfg.H), 0xBFC0, np.uint16)
+    with _runner(epmod, cfg, flags=flags, ht_slices=slices, ht_ring_slots=W, reorder_window=5) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+        recv = torch.full((rows, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")
+        want_cmds = None
+        for s in (0, 7, 31):
+            x = g.activations(cfg, s)
+            epmod.ep_ht_dispatch(r.h, bits_to_bf16(x), d_idx[s], lay.dst_row[s], cfg.T, s, ring, recv, rows)
+            r.wait()
+            part, wc = oracle.dispatch_bf16(x, idx[s], want_lay["dst_row"][s], cfg.E_loc, rows, -1, fill=0xBFC0)
+            want[wc > 0] = part[wc > 0]
+            exp = oracle.expected_ring_cmds(idx[s], s, cfg.E_loc, cfg.R, cfg.H, slices, W)
+            want_cmds = exp if want_cmds is None else want_cmds + exp
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_to_bits(recv), want)
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        assert oracle.ring_cmd_multiset(epmod.ep_cmd_log(r.h)) == want_cmds
+        oracle.check_ring_trace(epmod.ep_event_log(r.h), W)
+        tail, head = epmod.ep_ring_counters(r.h, cfg.S, slices, cfg.R)
+        for s in range(cfg.S):
+            per = oracle.ring_channel_rows(idx[s], cfg.E_loc, cfg.R, slices) if s in (0, 7, 31) else 0
+            assert np.array_equal(tail[s], per + np.zeros_like(tail[s])) and np.array_equal(head[s], tail[s])
+
+
 @pytest.mark.parametrize("cid,slices,W", [(4, 128, 2), (5, 64, 4)])
 def test_ht_ring_dispatch_full_size(epmod, oracle, cid, slices, W):
     """The full prefill-sized workloads through the rings, in the shape the timing suite launches."""
