@@ -148,8 +148,9 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out);
  * joins the proxy threads, frees everything.  The handle is dead afterwards. */
 int ep_proxy_stop(ep_handle *h);
 
-/* ep_layout - "dynamically size and route messages every step" (Section 2.1,
- * Irregular communication): from the router's top-k expert ids compute
+/* ep_layout - routing is only known at run time, so sizes and destinations of the
+ * transfers are worked out anew for every step (Section 2.1, paragraph on irregular
+ * communication): from the router's top-k expert ids compute
  *   count[s][e]      tokens of source s that chose expert e
  *   expert_total[e], rank_total[r]
  *   base[s][e]       first receive row of (s, e): rows are expert-major,

@@ -4,7 +4,7 @@
  * TEST INFRASTRUCTURE, NOT PRODUCT: a plain, slow, scalar C implementation of
  * what the path computes, written from the paper's statement of the problem
  * (Section 2.1: tokens are dispatched to the GPUs hosting their selected
- * experts and expert outputs are merged back "in the original token order";
+ * experts and expert outputs are merged back into the order of the tokens;
  * Section 2.2: the combine reduce is a weighted sum; Section 2.1 "Fine-grained
  * token-level transfers": a token is an FP8, hidden-7168, ~7 KB message).
  * It shares no code, header, table or constant with the HIP library and is
@@ -258,7 +258,7 @@ void oracle_dequant_rows(const uint8_t *q, const float *scale, long rows, int H,
 
 /* ---------------------------------------------------------------- combine
  * Step (4): expert outputs are gathered back to the original token order and
- * reduced by a weighted sum (Section 2.2: "reduce (weighted sum)"):
+ * reduced by a weighted sum (Section 2.2):
  *   out[t,h] = bf16( sum_k w[t,k] * y[dst_row[t,k], h] )
  * with an fp32 accumulator that starts at +0 and takes the k terms in
  * ascending k as fused multiply-adds; masked k (dst_row == -1) are skipped;
