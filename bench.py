@@ -207,7 +207,9 @@ def run_suite(args) -> int:
                     del recv_g, partial
             # sender-side policies of the proxy on the per-token stream: best-effort packing, pacing
             for label, kw in (("pack8", dict(pack_rows=8)), ("pack8_hold50us", dict(pack_rows=8, pack_hold_us=50)),
-                              ("pace32_window256", dict(max_outstanding=32, reorder_window=256))):
+                              ("pace32_window256", dict(max_outstanding=32, reorder_window=256)),
+                              ("receiver_fence_window64", dict(reorder_window=64)),
+                              ("sender_fence_window64", dict(reorder_window=64, flags=ep.EP_FLAG_SENDER_FENCE))):
                 with EPRunner(R, E, K, H, T, num_proxy_threads=4, spin_timeout_ms=10000, **kw) as rp:
                     Lp = rp.layout(d_idx)
                     e2e = []
@@ -222,7 +224,8 @@ def run_suite(args) -> int:
                     res[f"per_token_{label}"] = {
                         "launch_to_last_counter_us": round(e2e[len(e2e) // 2], 1), "writes_per_dispatch": st["writes"] // 13,
                         "messages_per_dispatch": st["write_msgs"] // 13, "paced_per_dispatch": st["paced"] // 13,
-                        "max_in_flight": st["max_in_flight"]}
+                        "max_in_flight": st["max_in_flight"], "atomics_deferred_per_dispatch": st["atomics_deferred"] // 13,
+                        "sender_held_per_dispatch": st["sender_held"] // 13}
             # ring-buffer channels: sender -> ring slot -> receiver -> packed buffer, head/tail through the proxy
             for slices, W in ((128, 2), (128, 4), (256, 2)):
                 with EPRunner(R, E, K, H, T, num_proxy_threads=4, spin_timeout_ms=10000, ht_slices=slices,

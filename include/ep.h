@@ -84,7 +84,10 @@ enum ep_cmd_mode {
 enum ep_flags {
   EP_FLAG_LOG_CMDS = 1,   /* proxy keeps every polled command (ep_cmd_log)          */
   EP_FLAG_LOG_EVENTS = 2, /* proxy keeps the receiver-side event trace (ep_event_log) */
-  EP_FLAG_HOST_ONLY = 4   /* no device: ring + proxy only, producer is ep_host_push  */
+  EP_FLAG_HOST_ONLY = 4,  /* no device: ring + proxy only, producer is ep_host_push  */
+  EP_FLAG_SENDER_FENCE = 8 /* the alternative Section 3.3 weighs against the receiver-side fence: the SENDER half
+                              holds a count Atomic back until the Writes it vouches for have completed, then
+                              sends it; the receiver never has to buffer one.  Costs the sender a round trip. */
 };
 
 typedef struct ep_config {
@@ -122,6 +125,7 @@ typedef struct ep_stats_t {
   uint64_t write_rows;       /* sum of rows carried by Writes                          */
   uint64_t atomics_applied;
   uint64_t atomics_deferred; /* atomics that had to wait in the control buffer         */
+  uint64_t sender_held;      /* atomics the sender half held back (EP_FLAG_SENDER_FENCE) */
   uint64_t ordered_parked;   /* sequenced messages that arrived ahead of their turn    */
   uint64_t rejected;         /* commands that failed offset translation / bounds check */
   uint64_t write_msgs;       /* messages that carried the Writes (fewer than writes when rows were packed) */

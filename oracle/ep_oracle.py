@@ -513,6 +513,8 @@ EV_WRITE, EV_ATOMIC_IN, EV_ATOMIC_APPLIED = 1, 2, 3
 # Sender half: kind 14 = a message handed to the transport; [1] source, [2] destination rank,
 # [3] messages this thread then had in flight to that rank.
 EV_SENT = 14
+# kind 15 = a count Atomic held back by the sender half (sender-side fence); [2] global expert, [3] X
+EV_SENDER_HELD = 15
 
 
 def check_fence_trace(events: np.ndarray, count: np.ndarray) -> Dict[str, int]:
@@ -529,7 +531,7 @@ def check_fence_trace(events: np.ndarray, count: np.ndarray) -> Dict[str, int]:
     waited = 0
     for kind_thr, src, e, val in ev.tolist():
         kind, thr = kind_thr & 0xFF, kind_thr >> 8
-        if EV_ORD_WRITE_IN <= kind <= EV_SENT:
+        if EV_ORD_WRITE_IN <= kind <= EV_SENDER_HELD:
             continue                                   # records of the other protocols and of the sender half
         key = (src, e)
         assert owner.setdefault(key, thr) == thr, f"(src,expert) {key} handled by two threads"

@@ -90,6 +90,8 @@ struct alignas(64) ProxyThread {
   // receiver half: rows seen and parked atomics per (source, global expert)
   std::vector<int32_t> seen;
   std::vector<std::deque<int32_t>> parked;  // the control buffer
+  std::vector<std::deque<int32_t>> sender_parked;  // sender-side fence: atomics not yet sent, per (source, expert)
+  std::vector<uint8_t> atomic_flying;              // ... and whether one of that expert is on its way
   std::vector<WireEvent> window;            // in-flight immediates (reordering hook)
   // proxy-performed peer writes (registered heaps): descriptors of the batch being filled, and the
   // batches in flight with the arrival notices they will release when their copy kernel is done
@@ -122,7 +124,7 @@ struct alignas(64) ProxyThread {
   // statistics (written by the owner thread only, read racy-but-atomically)
   std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
       applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0}, barriers{0},
-      copy_batches{0}, copied_bytes{0}, write_msgs{0}, paced{0}, max_in_flight{0};
+      copy_batches{0}, copied_bytes{0}, write_msgs{0}, paced{0}, max_in_flight{0}, sender_held{0};
   std::mutex log_mu;
   std::vector<uint32_t> cmd_log, event_log;
 };
@@ -197,6 +199,8 @@ void log_event(ep_handle *h, ProxyThread &P, uint32_t kind, uint32_t src, uint32
   P.event_log.insert(P.event_log.end(), {kind | ((uint32_t)P.tid << 8), src, e, val});
 }
 
+void release_sender_parked(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t dr, uint32_t le, size_t key);
+
 void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_t value) {
   const size_t key = (size_t)src * h->cfg.num_experts + e;
   P.seen[key] -= value;
@@ -206,6 +210,11 @@ void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_
   log_event(h, P, 3, src, e, (uint32_t)value);
   P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
   P.applied.store(P.applied.load(std::memory_order_relaxed) + 1, std::memory_order_release);
+  if (!P.sender_parked.empty()) {  // sender-side fence: the next Atomic of this expert may go now
+    P.atomic_flying[key] = 0;
+    if (!P.sender_parked[key].empty())
+      release_sender_parked(h, P, src, e / (uint32_t)h->E_loc, e % (uint32_t)h->E_loc, key);
+  }
 }
 
 // Receiver half: interpret one immediate.  Writes have already landed; they
@@ -213,6 +222,8 @@ void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_
 // only when that count has reached its value, otherwise it waits in the
 // control buffer; arrivals for other experts never release it (Section 3.3,
 // "partial completion fence").
+void send_msg(ep_handle *h, ProxyThread &P, const Outbound &m);
+void release_sender_parked(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t dr, uint32_t le, size_t key);
 void deliver_ordered(ep_handle *h, ProxyThread &P, const WireEvent &ev);
 void deliver_ring(ep_handle *h, ProxyThread &P, const WireEvent &ev);
 
@@ -233,6 +244,9 @@ void deliver(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
     const int32_t rows = (int32_t)((ev.imm >> 13) & 0x3Fu) + 1;
     P.seen[key] += rows;
     log_event(h, P, 1, ev.src, e, (uint32_t)rows);
+    // sender-side fence: this arrival is also the completion the sender half was waiting for
+    if (!P.sender_parked.empty() && !P.sender_parked[key].empty())
+      release_sender_parked(h, P, ev.src, ev.dst_rank, le, key);
     std::deque<int32_t> &q = P.parked[key];
     while (!q.empty() && P.seen[key] >= q.front()) {
       const int32_t v = q.front();
@@ -452,6 +466,22 @@ void send_msg(ep_handle *h, ProxyThread &P, const Outbound &m) {
   launch_msg(h, P, m);
 }
 
+// Sender-side fence (the alternative weighed in Section 3.3, "Where to enforce the delivery
+// semantics"): a count Atomic leaves only when the rows it vouches for have completed.  Sender and
+// receiver halves share the arrival counts, so "completed" is the arrival of the rows' notices.
+void release_sender_parked(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t dr, uint32_t le, size_t key) {
+  std::deque<int32_t> &q = P.sender_parked[key];
+  // one Atomic per expert on its way at a time: the next one's rows are counted after this one has
+  // been applied (it takes its rows off the arrival count)
+  if (q.empty() || P.atomic_flying[key] || P.seen[key] < q.front()) return;
+  const int32_t value = q.front();
+  q.pop_front();
+  P.atomic_flying[key] = 1;
+  Outbound m;
+  m.notice = WireEvent{(1u << 31) | (le << 19) | (uint32_t)value, (uint16_t)src, (uint8_t)dr, 0};
+  send_msg(h, P, m);
+}
+
 // Lets waiting messages go wherever arrivals have made room.
 void pump_held(ep_handle *h, ProxyThread &P) {
   if (!P.held_total) return;
@@ -586,6 +616,18 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       if (c.pack_rows > 1) {  // rows of this expert still being packed leave before their count does
         const int32_t slot = P.open_idx[src * (uint32_t)c.num_experts + dr * (uint32_t)h->E_loc + le];
         if (slot >= 0) close_open(h, P, (size_t)slot);
+      }
+      if (c.flags & EP_FLAG_SENDER_FENCE) {
+        const size_t key = (size_t)src * c.num_experts + (size_t)dr * h->E_loc + le;
+        std::deque<int32_t> &q = P.sender_parked[key];
+        if (!q.empty() || P.atomic_flying[key] || P.seen[key] < (int32_t)w1) {
+          // rows still outstanding (or an earlier Atomic of this expert not applied yet): it waits here
+          bump(P.sender_held, 1);
+          log_event(h, P, 15, src, dr * (uint32_t)h->E_loc + le, w1);
+        }
+        q.push_back((int32_t)w1);
+        release_sender_parked(h, P, src, dr, le, key);
+        break;
       }
       Outbound m;
       m.notice = WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint8_t)dr, 0};
@@ -1006,6 +1048,10 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     }
     P.seen.assign((size_t)S * E, 0);
     P.parked.resize((size_t)S * E);
+    if (cfg->flags & EP_FLAG_SENDER_FENCE) {
+      P.sender_parked.resize((size_t)S * E);
+      P.atomic_flying.assign((size_t)S * E, 0);
+    }
     P.next_seq.assign((size_t)S * cfg->num_ranks, 0);
     P.early.resize((size_t)S * cfg->num_ranks);
     P.in_flight.assign((size_t)cfg->num_ranks, 0);
@@ -1413,6 +1459,7 @@ int ep_stats(ep_handle *h, ep_stats_t *out) {
     out->atomics_deferred += P.deferred.load();
     out->ordered_parked += P.ordered_parked.load();
     out->rejected += P.rejected.load();
+    out->sender_held += P.sender_held.load();
     out->write_msgs += P.write_msgs.load();
     out->paced += P.paced.load();
     if (P.max_in_flight.load() > out->max_in_flight) out->max_in_flight = P.max_in_flight.load();
@@ -1443,7 +1490,8 @@ int ep_reset_stats(ep_handle *h) {
     ProxyThread &P = h->threads[i];
     for (auto *a : {&P.cmds, &P.writes, &P.atomics, &P.drains, &P.write_bytes, &P.write_rows, &P.applied,
                     &P.deferred, &P.rejected, &P.first_poll_ns, &P.last_apply_ns, &P.ordered_parked, &P.barriers,
-                    &P.copy_batches, &P.copied_bytes, &P.write_msgs, &P.paced, &P.max_in_flight})
+                    &P.copy_batches, &P.copied_bytes, &P.write_msgs, &P.paced, &P.max_in_flight,
+                    &P.sender_held})
       a->store(0);
     std::lock_guard<std::mutex> g(P.log_mu);
     P.cmd_log.clear();

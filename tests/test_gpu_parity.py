@@ -74,13 +74,13 @@ def test_layout_special_shapes(epmod, oracle):
 
 # ---------------------------------------------------------- dispatch bf16
 def _dispatch_case(epmod, oracle, cfg, T, mask, cmd_mode, rank_filter=-1, src=0, extra_rows=3, proxy_writes=False,
-                   **kw):
+                   extra_flags=0, **kw):
     idx, w = g.routing_all(cfg, T)
     if mask:
         idx = g.mask_random(idx, mask, seed=23)
     T = idx.shape[1]
     x = g.activations(cfg, src, T=T)
-    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS | extra_flags
     rows = int((idx >= 0).sum()) + extra_rows
     with _runner(epmod, cfg, T, flags=flags, heap_rows=rows, **kw) as r:
         d_idx = _dev(idx)
@@ -305,6 +305,23 @@ def test_atomics_first_forces_the_fence_path(epmod, oracle):
         # one channel, atomics pushed by the first wavefront before it stores anything: atomics with a
         # nonzero count reach the receiver ahead of (some of) their rows and must wait
         assert res["waited"] == out["stats"]["atomics_deferred"] and res["waited"] >= 1
+
+
+@pytest.mark.parametrize("cid,T,window,proxy_writes", [(1, None, 0, False), (4, 400, 32, False), (5, 300, 8, True)])
+def test_sender_side_fence_on_a_real_dispatch(epmod, oracle, cid, T, window, proxy_writes):
+    """The count Atomics are pushed before any row (one channel, one thread), so each one with a nonzero
+    count reaches the proxy ahead of its rows.  With the sender-side fence the sender half holds them;
+    none has to wait at the receiver, and buffer, counters and fence trace are as ever."""
+    cfg = g.config(cid, S=1)
+    out = _dispatch_case(epmod, oracle, cfg, T, 0.0, epmod.EP_CMD_PER_TOKEN | epmod.EP_CMD_ATOMICS_FIRST,
+                         proxy_writes=proxy_writes, extra_flags=epmod.EP_FLAG_SENDER_FENCE, num_channels=1,
+                         num_proxy_threads=1, reorder_window=window, reorder_seed=4)
+    res = _check_commands(epmod, oracle, cfg, out, "per_token")
+    st = out["stats"]
+    assert res["waited"] == 0 and st["atomics_deferred"] == 0
+    assert st["sender_held"] >= 1
+    held = out["events"][(out["events"][:, 0] & 0xFF) == oracle.EV_SENDER_HELD]
+    assert len(held) == st["sender_held"]
 
 
 def test_drain_blocks_until_popped_and_small_ring_backpressure(epmod, oracle):

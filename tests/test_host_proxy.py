@@ -636,3 +636,53 @@ def test_pacing_and_packing_configuration_is_validated(ep):
         with pytest.raises(ep.EPError) as ei:
             ep.ep_proxy_stop(_start(ep, **kw))
         assert ei.value.rc == ep.EP_EINVAL
+
+
+# ------------------------------------- sender-side fence (Section 3.3, the alternative)
+@pytest.mark.parametrize("window", [0, 8, 300])
+def test_sender_side_fence_holds_atomics_at_the_sender(ep, oracle, window):
+    """With EP_FLAG_SENDER_FENCE the sender half keeps a count Atomic until the rows it vouches for have
+    arrived, so the receiver never buffers one - whatever the push order and the reordering in flight -
+    and the counters come out the same.  Two rounds on the same experts: the second round's Atomic waits
+    for the first to be applied."""
+    E_loc, rb, C = 4, 2048, 4
+    h = _start(ep, reorder_window=window, reorder_seed=21, num_src=1,
+               flags=ep.EP_FLAG_HOST_ONLY | ep.EP_FLAG_LOG_CMDS | ep.EP_FLAG_LOG_EVENTS | ep.EP_FLAG_SENDER_FENCE)
+    try:
+        rng = np.random.default_rng(window)
+        row = 0
+        for rnd in range(2):
+            count = rng.integers(0, 30, size=(1, 16))
+            count[0, 3] = 0
+            ep.ep_host_expect_atomics(h, 16)
+            order = rng.permutation(16)
+            for e in order[:8]:                                   # these Atomics come before their rows
+                _atomic(ep, h, int(e) % C, 0, int(e) // E_loc, int(e) % E_loc, int(count[0, e]), E_loc)
+            for e in rng.permutation(np.repeat(np.arange(16), count[0])):
+                _write(ep, h, int(e) % C, 0, int(e) // E_loc, int(e) % E_loc, 1, rb, row)
+                row += 1
+            for e in order[8:]:
+                _atomic(ep, h, int(e) % C, 0, int(e) // E_loc, int(e) % E_loc, int(count[0, e]), E_loc)
+            ep.ep_wait(h)
+            assert np.array_equal(ep.ep_counters(h, 1, 16), count)
+        _drain_all(ep, h, C)
+        st = ep.ep_stats(h)
+        assert st["atomics_deferred"] == 0 and st["atomics_applied"] == 32 and st["proxy_error"] == 0
+        assert st["sender_held"] >= 1
+        ev = ep.ep_event_log(h)
+        held = ev[(ev[:, 0] & 0xFF) == oracle.EV_SENDER_HELD]
+        assert len(held) == st["sender_held"]
+        # at the receiver every Atomic found its rows there already
+        seen, waited = {}, 0
+        for kind_thr, src, e, val in ev.tolist():
+            kind = kind_thr & 0xFF
+            if kind == oracle.EV_WRITE:
+                seen[e] = seen.get(e, 0) + val
+            elif kind == oracle.EV_ATOMIC_IN:
+                waited += seen.get(e, 0) < val
+            elif kind == oracle.EV_ATOMIC_APPLIED:
+                seen[e] = seen.get(e, 0) - val
+        assert waited == 0
+        oracle.check_pacing_trace(ev, 0, E_loc)
+    finally:
+        ep.ep_proxy_stop(h)
