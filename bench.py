@@ -246,6 +246,30 @@ def run_suite(args) -> int:
                         "ring_MiB": rr_.ht_ring_bytes() >> 20,
                         "GBs_rows_delivered": round(my_rows * H * 2 / e2e[len(e2e) // 2] / 1e3, 1)}
                     del ring
+        if cid == 4:
+            # closed-loop FIFO stress: commands per second and push -> popped latency against the number of pushers
+            fs = {}
+            for threads in (1, 4):
+                for pushers in (1, 16, 256, 4096):
+                    per = 400 if pushers <= 256 else 50
+                    with EPRunner(R, E, K, H, T, num_proxy_threads=threads, spin_timeout_ms=10000) as rf:
+                        ls = torch.zeros(pushers, dtype=torch.int64, device="cuda")
+                        lm = torch.zeros(pushers, dtype=torch.int64, device="cuda")
+                        ep.ep_fifo_stress(rf.h, pushers, 20, ls, lm)
+                        rf.wait()
+                        torch.cuda.synchronize()
+                        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        a.record()
+                        ep.ep_fifo_stress(rf.h, pushers, per, ls, lm)
+                        b.record()
+                        rf.wait()
+                        torch.cuda.synchronize()
+                        us = a.elapsed_time(b) * 1e3
+                        fs[f"threads{threads}_pushers{pushers}"] = {
+                            "Mcmd_per_s": round(pushers * per / us, 2),
+                            "mean_latency_us": round(float(ls.sum().item()) / (pushers * per) / 100.0, 2),
+                            "max_latency_us": round(float(lm.max().item()) / 100.0, 1)}
+            res["fifo_stress"] = fs
         out[cfg.name] = res
         del recv, rq, rs, d_x, o
         torch.cuda.empty_cache()

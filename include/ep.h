@@ -357,6 +357,17 @@ int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx);
  * (ep_dispatch does this itself for its own). */
 int ep_host_expect_atomics(ep_handle *h, int32_t n);
 
+/* ep_fifo_stress - closed-loop load test of the GPU->CPU channel (the FIFO stress
+ * test of Section 5.3): `pushers` wavefronts (lane 0 of each; channel = pusher
+ * mod C) each push `cmds_per_pusher` commands, one after the other, waiting with
+ * Check-completion until the proxy has popped each before pushing the next.  The
+ * command is a count Atomic of value 0 for (source 0, expert 0): harmless, applied
+ * at once (ep_wait accounts for them; do not run it while a dispatch of source 0
+ * is being awaited).  d_lat_sum / d_lat_max (device, uint64 [pushers]) receive
+ * each pusher's summed and largest push->popped time in ticks of 10 ns. */
+int ep_fifo_stress(ep_handle *h, int32_t pushers, int32_t cmds_per_pusher, uint64_t *d_lat_sum, uint64_t *d_lat_max,
+                   void *stream);
+
 /* ep_bw_probe - plain streaming kernels for measuring this device's bandwidth
  * ceilings next to the path's kernels (no part of the method): kind 0 reads
  * `bytes` from d_src (16-byte non-temporal loads, one per lane), kind 1 writes

@@ -68,7 +68,7 @@ EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_co
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
-           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters"]
+           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters", "ep_fifo_stress"]
 
 _lib = None
 
@@ -118,6 +118,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_register_heaps.argtypes = [vp, vp, i64, vp, i64]
     L.ep_ht_dispatch.argtypes = [vp, vp, vp, vp, i32, i32, vp, i64, vp, i64, vp]
     L.ep_ring_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
+    L.ep_fifo_stress.argtypes = [vp, i32, i32, vp, vp, vp]
     for name in EXPORTS:
         getattr(L, name).restype = C.c_int
     L.ep_last_error.argtypes = []
@@ -237,6 +238,11 @@ def ep_ht_dispatch(h: int, x, topk_idx, dst_row, T: int, src_rank: int, ring, re
     _check("ep_ht_dispatch", load_library().ep_ht_dispatch(h, _ptr(x), _ptr(topk_idx), _ptr(dst_row), T, src_rank,
                                                            _ptr(ring), ring.numel() * ring.element_size(),
                                                            _ptr(recv), recv_rows, _stream(stream)))
+
+
+def ep_fifo_stress(h: int, pushers: int, cmds_per_pusher: int, lat_sum, lat_max, stream=None) -> None:
+    _check("ep_fifo_stress", load_library().ep_fifo_stress(h, pushers, cmds_per_pusher, _ptr(lat_sum), _ptr(lat_max),
+                                                           _stream(stream)))
 
 
 def ep_ring_counters(h: int, S: int, slices: int, R: int):

@@ -1333,6 +1333,21 @@ int ep_barrier(ep_handle *h, void *stream) {
   return HIP_OK((hipError_t)launch_barrier(h->ring, stream)) ? EP_OK : EP_EHIP;
 }
 
+int ep_fifo_stress(ep_handle *h, int32_t pushers, int32_t cmds_per_pusher, uint64_t *d_lat_sum, uint64_t *d_lat_max,
+                   void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (h->nthreads < 1) return EP_ESTATE;  // nobody would ever pop a command
+  if (pushers < 1 || pushers > 65536 || cmds_per_pusher < 1 || cmds_per_pusher > (1 << 20)) return EP_EINVAL;
+  if (!d_lat_sum || !d_lat_max) return EP_EINVAL;
+  if (int e = dev_err(h)) return e;
+  h->expected_atomics.fetch_add((int64_t)pushers * cmds_per_pusher, std::memory_order_relaxed);
+  return HIP_OK((hipError_t)launch_fifo_stress(h->ring, pushers, cmds_per_pusher, (unsigned long long *)d_lat_sum,
+                                               (unsigned long long *)d_lat_max, stream))
+             ? EP_OK
+             : EP_EHIP;
+}
+
 int ep_recv_wait(ep_handle *h, int32_t src_rank, int32_t dst_rank_filter, int32_t *d_counts_out, void *stream) {
   if (!h) return EP_EINVAL;
   if (h->host_only) return EP_ESTATE;

@@ -157,6 +157,8 @@ int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
 int launch_combine(const CombineArgs &a, void *stream);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
 int launch_barrier(const RingDev &ring, void *stream);
+int launch_fifo_stress(const RingDev &ring, int pushers, int per_pusher, unsigned long long *lat_sum,
+                       unsigned long long *lat_max, void *stream);
 int launch_ht_ring(const HtRingArgs &a, void *stream);
 int launch_copy_batch(const CopyBatchArgs &b, void *stream);
 int launch_dedup(const DedupArgs &a, void *stream);

@@ -1361,6 +1361,34 @@ int launch_barrier(const RingDev &ring, void *stream) {
   return (int)hipGetLastError();
 }
 
+// ------------------------------------------------------------- FIFO stress
+// Closed loop: lane 0 of every wave pushes a command, waits until the proxy has popped it
+// (Check-completion), and only then pushes the next one.
+__global__ void fifo_stress_kernel(RingDev ring, int pushers, int per_pusher, unsigned long long *lat_sum,
+                                   unsigned long long *lat_max) {
+  const int p = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  if (p >= pushers || lane_id() != 0) return;
+  const unsigned ch = (unsigned)p % ring.channels;
+  unsigned long long sum = 0, mx = 0;
+  for (int i = 0; i < per_pusher; ++i) {
+    const unsigned long long t0 = wall_clock64();
+    const unsigned long long idx = ring_push(ring, ch, cmd_w0(EP_OP_ATOMIC, 0, 0, 0), 0u, 0u, 0u);
+    if (idx == ~0ull || !ring_wait_completion(ring, ch, idx)) break;
+    const unsigned long long dt = wall_clock64() - t0;
+    sum += dt;
+    mx = dt > mx ? dt : mx;
+  }
+  lat_sum[p] = sum;
+  lat_max[p] = mx;
+}
+
+int launch_fifo_stress(const RingDev &ring, int pushers, int per_pusher, unsigned long long *lat_sum,
+                       unsigned long long *lat_max, void *stream) {
+  hipLaunchKernelGGL(fifo_stress_kernel, dim3((unsigned)((pushers + 3) / 4)), dim3(256), 0, (hipStream_t)stream, ring,
+                     pushers, per_pusher, lat_sum, lat_max);
+  return (int)hipGetLastError();
+}
+
 // ------------------------------------------------------------ receive wait
 // One thread per expert polls its arrival flag in pinned host memory with
 // system-scope loads (each poll is a PCIe read, so lanes sleep between polls),

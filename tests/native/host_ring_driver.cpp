@@ -21,6 +21,7 @@ int launch_combine_partial(const CombinePartialArgs&, void*) { return 0; }
 int launch_bw_probe(int, const void*, void*, long long, void*) { return 0; }
 int launch_copy_batch(const CopyBatchArgs&, void*) { return 0; }
 int launch_ht_ring(const HtRingArgs&, void*) { return 0; }
+int launch_fifo_stress(const RingDev&, int, int, unsigned long long*, unsigned long long*, void*) { return 0; }
 }
 static uint32_t w0(uint32_t op, uint32_t src, uint32_t dr, uint32_t le) { return (op << 28) | (src << 20) | (dr << 12) | le; }
 int main() {

@@ -1079,6 +1079,28 @@ def test_ht_ring_dispatch_argument_errors(epmod):
         assert r.stats()["drains"] == 8 and r.stats()["writes"] == 0
 
 
+def test_fifo_stress_closed_loop(epmod):
+    """Every pusher gets every command popped (Check-completion), the proxy sees exactly pushers x commands,
+    spread over the channels, and each round trip takes a plausible time."""
+    cfg = g.config(1)
+    for pushers, per, ring_entries in ((1, 50, 4096), (64, 40, 4096), (1000, 10, 16)):
+        with _runner(epmod, cfg, num_channels=8, num_proxy_threads=4, ring_entries=ring_entries) as r:
+            s = torch.zeros(pushers, dtype=torch.int64, device="cuda")
+            m = torch.zeros(pushers, dtype=torch.int64, device="cuda")
+            epmod.ep_fifo_stress(r.h, pushers, per, s, m)
+            r.wait()
+            torch.cuda.synchronize()
+            st = r.stats()
+            assert st["cmds"] == pushers * per == st["atomics_applied"] and st["device_error"] == 0
+            assert sum(st["per_thread_cmds"]) == pushers * per
+            mean_us = s.cpu().numpy() / per / 100.0
+            assert (mean_us > 0.5).all() and (mean_us < 5000).all()           # a PCIe round trip at least
+            assert (m.cpu().numpy() >= s.cpu().numpy() / per).all()
+    with _runner(epmod, cfg, num_proxy_threads=0) as r:                       # nobody would pop
+        with pytest.raises(epmod.EPError):
+            epmod.ep_fifo_stress(r.h, 1, 1, s, m)
+
+
 def _cpu_barrier_peer(name, delay, q):
     import time as _t
     import paper_2512_19849_amd as ep_
