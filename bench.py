@@ -245,6 +245,16 @@ def run_suite(args) -> int:
                         "launch_to_drained_us": round(e2e[len(e2e) // 2], 1), "cmds_per_dispatch": st["cmds"] // 13,
                         "ring_MiB": rr_.ht_ring_bytes() >> 20,
                         "GBs_rows_delivered": round(my_rows * H * 2 / e2e[len(e2e) // 2] / 1e3, 1)}
+                    if cid == 5 and (slices, W) == (128, 2):
+                        e2e = []
+                        for _ in range(13):
+                            torch.cuda.synchronize()
+                            t0 = time.perf_counter()
+                            rr_.ht_dispatch(d_x, d_idx[0], Lr, ring, rq, recv_scale=rs)
+                            rr_.wait()
+                            e2e.append((time.perf_counter() - t0) * 1e6)
+                        e2e = sorted(e2e[3:])
+                        res["ht_ring_fp8_slices128_slots2"] = {"launch_to_drained_us": round(e2e[len(e2e) // 2], 1)}
                     del ring
         if cid == 4:
             # closed-loop FIFO stress: commands per second and push -> popped latency against the number of pushers

@@ -308,14 +308,19 @@ int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv
  * (ep_ring_counters).  The launch ends with a Drain on every FIFO; ep_wait
  * returns when those are through.
  *   d_x [T,H] bf16, d_topk_idx / d_dst_row int32 [T,K] of source src_rank
- *   d_ring   device, ring_bytes >= ht_slices * R * W * (128 + 32 * 2H), 16-byte aligned
- *   d_recv   device bf16 [recv_rows, H]
+ *   payload  EP_BF16: rows travel as they are.  EP_FP8_E4M3: the sender quantises (as ep_dispatch does) and a
+ *            row in a slot is H codes followed by H/128 fp32 scales (padded to 16 bytes); the receiver splits it
+ *            into d_recv (u8 [recv_rows, H]) and d_recv_scale (f32 [recv_rows, H/128]).  d_recv_scale is NULL
+ *            exactly for EP_BF16.
+ *   d_ring   device, ring_bytes >= ht_slices * R * W * (128 + 32 * 2H), 16-byte aligned (the slot stride is the
+ *            same for both payloads)
+ *   d_recv   device bf16 [recv_rows, H] (or the FP8 pair)
  * Needs ht_slices > 0 and proxy threads; one ep_ht_dispatch per source at a time
  * (wait with ep_wait before the next one of the same source).  Every wait in the
  * kernel is bounded by spin_timeout_ms (EP_ETIMEOUT in the sticky device error). */
 int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const int32_t *d_dst_row, int32_t T,
-                   int32_t src_rank, void *d_ring, int64_t ring_bytes, void *d_recv, int64_t recv_rows,
-                   void *stream);
+                   int32_t src_rank, int32_t payload, void *d_ring, int64_t ring_bytes, void *d_recv,
+                   float *d_recv_scale, int64_t recv_rows, void *stream);
 
 /* ep_ring_counters - pinned-host int32 [S, ht_slices, R] each: rows announced
  * (tail) and rows released (head) per ring-buffer channel, running totals. */

@@ -620,11 +620,12 @@ def decode_ring_cmd(words: Iterable[int]) -> Dict[str, int]:
 
 
 def expected_ring_cmds(idx_s: np.ndarray, s: int, E_loc: int, R: int, H: int, slices: int, W: int,
-                       seq_base: Optional[np.ndarray] = None, rseq_base: Optional[np.ndarray] = None) -> Counter:
+                       seq_base: Optional[np.ndarray] = None, rseq_base: Optional[np.ndarray] = None,
+                       payload: str = "bf16") -> Counter:
     """Multiset of the ring-mode messages of one dispatch of source s; seq_base / rseq_base [slices, R]
     are the channels' sequence numbers before the dispatch (they keep running across dispatches)."""
     rows = ring_channel_rows(idx_s, E_loc, R, slices)
-    rb, sb = row_bytes(H, "bf16"), ring_slot_bytes(H)
+    rb, sb = row_bytes(H, payload), ring_slot_bytes(H)      # the slot stride does not depend on the payload
     out: Counter = Counter()
     for c in range(slices):
         for r in range(R):

@@ -116,7 +116,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_host_expect_atomics.argtypes = [vp, i32]
     L.ep_bw_probe.argtypes = [i32, vp, vp, i64, vp]
     L.ep_register_heaps.argtypes = [vp, vp, i64, vp, i64]
-    L.ep_ht_dispatch.argtypes = [vp, vp, vp, vp, i32, i32, vp, i64, vp, i64, vp]
+    L.ep_ht_dispatch.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp]
     L.ep_ring_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     L.ep_fifo_stress.argtypes = [vp, i32, i32, vp, vp, vp]
     for name in EXPORTS:
@@ -234,10 +234,11 @@ def ep_counters(h: int, S: int, E: int) -> np.ndarray:
 
 
 def ep_ht_dispatch(h: int, x, topk_idx, dst_row, T: int, src_rank: int, ring, recv, recv_rows: int,
-                   stream=None) -> None:
+                   stream=None, payload: int = EP_BF16, recv_scale=None) -> None:
     _check("ep_ht_dispatch", load_library().ep_ht_dispatch(h, _ptr(x), _ptr(topk_idx), _ptr(dst_row), T, src_rank,
-                                                           _ptr(ring), ring.numel() * ring.element_size(),
-                                                           _ptr(recv), recv_rows, _stream(stream)))
+                                                           payload, _ptr(ring), ring.numel() * ring.element_size(),
+                                                           _ptr(recv), _ptr(recv_scale), recv_rows,
+                                                           _stream(stream)))
 
 
 def ep_fifo_stress(h: int, pushers: int, cmds_per_pusher: int, lat_sum, lat_max, stream=None) -> None:

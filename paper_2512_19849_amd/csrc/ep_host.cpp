@@ -684,7 +684,9 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
         const uint64_t len = (uint64_t)(w1 & 0xFFFFFFu) << 4, dof = (uint64_t)w3 << 4;
         // the slot must be one of this channel's own, and the length what its rows need
         const uint64_t first = ((uint64_t)slice * c.num_ranks + dr) * c.ht_ring_slots * h->ring_slot_bytes;
-        if (rows > (uint32_t)kChunkRows || len != 128u + (uint64_t)rows * 2u * c.hidden || dof < first ||
+        const uint64_t rb8 = ((uint64_t)c.hidden + (uint64_t)c.hidden / 32u + 15u) / 16u * 16u;  // an FP8 row
+        if (rows > (uint32_t)kChunkRows ||
+            (len != 128u + (uint64_t)rows * 2u * c.hidden && len != 128u + (uint64_t)rows * rb8) || dof < first ||
             dof >= first + (uint64_t)c.ht_ring_slots * h->ring_slot_bytes || (dof - first) % h->ring_slot_bytes ||
             dof + len > h->ring_total_bytes) {
           reject(h, P);
@@ -1408,13 +1410,15 @@ int ep_ring_counters(ep_handle *h, const int32_t **ring_tail, const int32_t **ri
 }
 
 int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const int32_t *d_dst_row, int32_t T,
-                   int32_t src_rank, void *d_ring, int64_t ring_bytes, void *d_recv, int64_t recv_rows,
-                   void *stream) {
+                   int32_t src_rank, int32_t payload, void *d_ring, int64_t ring_bytes, void *d_recv,
+                   float *d_recv_scale, int64_t recv_rows, void *stream) {
   if (!h) return EP_EINVAL;
   if (h->host_only || h->cfg.ht_slices <= 0) return EP_ESTATE;
   const ep_config &c = h->cfg;
   if (T < 0 || T > c.max_tokens || src_rank < 0 || src_rank >= c.num_src) return EP_EINVAL;
   if (recv_rows < 0 || recv_rows > c.heap_rows) return EP_EINVAL;
+  if (payload != EP_BF16 && payload != EP_FP8_E4M3) return EP_EINVAL;
+  if ((payload == EP_FP8_E4M3) != (d_recv_scale != nullptr)) return EP_EINVAL;
   if (!d_ring || ring_bytes < 0 || (uint64_t)ring_bytes < h->ring_total_bytes) return EP_EINVAL;
   if (T > 0 && (!d_x || !d_topk_idx || !d_dst_row || !d_recv)) return EP_EINVAL;
   if (((uintptr_t)d_x | (uintptr_t)d_recv | (uintptr_t)d_ring) & 15) return EP_EINVAL;
@@ -1426,7 +1430,10 @@ int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, con
   a.dst_row = d_dst_row;
   a.ring_buf = d_ring;
   a.recv = d_recv;
+  a.recv_scale = d_recv_scale;
   a.recv_rows = recv_rows;
+  a.payload = payload;
+  a.row_bytes = row_bytes_of(c.hidden, payload);
   a.T = T;
   a.K = c.top_k;
   a.H = c.hidden;

@@ -133,10 +133,12 @@ struct HtRingArgs {
   const int32_t *idx;      // [T,K]
   const int32_t *dst_row;  // [T,K]
   void *ring_buf;          // [slices][R][W] slots of slot_bytes
-  void *recv;              // bf16 [recv_rows,H]
+  void *recv;              // bf16 [recv_rows,H], or E4M3 codes u8 [recv_rows,H]
+  float *recv_scale;       // FP8: [recv_rows, H/128]
   long long recv_rows;
-  int32_t T, K, H, E_loc, R, src, slices, slice_len, W;
-  unsigned slot_bytes;
+  int32_t T, K, H, E_loc, R, src, slices, slice_len, W, payload;
+  unsigned slot_bytes;     // stride of a slot (header + 32 bf16 rows, whatever the payload)
+  unsigned row_bytes;      // bytes of one row in a slot: 2H, or H codes + H/32 scale bytes padded to 16
   const int32_t *tail, *head;                       // pinned host [slices*R] of this source, written by the proxy
   unsigned *seq_fwd, *seq_rev, *cum_fwd, *cum_rev;  // device [slices*R] of this source
   unsigned *waves_done;

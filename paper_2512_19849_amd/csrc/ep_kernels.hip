@@ -528,6 +528,35 @@ EP_DEV unsigned cvt2_e4m3(float x, float y, unsigned old) {
 // A lane owns 16 consecutive channels (two 16-byte loads, one 16-byte store of
 // codes); 8 adjacent lanes own one 128-channel block and share its amax through
 // three xor-shuffles.  scale = amax/448 and inv = 448/amax are IEEE divisions.
+// Every lane of the wave must call this (lanes past the row's end with zeros).
+EP_DEV void quant16(const u32x4 &lo, const u32x4 &hi, u32x4 &q, float &scale_out) {
+  float f[16];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    f[2 * j] = bf16_lo(lo[j]);
+    f[2 * j + 1] = bf16_hi(lo[j]);
+    f[8 + 2 * j] = bf16_lo(hi[j]);
+    f[8 + 2 * j + 1] = bf16_hi(hi[j]);
+  }
+  float amax = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) amax = fmaxf(amax, fabsf(f[j]));
+  amax = fmaxf(amax, __shfl_xor(amax, 1));
+  amax = fmaxf(amax, __shfl_xor(amax, 2));
+  amax = fmaxf(amax, __shfl_xor(amax, 4));
+  float scale = 1.0f, inv = 1.0f;
+  if (amax >= 0x1p-100f) {
+    scale = amax / 448.0f;
+    inv = 448.0f / amax;
+  }
+  scale_out = scale;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    unsigned d = cvt2_e4m3<false>(f[4 * j] * inv, f[4 * j + 1] * inv, 0u);
+    q[j] = cvt2_e4m3<true>(f[4 * j + 2] * inv, f[4 * j + 3] * inv, d);
+  }
+}
+
 template <int VPL>
 __global__ void dispatch_fp8_kernel(DispatchArgs a) {
   const int wave = threadIdx.x >> 6, lane = lane_id();
@@ -556,33 +585,7 @@ __global__ void dispatch_fp8_kernel(DispatchArgs a) {
         hi[i] = u32x4{0, 0, 0, 0};
       }
 #pragma unroll
-    for (int i = 0; i < VPL; ++i) {
-      float f[16];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f[2 * j] = bf16_lo(lo[i][j]);
-        f[2 * j + 1] = bf16_hi(lo[i][j]);
-        f[8 + 2 * j] = bf16_lo(hi[i][j]);
-        f[8 + 2 * j + 1] = bf16_hi(hi[i][j]);
-      }
-      float amax = 0.0f;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) amax = fmaxf(amax, fabsf(f[j]));
-      amax = fmaxf(amax, __shfl_xor(amax, 1));
-      amax = fmaxf(amax, __shfl_xor(amax, 2));
-      amax = fmaxf(amax, __shfl_xor(amax, 4));
-      float scale = 1.0f, inv = 1.0f;
-      if (amax >= 0x1p-100f) {
-        scale = amax / 448.0f;
-        inv = 448.0f / amax;
-      }
-      sc[i] = scale;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        unsigned d = cvt2_e4m3<false>(f[4 * j] * inv, f[4 * j + 1] * inv, 0u);
-        q[i][j] = cvt2_e4m3<true>(f[4 * j + 2] * inv, f[4 * j + 3] * inv, d);
-      }
-    }
+    for (int i = 0; i < VPL; ++i) quant16(lo[i], hi[i], q[i], sc[i]);
     unsigned long long mm = vmask;
     while (mm) {
       const int k = __builtin_ctzll(mm);
@@ -1091,7 +1094,7 @@ EP_DEV void ht_count_stored(const HtRingArgs &a, HtShared &sh, int c, bool mine,
   HT_ST(&sh.done[r * a.W + w], 0);
   const int chan = c * a.R + r;
   const unsigned seq = sh.seqb[r] + 2u * (unsigned)n, fifo = (unsigned)chan % a.fifo.channels;
-  const unsigned len = (unsigned)kHtHeader + (unsigned)sz * 2u * (unsigned)a.H;
+  const unsigned len = (unsigned)kHtHeader + (unsigned)sz * a.row_bytes;
   const unsigned w0 = cmd_w0(EP_OP_RING, a.src, (unsigned)r, (unsigned)c);
   ring_push(a.fifo, fifo, w0, ((unsigned)EP_RING_WRITE << 30) | ((unsigned)(sz - 1) << 24) | (len >> 4), seq,
             (unsigned)((((size_t)chan * a.W + w) * a.slot_bytes) >> 4));
@@ -1110,7 +1113,7 @@ EP_DEV bool ht_send_entry(const HtRingArgs &a, HtShared &sh, int c, int t, int k
   if (!ht_valid(a, e, row)) return true;
   if (HT_LD(&sh.abort)) return false;
   const int nvec = a.H >> 3;
-  const unsigned rb = 2u * (unsigned)a.H;
+  const unsigned rb = a.row_bytes;
   const int r = e / a.E_loc, chan = c * a.R + r;
   // positions are handed out in arrival order
   int p = 0;
@@ -1129,9 +1132,30 @@ EP_DEV bool ht_send_entry(const HtRingArgs &a, HtShared &sh, int c, int t, int k
     if (!ht_wait_head(a, sh, chan, r, 32u * (unsigned)(n - a.W + 1), lane)) return false;
   }
   char *slot = (char *)a.ring_buf + ((size_t)chan * a.W + w) * a.slot_bytes;
-  u32x4 regs[8];  // cached loads: the token's row comes from HBM once and from a cache for its other k
-  ht_copy_row<false, true, 8>(regs, (u32x4 *)(slot + kHtHeader + (size_t)slot_row * rb),
-                              (const u32x4 *)((const char *)a.x + (size_t)t * rb), nvec, lane);
+  char *dst = slot + kHtHeader + (size_t)slot_row * rb;
+  const u32x4 *xrow = (const u32x4 *)((const char *)a.x + (size_t)t * 2u * (unsigned)a.H);
+  if (a.payload == EP_BF16) {
+    u32x4 regs[8];  // cached loads: the token's row comes from HBM once and from a cache for its other k
+    ht_copy_row<false, true, 8>(regs, (u32x4 *)dst, xrow, nvec, lane);
+  } else {
+    // FP8 message: the row's E4M3 codes, then one fp32 scale per 128 channels (Section 2.1: the ~7 KB token)
+    const int npair = a.H >> 4;
+    for (int p0 = 0; p0 < npair; p0 += 64) {
+      const int p = p0 + lane;
+      u32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0}, q;
+      float sc;
+      if (p < npair) {
+        lo = xrow[2 * p];
+        hi = xrow[2 * p + 1];
+      }
+      quant16(lo, hi, q, sc);
+      if (p < npair) {
+        store_payload((u32x4 *)dst + p, q);
+        if ((lane & 7) == 0)
+          __hip_atomic_store((float *)(dst + a.H) + (p >> 3), sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+    }
+  }
   if (lane == 0) __hip_atomic_store((int *)slot + slot_row, row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   if (lane == j) {
     pd.mine = true;
@@ -1182,8 +1206,9 @@ EP_DEV void ht_sender(const HtRingArgs &a, HtShared &sh, int c, int t0, int t1) 
 
 EP_DEV void ht_receiver(const HtRingArgs &a, HtShared &sh, int c) {
   const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6, nwaves = blockDim.x >> 6;
-  const int nvec = a.H >> 3;
-  const unsigned rb = 2u * (unsigned)a.H;
+  const bool fp8 = a.payload != EP_BF16;
+  const int nvec = fp8 ? a.H >> 4 : a.H >> 3;  // 16-byte vectors of payload per row
+  const unsigned rb = a.row_bytes;
   unsigned long long last = wall_clock64();
   for (;;) {
     // which chunks have been announced since the last sweep (at most W per channel)
@@ -1212,16 +1237,35 @@ EP_DEV void ht_receiver(const HtRingArgs &a, HtShared &sh, int c) {
         }
         const int sz = min(kChunkRows, sh.total[r] - (n << 5));
         const char *slot = (const char *)a.ring_buf + ((size_t)(c * a.R + r) * a.W + n % a.W) * a.slot_bytes;
-        for (int j = 0; j < sz; ++j, ++q) {
-          if (q % nwaves != wave) continue;
-          const int row = __builtin_nontemporal_load((const int *)slot + j);
-          if (row < 0 || row >= a.recv_rows) {
-            dev_set_error(a.fifo.error, EP_EBOUNDS);
-            continue;
+        // this wave's rows of the chunk: j = first, first + nwaves, ... (rows are dealt round-robin over all chunks)
+        const int first = (wave - q % nwaves + nwaves) % nwaves;
+        q += sz;
+        if (first >= sz) continue;
+        // one load brings the destination rows of the whole chunk; the rows are then moved two at a
+        // time so that the loads of both are in flight together
+        const int hdr = lane < sz ? __builtin_nontemporal_load((const int *)slot + lane) : -1;
+        const size_t out_stride = fp8 ? (size_t)a.H : (size_t)rb;
+        for (int j = first; j < sz; j += 2 * nwaves) {
+          const int j2 = j + nwaves;
+          const int rowA = __builtin_amdgcn_readlane(hdr, __builtin_amdgcn_readfirstlane(j));
+          const int rowB = j2 < sz ? __builtin_amdgcn_readlane(hdr, __builtin_amdgcn_readfirstlane(j2)) : -1;
+          const bool okA = rowA >= 0 && rowA < a.recv_rows, okB = rowB >= 0 && rowB < a.recv_rows;
+          if (!okA || (j2 < sz && !okB)) dev_set_error(a.fifo.error, EP_EBOUNDS);
+          const char *srcA = slot + kHtHeader + (size_t)j * rb, *srcB = slot + kHtHeader + (size_t)j2 * rb;
+          u32x4 *dstA = (u32x4 *)((char *)a.recv + (size_t)(okA ? rowA : 0) * out_stride);
+          u32x4 *dstB = (u32x4 *)((char *)a.recv + (size_t)(okB ? rowB : 0) * out_stride);
+          for (int v0 = lane; v0 < nvec; v0 += 64 * 8) {
+            u32x4 ra[8], rb2[8];
+            if (okA) ht_load_piece<true, 8>(ra, (const u32x4 *)srcA, v0, nvec);
+            if (okB) ht_load_piece<true, 8>(rb2, (const u32x4 *)srcB, v0, nvec);
+            if (okA) ht_store_piece<false, 8>(ra, dstA, v0, nvec);
+            if (okB) ht_store_piece<false, 8>(rb2, dstB, v0, nvec);
           }
-          u32x4 regs[8];
-          ht_copy_row<true, false, 8>(regs, (u32x4 *)((char *)a.recv + (size_t)row * rb),
-                                   (const u32x4 *)(slot + kHtHeader + (size_t)j * rb), nvec, lane);
+          if (fp8)  // the scales behind the codes go to their own array
+            for (int b = lane; b < (a.H >> 7); b += 64) {
+              if (okA) a.recv_scale[(size_t)rowA * (a.H >> 7) + b] = __builtin_nontemporal_load((const float *)(srcA + a.H) + b);
+              if (okB) a.recv_scale[(size_t)rowB * (a.H >> 7) + b] = __builtin_nontemporal_load((const float *)(srcB + a.H) + b);
+            }
         }
       }
     }

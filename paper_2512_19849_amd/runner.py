@@ -105,8 +105,10 @@ class EPRunner:
         return self.ht_slices * self.R * self.ht_ring_slots * (128 + 32 * 2 * self.H)
 
     def ht_dispatch(self, x: torch.Tensor, topk_idx_s: torch.Tensor, lay: LayoutOut, ring: torch.Tensor,
-                    recv: torch.Tensor, src: int = 0) -> None:
-        ep.ep_ht_dispatch(self.h, x, topk_idx_s, lay.dst_row[src], x.shape[0], src, ring, recv, recv.shape[0])
+                    recv: torch.Tensor, src: int = 0, recv_scale: Optional[torch.Tensor] = None) -> None:
+        payload = ep.EP_BF16 if recv_scale is None else ep.EP_FP8_E4M3
+        ep.ep_ht_dispatch(self.h, x, topk_idx_s, lay.dst_row[src], x.shape[0], src, ring, recv, recv.shape[0],
+                          payload=payload, recv_scale=recv_scale)
 
     def recv_wait(self, counts_out: Optional[torch.Tensor] = None, src: int = 0, rank_filter: int = -1) -> None:
         ep.ep_recv_wait(self.h, src, rank_filter, counts_out)

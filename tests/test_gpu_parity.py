@@ -982,6 +982,56 @@ def test_ht_ring_dispatch(epmod, oracle, cid, T, mask, slices, W, window, thread
         assert np.array_equal(tail[0], 2 * per_channel) and np.array_equal(head[0], 2 * per_channel)
 
 
+@pytest.mark.parametrize("cid,T,mask,slices,W,window", [(3, None, 0.0, 4, 2, 0), (3, 50, 0.3, 3, 1, 4),
+                                                        (5, 700, 0.0, 8, 2, 8), (4, 300, 0.1, 2, 1, 0),
+                                                        ("h128", 90, 0.0, 3, 2, 0)])
+def test_ht_ring_dispatch_fp8(epmod, oracle, cid, T, mask, slices, W, window):
+    """FP8 tokens through the rings: the sender quantises, a slot row is codes + scales, the receiver splits
+    it into the two receive arrays.  Codes and scales must equal the oracle's bit for bit; the messages carry
+    the FP8 row length."""
+    if cid == "h128":                                          # one block per row: the row is padded to 16 bytes
+        cfg = g.EPConfig("h128", T=T, H=128, E=8, K=2, R=4, S=1)
+        rng = np.random.default_rng(3)
+        idx = np.stack([rng.permutation(8)[:2] for _ in range(T)]).astype(np.int32)[None]
+    else:
+        cfg = g.config(cid, S=1)
+        idx, _ = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=31)
+    T = idx.shape[1]
+    rows = int((idx >= 0).sum()) + 2
+    from paper_2512_19849_amd.runner import bits_to_bf16
+    flags = epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    nch = -(-oracle.ring_channel_rows(idx[0], cfg.E_loc, cfg.R, slices) // 32)
+    with _runner(epmod, cfg, T, flags=flags, heap_rows=rows, ht_slices=slices, ht_ring_slots=W,
+                 reorder_window=window, reorder_seed=6) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+        rq = torch.empty((rows, cfg.H), dtype=torch.uint8, device="cuda")
+        rs = torch.empty((rows, cfg.H // 128), dtype=torch.float32, device="cuda")
+        want_cmds = None
+        for it in range(2):
+            x = g.activations(cfg, it, T=T)
+            rq.fill_(0xA5)
+            rs.fill_(-1.0)
+            r.ht_dispatch(bits_to_bf16(x), d_idx[0], lay, ring, rq, recv_scale=rs)
+            r.wait()
+            torch.cuda.synchronize()
+            wq, ws, _ = oracle.dispatch_fp8(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+            assert np.array_equal(rs.cpu().numpy().view(np.uint32), ws.view(np.uint32)), "scales differ"
+            assert np.array_equal(rq.cpu().numpy(), wq), "codes differ"
+            exp = oracle.expected_ring_cmds(idx[0], 0, cfg.E_loc, cfg.R, cfg.H, slices, W, 2 * nch * it, nch * it,
+                                            payload="fp8")
+            want_cmds = exp if want_cmds is None else want_cmds + exp
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        assert oracle.ring_cmd_multiset(epmod.ep_cmd_log(r.h)) == want_cmds
+        oracle.check_ring_trace(epmod.ep_event_log(r.h), W)
+        assert st["write_bytes"] == 2 * (128 * int(nch.sum()) + (rows - 2) * oracle.row_bytes(cfg.H, "fp8"))
+
+
 def test_ht_ring_dispatch_of_several_sources(epmod, oracle):
     """Config 2's 32 routing tables: sources 0, 7 and 31 each send their tokens through their own set of
     channels (counters, sequence numbers and proxy state are per source) into the one receive buffer."""
@@ -1073,6 +1123,11 @@ def test_ht_ring_dispatch_argument_errors(epmod):
                                                   recv.shape[0])) == epmod.EP_EINVAL      # source 1 of 1
         assert rc_of(lambda: epmod.ep_ht_dispatch(r.h, x, idx[0], lay.dst_row[0], cfg.T + 1, 0, ring, recv,
                                                   recv.shape[0])) == epmod.EP_EINVAL      # beyond max_tokens
+        sc = torch.zeros((recv.shape[0], cfg.H // 128), dtype=torch.float32, device="cuda")
+        assert rc_of(lambda: epmod.ep_ht_dispatch(r.h, x, idx[0], lay.dst_row[0], cfg.T, 0, ring, recv, recv.shape[0],
+                                                  payload=epmod.EP_FP8_E4M3)) == epmod.EP_EINVAL   # FP8 needs the scales
+        assert rc_of(lambda: epmod.ep_ht_dispatch(r.h, x, idx[0], lay.dst_row[0], cfg.T, 0, ring, recv, recv.shape[0],
+                                                  recv_scale=sc)) == epmod.EP_EINVAL                # bf16 must not have them
         # T = 0: nothing travels, the drains still do
         epmod.ep_ht_dispatch(r.h, x, idx[0], lay.dst_row[0], 0, 0, ring, recv, recv.shape[0])
         r.wait()
