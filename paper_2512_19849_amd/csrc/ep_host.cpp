@@ -95,8 +95,10 @@ struct alignas(64) ProxyThread {
   std::vector<WireEvent> window;            // in-flight immediates (reordering hook)
   // proxy-performed peer writes (registered heaps): descriptors of the batch being filled, and the
   // batches in flight with the arrival notices they will release when their copy kernel is done
-  static constexpr int kBatchSlots = 32;
+  static constexpr int kBatchSlots = 8;
   hipEvent_t events[kBatchSlots] = {};
+  CopyDesc *descs = nullptr;    // pinned host [kBatchSlots][kCopyBatchMax]
+  CopyDesc *d_descs = nullptr;  // the same memory as the device sees it
   CopyBatchArgs cur{};
   struct Batch {
     int slot;
@@ -393,6 +395,8 @@ void fail_hip(ep_handle *h) {
 // behind it.  Its notices stay with the batch until the event has fired.
 void launch_batch(ep_handle *h, ProxyThread &P) {
   if (P.cur.n == 0) return;
+  P.cur.descs = P.d_descs + (size_t)P.cur_slot * kCopyBatchMax;
+  P.cur.host_descs = P.descs + (size_t)P.cur_slot * kCopyBatchMax;
   {
     std::lock_guard<std::mutex> g(h->copy_mu);  // launch and event stay adjacent in the shared stream
     if (launch_copy_batch(P.cur, h->copy_stream) != 0 ||
@@ -430,7 +434,8 @@ void queue_copy(ep_handle *h, ProxyThread &P, const char *sbase, char *dbase, ui
   while (P.cur.n == 0 && (int)P.inflight.size() >= ProxyThread::kBatchSlots - 1) reap_batches(h, P, kReapOne);
   P.cur.src_base = sbase;
   P.cur.dst_base = dbase;
-  P.cur.d[P.cur.n] = CopyBatchArgs::Desc{(unsigned)(so >> 4), (unsigned)(dof >> 4), (unsigned)(len >> 4)};
+  P.descs[(size_t)P.cur_slot * kCopyBatchMax + P.cur.n] =
+      CopyDesc{(unsigned)(so >> 4), (unsigned)(dof >> 4), (unsigned)(len >> 4)};
   if (notice) P.cur_notices.push_back(*notice);
   if ((unsigned)(len >> 4) > P.cur.max_len16) P.cur.max_len16 = (unsigned)(len >> 4);
   bump(P.copied_bytes, len);
@@ -812,9 +817,11 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
       close_due_open(h, P);
       if (!P.open.empty()) any = true;  // keep sweeping: the open messages have a deadline
     }
-    // what this sweep collected goes out as one batch of peer writes; finished batches release
-    // their arrival notices
-    if (P.cur.n) launch_batch(h, P);
+    // What has been collected goes out as one batch of peer writes - at once when nothing new came in,
+    // else when it is worth a launch of its own (launches on the shared stream run one after the other,
+    // ~10 us apart: during a burst few large batches beat many small ones); finished batches release
+    // their arrival notices.
+    if (P.cur.n && (!any || P.cur.n >= 2048)) launch_batch(h, P);
     if (!P.inflight.empty()) {
       reap_batches(h, P, kReapReady);
       any = true;
@@ -1080,6 +1087,7 @@ int ep_proxy_stop(ep_handle *h) {
     if (!P.gpu_ready) continue;
     for (hipEvent_t &e : P.events)
       if (e) (void)hipEventDestroy(e);
+    if (P.descs) (void)hipHostFree(P.descs);
   }
   if (h->copy_stream) (void)hipStreamDestroy(h->copy_stream);
   free_all(h);
@@ -1112,6 +1120,13 @@ int ep_register_heaps(ep_handle *h, const void *d_src_base, int64_t src_bytes, v
     if (P.gpu_ready) continue;
     for (hipEvent_t &e : P.events)
       if (!HIP_OK(hipEventCreateWithFlags(&e, hipEventDisableTiming))) return EP_EHIP;
+    void *q = nullptr, *dq = nullptr;
+    if (!HIP_OK(hipHostMalloc(&q, sizeof(CopyDesc) * ProxyThread::kBatchSlots * kCopyBatchMax,
+                              hipHostMallocMapped | hipHostMallocCoherent)))
+      return EP_ENOMEM;
+    P.descs = (CopyDesc *)q;
+    if (!HIP_OK(hipHostGetDevicePointer(&dq, q, 0))) return EP_EHIP;
+    P.d_descs = (CopyDesc *)dq;
     P.gpu_ready = true;
   }
   h->src_bytes = (uint64_t)src_bytes;

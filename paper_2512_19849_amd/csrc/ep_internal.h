@@ -113,18 +113,29 @@ struct CombinePartialArgs {
   int *error;
 };
 
-// A batch of peer writes the proxy performs on behalf of the GPU (registered heaps).  The whole
-// batch travels as the kernel's argument block (reads of descriptors left in host memory cost a
-// PCIe round trip per workgroup), hence offsets and lengths in 16-byte units.
-constexpr int kCopyBatchMax = 256;
+// A batch of peer writes the proxy performs on behalf of the GPU (registered heaps).  Descriptors
+// (offsets and lengths in 16-byte units) stay in pinned host memory; a workgroup fetches the 16 it
+// serves with ONE coalesced read (a descriptor read per workgroup cost a PCIe round trip each and
+// made the copy kernels 10x slower).
+constexpr int kCopyBatchMax = 4096, kCopyGroup = 16;
+struct CopyDesc {
+  unsigned src16, dst16, len16;
+};
 struct CopyBatchArgs {
   const char *src_base;
   char *dst_base;
+  const CopyDesc *descs;       // device address of the pinned array
+  const CopyDesc *host_descs;  // the same array as the host sees it
   int n;
   unsigned max_len16;
-  struct Desc {
-    unsigned src16, dst16, len16;
-  } d[kCopyBatchMax];
+};
+// Large copies (chunks) are few per batch and want a workgroup per (copy, piece): their descriptors
+// travel inside the kernel-argument block instead, up to this many per launch.
+constexpr int kCopyArgMax = 256;
+struct CopyArgBatch {
+  const char *src_base;
+  char *dst_base;
+  CopyDesc d[kCopyArgMax];
 };
 
 // Ring-buffer channels of the high-throughput mode: one sender and one receiver workgroup per slice.

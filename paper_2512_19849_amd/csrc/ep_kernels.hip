@@ -990,7 +990,24 @@ int launch_combine_partial(const CombinePartialArgs &a0, void *stream) {
 // ------------------------------------------------- proxy-issued peer writes
 // blockIdx.y = descriptor, blockIdx.x strides over its 16-byte vectors.
 __global__ __launch_bounds__(256) void copy_batch_kernel(const CopyBatchArgs b) {
-  const CopyBatchArgs::Desc d = b.d[blockIdx.y];
+  __shared__ unsigned sd[3 * kCopyGroup];
+  const int g0 = blockIdx.y * kCopyGroup;
+  const int mine = min(kCopyGroup, b.n - g0);
+  if ((int)threadIdx.x < 3 * mine)
+    sd[threadIdx.x] = __hip_atomic_load((const unsigned *)(b.descs + g0) + threadIdx.x, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_SYSTEM);
+  __syncthreads();
+  for (int k = 0; k < mine; ++k) {
+    const unsigned src16 = sd[3 * k], dst16 = sd[3 * k + 1], len16 = sd[3 * k + 2];
+    const u32x4 *s = (const u32x4 *)b.src_base + src16;
+    u32x4 *o = (u32x4 *)b.dst_base + dst16;
+    for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < len16; i += gridDim.x * 256)
+      o[i] = __builtin_nontemporal_load(s + i);
+  }
+}
+
+__global__ __launch_bounds__(256) void copy_large_kernel(const CopyArgBatch b) {
+  const CopyDesc d = b.d[blockIdx.y];
   const u32x4 *s = (const u32x4 *)b.src_base + d.src16;
   u32x4 *o = (u32x4 *)b.dst_base + d.dst16;
   for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < d.len16; i += gridDim.x * 256)
@@ -1002,7 +1019,19 @@ int launch_copy_batch(const CopyBatchArgs &b, void *stream) {
   unsigned gx = (b.max_len16 + 255) / 256;
   if (gx < 1) gx = 1;
   if (gx > 64) gx = 64;  // 64 x 4 KiB per pass and descriptor, grid-stride beyond
-  hipLaunchKernelGGL(copy_batch_kernel, dim3(gx, (unsigned)b.n), dim3(256), 0, (hipStream_t)stream, b);
+  if (b.max_len16 > 2048) {  // copies beyond 32 KiB: a workgroup per (copy, piece), descriptors as arguments
+    CopyArgBatch a;
+    a.src_base = b.src_base;
+    a.dst_base = b.dst_base;
+    for (int first = 0; first < b.n; first += kCopyArgMax) {
+      const int m = b.n - first < kCopyArgMax ? b.n - first : kCopyArgMax;
+      for (int i = 0; i < m; ++i) a.d[i] = b.host_descs[first + i];
+      hipLaunchKernelGGL(copy_large_kernel, dim3(gx, (unsigned)m), dim3(256), 0, (hipStream_t)stream, a);
+    }
+    return (int)hipGetLastError();
+  }
+  hipLaunchKernelGGL(copy_batch_kernel, dim3(gx, (unsigned)((b.n + kCopyGroup - 1) / kCopyGroup)), dim3(256), 0,
+                     (hipStream_t)stream, b);
   return (int)hipGetLastError();
 }
 
