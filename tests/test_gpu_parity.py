@@ -207,6 +207,16 @@ def test_proxy_performs_chunk_writes(epmod, oracle, cid, T, mask, window, mode):
         assert out["stats"]["drains"] == 8
 
 
+def test_proxy_performs_writes_of_another_source_into_one_rank(epmod, oracle):
+    """Config 2's inbound share: source 31's rows for rank 5 only, moved by the proxy (per token out of that
+    source's x; as chunks out of a send heap), with the other ranks' partitions untouched."""
+    cfg = g.config(2)
+    for mode, name in ((epmod.EP_CMD_PER_TOKEN, "per_token"), (epmod.EP_CMD_CHUNK32, "chunk32")):
+        out = _dispatch_case(epmod, oracle, cfg, 64, 0.0, mode, rank_filter=5, src=31, proxy_writes=True,
+                             reorder_window=3)
+        _check_commands(epmod, oracle, cfg, out, name, src=31, rank_filter=5)
+
+
 def test_proxy_writes_follow_new_data_and_atomics_wait_for_them(epmod, oracle):
     """Three dispatches through the same registered heaps with different activations: each receive
     buffer holds that call's rows (nothing stale is forwarded), and count atomics, which do not wait for
