@@ -12,7 +12,7 @@ SRC = [os.path.join(ROOT, "paper_2512_19849_amd", "csrc", "ep_host.cpp"),
        os.path.join(ROOT, "tests", "native", "host_ring_driver.cpp")]
 
 
-def _build_and_run(tmp_path, sanitizer):
+def _build_and_run(tmp_path, sanitizer, *args):
     if not shutil.which("g++") or not os.path.exists("/opt/rocm/include/hip/hip_runtime_api.h"):
         pytest.skip("g++ or the HIP headers are not available")
     exe = str(tmp_path / f"driver_{sanitizer}")
@@ -22,7 +22,7 @@ def _build_and_run(tmp_path, sanitizer):
     subprocess.run(cmd, check=True, capture_output=True, timeout=300)
     env = dict(os.environ, TSAN_OPTIONS="halt_on_error=0 report_signal_unsafe=0",
                ASAN_OPTIONS="detect_leaks=0 protect_shadow_gap=0")
-    return subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    return subprocess.run([exe, *args], capture_output=True, text=True, timeout=300, env=env)
 
 
 def test_ring_and_proxy_are_clean_under_thread_sanitizer(tmp_path):
@@ -30,6 +30,19 @@ def test_ring_and_proxy_are_clean_under_thread_sanitizer(tmp_path):
     assert r.returncode == 0, r.stdout + r.stderr
     assert "ThreadSanitizer" not in r.stderr, r.stderr[-3000:]
     assert r.stdout.count("rc 0") == 3
+
+
+def test_proxy_policies_and_ring_channels_under_thread_sanitizer(tmp_path):
+    r = _build_and_run(tmp_path, "thread", "policies")
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "ThreadSanitizer" not in r.stderr, r.stderr[-3000:]
+    assert r.stdout.count("rc 0") == 3 and r.stdout.count("policies:") == 3
+
+
+def test_proxy_policies_and_ring_channels_under_address_sanitizer(tmp_path):
+    r = _build_and_run(tmp_path, "address,undefined", "policies")
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-3000:]
 
 
 def test_ring_and_proxy_are_clean_under_address_sanitizer(tmp_path):
