@@ -5,7 +5,10 @@ adds the command-stream side of the oracle, which is small enough for plain
 Python: the multiset of transfer commands a dispatch must emit (Section 3.1,
 "Types of TransferCmd"), a replay of a drained command log onto the oracle's
 own receive buffer, and a checker for the receiver-side completion fence of
-the low-latency mode (Section 3.3, "partial completion fence").
+the low-latency mode (Section 3.3, "partial completion fence"), and the checkers
+of the other receiver- and sender-side rules: per-channel sequence order,
+ring-buffer channels with head/tail flow control (Section 3.3, "partial
+ordering"), and pacing (Section 6).
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import
 this module.  It imports nothing from the HIP package.

@@ -937,6 +937,8 @@ def test_limits_round_trip(epmod, oracle, S, T, K, E, R, H):
     (1, None, 0.0, 4, 2, 0, 2), (1, 50, 0.3, 7, 1, 5, 1), (4, 700, 0.0, 16, 2, 16, 4), (5, 1000, 0.1, 8, 3, 0, 4),
     (4, 700, 0.05, 2, 1, 0, 4),       # ~175 rows per channel through a single slot: every chunk waits for a release
     (2, 128, 0.0, 3, 1, 3, 4), (1, 3, 0.0, 8, 2, 0, 2),
+    (4, 2000, 0.0, 2, 2, 0, 4),       # 8000 entries per slice: beyond the sender's order list, token by token
+    (5, 1500, 0.1, 1, 1, 5, 2),       # one slice, one slot
     ("wide", 100, 0.0, 4, 2, 0, 4),   # 64 experts per token over 256 ranks: the widest routing the handle accepts
     ("long", 40, 0.0, 3, 1, 0, 2)])   # rows of 128 KiB: a row is many pieces, a slot 4 MiB
 def test_ht_ring_dispatch(epmod, oracle, cid, T, mask, slices, W, window, threads):
