@@ -526,6 +526,64 @@ def test_round_trip_identity_expert(epmod, oracle):
 
 
 # ------------------------------------------------------------- error paths
+def test_ring_off_step_replays_from_a_hip_graph(epmod, oracle):
+    """layout -> dispatch (ring off) -> combine touch no host state and clear their own scratch, so the three
+    launches can be captured once and replayed: every replay, with new routing and new activations in the
+    same buffers and eager work in between, must give what the eager calls give (= the oracle's result)."""
+    cfg = g.config(1)
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    T, rows = cfg.T, cfg.T * cfg.K
+    with _runner(epmod, cfg, num_proxy_threads=0) as r:
+        d_idx = torch.zeros((1, T, cfg.K), dtype=torch.int32, device="cuda")
+        d_x = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        d_w = torch.zeros((T, cfg.K), dtype=torch.float32, device="cuda")
+        recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+        out = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+
+        def step():
+            lay = r.layout(d_idx)
+            r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_NONE)
+            r.combine(recv, d_w, lay.dst_row[0], out)
+            return lay
+
+        def load(seed):
+            c2 = g.EPConfig(cfg.name, T=cfg.T, H=cfg.H, E=cfg.E, K=cfg.K, R=cfg.R, S=1, seed=cfg.seed + seed)
+            idx, w = g.routing_all(c2)
+            x = g.activations(c2)
+            d_idx.copy_(_dev(idx))
+            d_w.copy_(_dev(w[0]))
+            d_x.copy_(bits_to_bf16(x))
+            return idx, w, x
+
+        load(0)
+        step()                                       # warm-up outside the capture (first-use initialisation)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                lay = step()
+        for seed in (1, 2, 3):
+            idx, w, x = load(seed)
+            recv.fill_(7.0)                          # eager work between the replays
+            graph.replay()
+            torch.cuda.synchronize()
+            want_lay = oracle.layout(idx, cfg.E, cfg.R)
+            got = lay.numpy()
+            for name, v in want_lay.items():
+                assert np.array_equal(got[name], v), (seed, name)
+            wrecv, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+            assert np.array_equal(bf16_to_bits(recv), wrecv), seed
+            wout = oracle.combine(wrecv, w[0], want_lay["dst_row"][0])
+            assert int(oracle.bf16_ulp_distance(bf16_to_bits(out), wout).max()) <= 1, seed
+            # and the eager path on the same inputs
+            out.zero_()
+            step()
+            torch.cuda.synchronize()
+            assert int(oracle.bf16_ulp_distance(bf16_to_bits(out), wout).max()) <= 1
+        assert r.stats()["device_error"] == 0
+
+
 def test_host_side_argument_errors(epmod):
     from paper_2512_19849_amd.runner import EPRunner
     with pytest.raises(epmod.EPError):
