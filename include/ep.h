@@ -101,7 +101,7 @@ typedef struct ep_config {
   int32_t num_channels;      /* FIFO channels C, 1..64 (the paper runs 8)              */
   int32_t ring_entries;      /* slots per channel = the paper's kMaxInflight; power of two >= 2 */
   int32_t num_proxy_threads; /* 0..16 (the paper runs 4); channel c belongs to thread c mod N   */
-  int32_t reorder_window;    /* test hook: receiver sees up to this many immediates out of order; 0 = in order */
+  int32_t reorder_window;    /* test hook: receiver sees up to this many immediates out of order; 0 = in order, <= 16384 */
   int32_t spin_timeout_ms;   /* bound of every GPU-side and host-side wait; 0 = 5000   */
   uint64_t reorder_seed;
   int64_t heap_rows;         /* rows of the registered receive heap; 0 = S * max_tokens * K */

@@ -864,7 +864,9 @@ int validate(const ep_config &c) {
   if (c.num_channels < 1 || c.num_channels > kMaxChannels) return EP_EINVAL;
   if (c.ring_entries < 2 || c.ring_entries > (1 << 20) || !is_pow2((uint32_t)c.ring_entries)) return EP_EINVAL;
   if (c.num_proxy_threads < 0 || c.num_proxy_threads > kMaxThreads) return EP_EINVAL;
-  if (c.reorder_window < 0 || c.reorder_window > 65536) return EP_EINVAL;
+  // sequenced messages carry 16 bits of their number: a message must not be overtaken by 32768 or
+  // more of its own channel, which a window of this size cannot do
+  if (c.reorder_window < 0 || c.reorder_window > 16384) return EP_EINVAL;
   if (c.spin_timeout_ms < 0 || c.spin_timeout_ms > 60000) return EP_EINVAL;
   if (c.heap_rows < 0) return EP_EINVAL;
   if (c.barrier_peers < 0 || c.barrier_peers > 1024) return EP_EINVAL;
