@@ -564,7 +564,11 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       const uint64_t so = (uint64_t)w2 << 4, dof = (uint64_t)(w3 & 0x7FFFFFFFu) << 4;
       char *const dbase = h->dst_base.load(std::memory_order_acquire);
       const char *const sbase = h->src_base.load(std::memory_order_relaxed);
-      const uint64_t slimit = dbase ? h->src_bytes : h->heap_bytes, dlimit = dbase ? h->dst_bytes : h->heap_bytes;
+      // without registered heaps the source side is the larger of the send buffer a source may own
+      // (max_tokens rows, per-token commands) and the receive heap (chunk commands: same offset on both sides)
+      const uint64_t own = (uint64_t)c.max_tokens * 2ull * (uint64_t)c.hidden;
+      const uint64_t slimit = dbase ? h->src_bytes : (own > h->heap_bytes ? own : h->heap_bytes);
+      const uint64_t dlimit = dbase ? h->dst_bytes : h->heap_bytes;
       if ((int)src >= c.num_src || (int)dr >= c.num_ranks || (int)le >= h->E_loc || len == 0 ||
           so + len > slimit || dof + len > dlimit) {
         reject(h, P);

@@ -32,37 +32,53 @@ EP_DEV int lane_id() { return threadIdx.x & 63; }
 // 16-byte command with a single store.  Returns Idx, or ~0 after a timeout.
 EP_DEV unsigned long long ring_push(const RingDev &r, unsigned c, unsigned w0, unsigned w1,
                                     unsigned w2, unsigned w3) {
-  unsigned long long idx =
+  const unsigned long long idx =
       __hip_atomic_fetch_add(&r.tail[c], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned gen = (((unsigned)(idx >> r.log2_entries)) & 1u) ^ 1u;
+  const u32x4 v = {w0 | (gen << 31), w1, w2, w3 | (gen << 31)};
+  u32x4 *slot = (u32x4 *)r.slots + (size_t)c * r.entries + (size_t)(idx & (r.entries - 1));
   unsigned long long head =
       __hip_atomic_load(&r.cached_head[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (idx - head >= r.entries) {
-    __hip_atomic_fetch_add(r.stalls, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // Full: wait for the proxy to pop.  Thousands of lanes can be waiting on one channel, and
-    // each re-read of the head is a PCIe round trip, so only the lane that holds the channel's
-    // refresh lock goes to host memory; everyone else watches the device-side copy it updates.
-    const unsigned long long t0 = wall_clock64();
-    for (;;) {
-      if (__hip_atomic_exchange(&r.refresh_lock[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-        const unsigned long long h =
-            __hip_atomic_load(&r.head[c * kHeadStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        __hip_atomic_fetch_max(&r.cached_head[c], h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&r.refresh_lock[c], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  unsigned long long result = idx, t0 = 0;
+  bool done = false, stalled = false;
+  // Lanes of one wavefront push side by side, and the proxy consumes a channel in Idx order: a lane
+  // whose Idx already fits must publish its command without waiting for a neighbour whose Idx does
+  // not fit yet (that neighbour may be waiting for the very slot this lane has to fill).  So the
+  // store sits INSIDE the wave-wide loop, and the loop ends when every active lane is done.
+  do {
+    if (!done) {
+      if (idx - head < r.entries) {
+        *(volatile __attribute__((address_space(1))) u32x4 *)slot = v;  // one 16-byte store straight to host memory (system scope)
+        done = true;
+      } else {
+        // Full: wait for the proxy to pop.  Thousands of lanes can be waiting on one channel, and
+        // each re-read of the head is a PCIe round trip, so only the lane that holds the channel's
+        // refresh lock goes to host memory; everyone else watches the device-side copy it updates.
+        if (!stalled) {
+          stalled = true;
+          t0 = wall_clock64();
+          __hip_atomic_fetch_add(r.stalls, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (__hip_atomic_exchange(&r.refresh_lock[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+          const unsigned long long h =
+              __hip_atomic_load(&r.head[c * kHeadStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          __hip_atomic_fetch_max(&r.cached_head[c], h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(&r.refresh_lock[c], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        head = __hip_atomic_load(&r.cached_head[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (idx - head >= r.entries) {
+          if (wall_clock64() - t0 > r.timeout_ticks) {
+            dev_set_error(r.error, EP_ETIMEOUT);
+            result = ~0ull;
+            done = true;
+          } else {
+            __builtin_amdgcn_s_sleep(32);
+          }
+        }
       }
-      head = __hip_atomic_load(&r.cached_head[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (idx - head < r.entries) break;
-      if (wall_clock64() - t0 > r.timeout_ticks) {
-        dev_set_error(r.error, EP_ETIMEOUT);
-        return ~0ull;
-      }
-      __builtin_amdgcn_s_sleep(32);
     }
-  }
-  const unsigned gen = (((unsigned)(idx >> r.log2_entries)) & 1u) ^ 1u;
-  u32x4 v = {w0 | (gen << 31), w1, w2, w3 | (gen << 31)};
-  u32x4 *slot = (u32x4 *)r.slots + (size_t)c * r.entries + (size_t)(idx & (r.entries - 1));
-  *(volatile u32x4 *)slot = v;  // one 16-byte store straight to host memory (system scope)
-  return idx;
+  } while (__ballot(!done) != 0ull);
+  return result;
 }
 
 // Check-completion(Idx): has the proxy popped command idx of channel c?

@@ -1226,6 +1226,70 @@ def test_fifo_stress_closed_loop(epmod):
             epmod.ep_fifo_stress(r.h, 1, 1, s, m)
 
 
+def test_seeded_sweep_of_small_shapes_through_every_dispatch_mode(epmod, oracle):
+    """Twenty seeded shapes (ranks, experts, top-k, hidden, tokens, masking, threads, channels, ring sizes,
+    reordering, pacing, packing drawn at random within the documented limits), each sent through every way
+    of dispatching - ring off, per token, chunks, sequenced chunks, ring-buffer channels, and the
+    proxy-performed forms - into one handle; every receive buffer must equal the plain definition."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    rng = np.random.default_rng(20251219)
+    for case in range(20):
+        R = int(rng.choice([1, 2, 4, 8, 16]))
+        E = R * int(rng.choice([1, 2, 3, 8]))
+        K = int(rng.integers(1, min(E, 9) + 1))
+        H = 128 * int(rng.choice([1, 2, 5, 8, 24]))
+        T = int(rng.integers(1, 400))
+        cfg = g.EPConfig(f"sweep{case}", T=T, H=H, E=E, K=K, R=R, S=1, seed=1000 + case)
+        idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32)[None]
+        if rng.random() < 0.5:
+            idx = g.mask_random(idx, float(rng.choice([0.05, 0.5])), seed=case)
+        x = g.activations(cfg)
+        rows = int((idx >= 0).sum()) + 1
+        slices, W = int(rng.integers(1, 9)), int(rng.integers(1, 4))
+        kw = dict(num_proxy_threads=int(rng.integers(1, 5)), num_channels=int(rng.choice([1, 3, 8, 16])),
+                  ring_entries=int(rng.choice([8, 64, 4096])), reorder_window=int(rng.choice([0, 3, 50])),
+                  reorder_seed=case, max_outstanding=int(rng.choice([0, 2, 16])), pack_rows=int(rng.choice([0, 4])),
+                  ht_slices=slices, ht_ring_slots=W, heap_rows=rows)
+        want_lay = oracle.layout(idx, E, R)
+        want, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows, -1, fill=0xBFC0)
+        tag = f"case {case}: R={R} E={E} K={K} H={H} T={T} {kw}"
+        with _runner(epmod, cfg, **kw) as r:
+            d_idx, d_x = _dev(idx), bits_to_bf16(x)
+            lay = r.layout(d_idx)
+            recv = torch.empty((rows, H), dtype=torch.bfloat16, device="cuda")
+            ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+            send = torch.empty((rows, H), dtype=torch.bfloat16, device="cuda")
+
+            def check(what):
+                torch.cuda.synchronize()
+                assert np.array_equal(bf16_to_bits(recv), want), f"{what}; {tag}"
+                st = r.stats()
+                assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0, f"{what}; {tag}"
+
+            for name in ("none", "per_token", "chunk32", "chunk32_ordered"):
+                recv.fill_(-1.5)
+                r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=epmod.CMD_MODES[name])
+                if name != "none":
+                    try:
+                        r.wait()
+                    except epmod.EPError as err:
+                        raise AssertionError(f"{name}: {err}; {tag}")
+                check(name)
+            recv.fill_(-1.5)
+            r.ht_dispatch(d_x, d_idx[0], lay, ring, recv)
+            r.wait()
+            check("ring-buffer channels")
+            for name, src_heap, target, flag in (("per_token", d_x, recv, epmod.EP_CMD_NO_PLACEMENT),
+                                                 ("chunk32", send, send, 0), ("chunk32_ordered", send, send, 0)):
+                recv.fill_(-1.5)
+                r.register_heaps(src_heap, recv)
+                r.dispatch(d_x, d_idx[0], lay, target, cmd_mode=epmod.CMD_MODES[name] | flag)
+                r.wait()
+                check("proxy-performed " + name)
+            r.register_heaps(None, None)
+            assert np.array_equal(lay.numpy()["dst_row"], want_lay["dst_row"]), tag
+
+
 def _cpu_barrier_peer(name, delay, q):
     import time as _t
     import paper_2512_19849_amd as ep_

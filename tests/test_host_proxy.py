@@ -179,7 +179,7 @@ def test_bounds_check_rejects_bad_commands(ep):
         good = ep.ep_host_push(h, 0, _w0(1, 0, 0, 0), 2048 >> 4, 0, (heap - 2048) >> 4)
         bad = [
             (_w0(1, 0, 0, 0), 2048 >> 4, 0, (heap - 2048 + 16) >> 4),     # destination runs past the heap
-            (_w0(1, 0, 0, 0), 2048 >> 4, (heap - 1024) >> 4, 0),          # source runs past the heap
+            (_w0(1, 0, 0, 0), 2048 >> 4, (4096 * 2 * H - 1024) >> 4, 0),  # source runs past a source's max_tokens rows
             (_w0(1, 0, 0, 0), 0, 0, 0),                                   # zero length
             (_w0(1, 1, 0, 0), 2048 >> 4, 0, 0),                           # source rank 1 of 1
             (_w0(1, 0, 4, 0), 2048 >> 4, 0, 0),                           # destination rank 4 of 4
