@@ -1290,6 +1290,151 @@ def test_seeded_sweep_of_small_shapes_through_every_dispatch_mode(epmod, oracle)
             assert np.array_equal(lay.numpy()["dst_row"], want_lay["dst_row"]), tag
 
 
+def test_seeded_sweep_of_sources_payloads_and_the_way_back(epmod, oracle):
+    """Twenty-five seeded shapes with several sources: the layout over all of them, then for a random
+    source and (sometimes) a single destination rank: FP8 dispatch in a random command mode, FP8 through
+    the ring-buffer channels, the GPU-side wait for the counters, and combine over random expert outputs -
+    each against the oracle."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    rng = np.random.default_rng(77)
+    for case in range(25):
+        R = int(rng.choice([1, 2, 4, 8, 32]))
+        E = R * int(rng.choice([1, 2, 4]))
+        K = int(rng.integers(1, min(E, 8) + 1))
+        H = 128 * int(rng.choice([1, 3, 8, 16, 56]))
+        S = int(rng.choice([1, 2, 3]))
+        T = int(rng.integers(1, 300))
+        cfg = g.EPConfig(f"sweepb{case}", T=T, H=H, E=E, K=K, R=R, S=S, seed=5000 + case)
+        idx = np.stack([np.stack([rng.permutation(E)[:K] for _ in range(T)]) for _ in range(S)]).astype(np.int32)
+        if rng.random() < 0.5:
+            idx = g.mask_random(idx, float(rng.choice([0.1, 0.6])), seed=case)
+        w = rng.standard_normal((T, K)).astype(np.float32)
+        s = int(rng.integers(S))
+        filt = int(rng.integers(R)) if rng.random() < 0.4 else -1
+        x = g.activations(cfg, s)
+        rows = int((idx >= 0).sum()) + 1
+        mode = str(rng.choice(["none", "per_token", "chunk32", "chunk32_ordered"]))
+        slices, W = int(rng.integers(1, 6)), int(rng.integers(1, 4))
+        kw = dict(num_proxy_threads=int(rng.integers(1, 5)), num_channels=int(rng.choice([2, 8, 32])),
+                  ring_entries=int(rng.choice([16, 256, 4096])), reorder_window=int(rng.choice([0, 5, 40])),
+                  reorder_seed=case, ht_slices=slices, ht_ring_slots=W, heap_rows=rows)
+        tag = f"case {case}: R={R} E={E} K={K} H={H} S={S} T={T} src={s} filter={filt} mode={mode} {kw}"
+        want_lay = oracle.layout(idx, E, R)
+        wq, ws, _ = oracle.dispatch_fp8(x, idx[s], want_lay["dst_row"][s], cfg.E_loc, rows, filt)
+        y = g.activations(cfg, s, tid=g.TID_Y, T=rows)
+        wout = oracle.combine(y, w, want_lay["dst_row"][s])
+        with _runner(epmod, cfg, **kw) as r:
+            d_idx, d_x = _dev(idx), bits_to_bf16(x)
+            lay = r.layout(d_idx)
+            torch.cuda.synchronize()
+            got = lay.numpy()
+            for name, v in want_lay.items():
+                assert np.array_equal(got[name], v), f"layout {name}; {tag}"
+            rq = torch.full((rows, H), 0xA5, dtype=torch.uint8, device="cuda")
+            rs = torch.full((rows, H // 128), -1.0, dtype=torch.float32, device="cuda")
+            counts = torch.full((E,), -7, dtype=torch.int32, device="cuda")
+            try:
+                r.dispatch(d_x, d_idx[s], lay, rq, rs, src=s, rank_filter=filt, payload=epmod.EP_FP8_E4M3,
+                           cmd_mode=epmod.CMD_MODES[mode])
+                if mode in ("per_token", "chunk32"):
+                    r.recv_wait(counts, src=s, rank_filter=filt)
+                if mode != "none":
+                    r.wait()
+                torch.cuda.synchronize()
+            except epmod.EPError as err:
+                raise AssertionError(f"{err}; {tag}")
+            assert np.array_equal(rs.cpu().numpy().view(np.uint32), ws.view(np.uint32)), f"scales; {tag}"
+            assert np.array_equal(rq.cpu().numpy(), wq), f"codes; {tag}"
+            if mode in ("per_token", "chunk32"):
+                sel = np.arange(E) // cfg.E_loc == filt if filt >= 0 else np.ones(E, bool)
+                wc = np.where(sel, want_lay["count"][s], -1)
+                assert np.array_equal(counts.cpu().numpy(), wc), f"counts; {tag}"
+            # the same source through the ring-buffer channels (all ranks)
+            wq2, ws2, _ = oracle.dispatch_fp8(x, idx[s], want_lay["dst_row"][s], cfg.E_loc, rows)
+            rq.fill_(0xA5)
+            rs.fill_(-1.0)
+            ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+            try:
+                r.ht_dispatch(d_x, d_idx[s], lay, ring, rq, src=s, recv_scale=rs)
+                r.wait()
+                torch.cuda.synchronize()
+            except epmod.EPError as err:
+                raise AssertionError(f"rings: {err}; {tag}")
+            assert np.array_equal(rs.cpu().numpy().view(np.uint32), ws2.view(np.uint32)), f"ring scales; {tag}"
+            assert np.array_equal(rq.cpu().numpy(), wq2), f"ring codes; {tag}"
+            out = torch.full((T, H), 7.0, dtype=torch.bfloat16, device="cuda")
+            r.combine(bits_to_bf16(y), _dev(w), lay.dst_row[s], out)
+            torch.cuda.synchronize()
+            assert int(oracle.bf16_ulp_distance(bf16_to_bits(out), wout).max()) <= 1, f"combine; {tag}"
+            st = r.stats()
+            assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0, tag
+
+
+def test_seeded_sweep_of_the_deduplicating_mode(epmod, oracle):
+    """Twenty seeded shapes of the high-throughput pipeline with random group sizes: dedup, group-level layout
+    and dispatch (per token, chunks or ring-buffer channels), per-expert index list, partial reduce per group
+    and final reduce, each stage against the oracle."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    rng = np.random.default_rng(5)
+    for case in range(20):
+        G = int(rng.choice([1, 2, 4, 8]))
+        NG = int(rng.choice([1, 2, 4]))
+        R = G * NG
+        E = R * int(rng.choice([1, 2, 4]))
+        K = int(rng.integers(1, min(E, 8) + 1))
+        H = 128 * int(rng.choice([1, 2, 8, 56]))
+        T = int(rng.integers(1, 300))
+        cfg = g.EPConfig(f"s3_{case}", T=T, H=H, E=E, K=K, R=R, S=1, seed=9000 + case)
+        idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32)[None]
+        if rng.random() < 0.5:
+            idx = g.mask_random(idx, float(rng.choice([0.1, 0.5])), seed=case)
+        w = rng.standard_normal((1, T, K)).astype(np.float32)
+        x = g.activations(cfg, 0)
+        tag = f"case {case}: G={G} NG={NG} E={E} K={K} H={H} T={T}"
+        wg, wf = oracle.dedup(idx, cfg.E_loc, G)
+        lay = oracle.layout(idx, E, R)
+        lay_g = oracle.layout(wg, NG, NG)
+        rows, rows_g = int((idx >= 0).sum()), int((wg >= 0).sum())
+        if rows == 0:
+            continue
+        windex = oracle.gather_index(lay["dst_row"][0], lay_g["dst_row"][0], wf[0], rows)
+        y = g.activations(cfg, 0, tid=g.TID_Y, T=max(rows, 1))
+        wpartial = oracle.combine_partial(y, w[0], lay["dst_row"][0], wf[0], lay_g["dst_row"][0], rows_g, fill=0x3F80)
+        wout = oracle.combine(wpartial, np.ones_like(w[0]), lay_g["dst_row"][0])
+        wrecv_g, _ = oracle.dispatch_bf16(x, wg[0], lay_g["dst_row"][0], 1, rows_g)
+        mode = str(rng.choice(["per_token", "chunk32", "ring"]))
+        ring_kw = dict(ht_slices=int(rng.integers(1, 5)), ht_ring_slots=int(rng.integers(1, 3)))
+        with EPRunner(R, E, K, H, T, num_proxy_threads=0, spin_timeout_ms=3000) as r, \
+                EPRunner(NG, NG, K, H, T, spin_timeout_ms=3000, reorder_window=int(rng.choice([0, 6])),
+                         heap_rows=max(rows_g, 1), **ring_kw) as rg:
+            d_idx, d_x, d_w = _dev(idx), bits_to_bf16(x), _dev(w[0])
+            gi, fk = torch.empty_like(d_idx), torch.empty_like(d_idx)
+            epmod.ep_dedup(r.h, d_idx, T, G, gi, fk)
+            L = r.layout(d_idx)
+            Lg = rg.layout(gi)
+            recv_g = torch.zeros((max(rows_g,1), H), dtype=torch.bfloat16, device="cuda")
+            if mode == "ring":
+                ring = torch.zeros(rg.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+                rg.ht_dispatch(d_x, gi[0], Lg, ring, recv_g)
+            else:
+                rg.dispatch(d_x, gi[0], Lg, recv_g, cmd_mode=epmod.CMD_MODES[mode])
+            index = torch.full((rows,), -1, dtype=torch.int32, device="cuda")
+            epmod.ep_gather_index(r.h, L.dst_row[0], Lg.dst_row[0], fk[0], T, rows, index)
+            partial = torch.ones((max(rows_g,1), H), dtype=torch.bfloat16, device="cuda")
+            epmod.ep_combine_partial(r.h, bits_to_bf16(y), d_w, L.dst_row[0], fk[0], Lg.dst_row[0], T, y.shape[0],
+                                     rows_g, partial)
+            out = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+            rg.combine(partial, torch.ones_like(d_w), Lg.dst_row[0], out)
+            rg.wait()
+            torch.cuda.synchronize()
+            assert np.array_equal(gi.cpu().numpy(), wg) and np.array_equal(fk.cpu().numpy(), wf), tag
+            assert np.array_equal(bf16_to_bits(recv_g)[:rows_g], wrecv_g), tag
+            assert np.array_equal(index.cpu().numpy(), windex), tag
+            assert np.array_equal(bf16_to_bits(partial)[:rows_g], wpartial[:rows_g]), tag
+            assert np.array_equal(bf16_to_bits(out), wout), tag
+            assert rg.stats()["device_error"] == 0 and r.stats()["device_error"] == 0 and rg.stats()["proxy_error"] == 0, tag
+
+
 def _cpu_barrier_peer(name, delay, q):
     import time as _t
     import paper_2512_19849_amd as ep_
