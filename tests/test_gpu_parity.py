@@ -1435,6 +1435,72 @@ def test_seeded_sweep_of_the_deduplicating_mode(epmod, oracle):
             assert rg.stats()["device_error"] == 0 and r.stats()["device_error"] == 0 and rg.stats()["proxy_error"] == 0, tag
 
 
+def test_seeded_sweep_of_proxy_options_and_dispatch_flags(epmod, oracle):
+    """Fifteen seeded shapes, three dispatches each on one handle, with the proxy's options (threads, channels,
+    ring size down to 8 slots, reordering, pacing, packing with and without hold time, fence at the sender or
+    at the receiver) and the dispatch flags (count Atomics first, Drain, proxy-performed writes) drawn at
+    random: buffer, counters, fence trace and pacing trace must hold in every combination."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    rng = np.random.default_rng(11)
+    for case in range(15):
+        R = int(rng.choice([1, 2, 4, 8, 16]))
+        E = R * int(rng.choice([1, 2, 3, 8]))
+        K = int(rng.integers(1, min(E, 8) + 1))
+        H = 128 * int(rng.choice([1, 2, 5, 8, 24]))
+        T = int(rng.integers(1, 500))
+        cfg = g.EPConfig(f"s4_{case}", T=T, H=H, E=E, K=K, R=R, S=1, seed=3000 + case)
+        idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32)[None]
+        if rng.random() < 0.5:
+            idx = g.mask_random(idx, float(rng.choice([0.05, 0.5])), seed=case)
+        x = g.activations(cfg)
+        rows = int((idx >= 0).sum()) + 1
+        flags = epmod.EP_FLAG_LOG_EVENTS | (epmod.EP_FLAG_SENDER_FENCE if rng.random() < 0.5 else 0)
+        kw = dict(num_proxy_threads=int(rng.integers(1, 5)), num_channels=int(rng.choice([1, 2, 8, 16])),
+                  ring_entries=int(rng.choice([8, 32, 4096])), reorder_window=int(rng.choice([0, 3, 50])),
+                  reorder_seed=case, max_outstanding=int(rng.choice([0, 1, 4])), pack_rows=int(rng.choice([0, 2, 16])),
+                  pack_hold_us=int(rng.choice([0, 30])), heap_rows=rows, flags=flags)
+        want_lay = oracle.layout(idx, E, R)
+        want, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows, -1, fill=0xBFC0)
+        with EPRunner(R, E, K, H, T, spin_timeout_ms=3000, **kw) as r:
+            d_idx, d_x = _dev(idx), bits_to_bf16(x)
+            lay = r.layout(d_idx)
+            recv = torch.empty((rows, H), dtype=torch.bfloat16, device="cuda")
+            send = torch.empty((rows, H), dtype=torch.bfloat16, device="cuda")
+            for rep in range(3):
+                base = str(rng.choice(["per_token", "chunk32"]))
+                cm = epmod.CMD_MODES[base]
+                if rng.random() < 0.4:
+                    cm |= epmod.EP_CMD_ATOMICS_FIRST
+                if rng.random() < 0.4:
+                    cm |= epmod.EP_CMD_DRAIN
+                pw = rng.random() < 0.4
+                tag = (f"case {case}.{rep}: R={R} E={E} K={K} H={H} T={T} mode={base} cm={cm:#x} pw={pw} "
+                       f"flags={flags} {kw}")
+                recv.fill_(-1.5)
+                target = recv
+                if pw:
+                    if base == "per_token":
+                        cm |= epmod.EP_CMD_NO_PLACEMENT
+                        r.register_heaps(d_x, recv)
+                    else:
+                        target = send
+                        r.register_heaps(send, recv)
+                r.dispatch(d_x, d_idx[0], lay, target, cmd_mode=cm)
+                r.wait()
+                torch.cuda.synchronize()
+                if pw:
+                    r.register_heaps(None, None)
+                assert np.array_equal(bf16_to_bits(recv), want), tag
+                st = r.stats()
+                assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0, tag
+                assert np.array_equal(r.counters()[0], want_lay["count"][0]), tag
+            ev = epmod.ep_event_log(r.h)
+            oracle.check_fence_trace(ev, want_lay["count"])
+            oracle.check_pacing_trace(ev, kw["max_outstanding"], cfg.E_loc)
+            if flags & epmod.EP_FLAG_SENDER_FENCE:
+                assert st["atomics_deferred"] == 0, tag
+
+
 def _cpu_barrier_peer(name, delay, q):
     import time as _t
     import paper_2512_19849_amd as ep_
