@@ -1,0 +1,305 @@
+// Dispatch (bf16 / FP8 E4M3) and the emission of transfer commands: HBM-bound row copies with 16-byte vector
+// accesses, one wavefront per token or per slice of a token; no dense contraction, hence no MFMA.
+#include "ep_device.h"
+
+namespace ep {
+
+// ------------------------------------------------- dispatch: command emission
+struct TokenMeta {
+  int e;       // expert of this lane's k (lane < K), -1 otherwise
+  int row;     // destination row
+  bool valid;  // this (t, k) is dispatched by this call
+};
+
+EP_DEV TokenMeta load_meta(const DispatchArgs &a, int t, int lane) {
+  TokenMeta m{-1, -1, false};
+  if (t < a.T && lane < a.K) {
+    m.e = a.idx[(size_t)t * a.K + lane];
+    m.row = a.dst_row[(size_t)t * a.K + lane];
+    if (m.e >= 0) {
+      if (m.e >= a.E || m.row < 0 || m.row >= a.recv_rows)
+        dev_set_error(a.ring.error, EP_EBOUNDS);
+      else if (a.filter < 0 || m.e / a.E_loc == a.filter)
+        m.valid = true;
+    } else if (m.e != -1) {
+      dev_set_error(a.ring.error, EP_EBOUNDS);
+    }
+  }
+  return m;
+}
+
+EP_DEV void push_count_atomic(const DispatchArgs &a, int e, int value) {
+  const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
+  ring_push(a.ring, (unsigned)e % a.ring.channels, cmd_w0(EP_OP_ATOMIC, a.src, dr, le), (unsigned)value, 0u,
+            (unsigned)(a.src * a.E_loc) + le);
+}
+
+// Kernel prologue (workgroup 0, wavefront 0): the count Atomics that no row
+// completion will trigger - experts with count 0, or all of them when the
+// caller wants the atomics ahead of the writes.
+EP_DEV void emit_leading_atomics(const DispatchArgs &a, int lane) {
+  const bool first = (a.cmd_mode & EP_CMD_ATOMICS_FIRST) != 0;
+  for (int e = lane; e < a.E; e += 64) {
+    if (a.filter >= 0 && e / a.E_loc != a.filter) continue;
+    const int c = a.count[e];
+    if (first || c == 0) push_count_atomic(a, e, c);
+  }
+}
+
+// Called by the lanes holding a dispatched (t,k) after the token's rows are
+// stored and acknowledged (write-through, so they are in memory).  LL granularity: one Write per row.
+// Chunk granularity: the lane that completes a run of <= 32 consecutive rows of
+// an expert pushes the Write for the run.  Whoever completes the expert pushes
+// its count Atomic (Section 3.3: the receiver holds it until that many rows
+// arrived).  The scratch counters return to zero by themselves.
+EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
+  const int e = m.e;
+  const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
+  // Everything for one destination expert goes through one FIFO (and therefore one proxy thread):
+  // in-FIFO order is the only order the channel guarantees (Section 3.1, "GPU-side contention").
+  const unsigned ch = (unsigned)e % a.ring.channels;
+  const int c = a.count[e];
+  const int mode = a.cmd_mode & EP_CMD_MODE_MASK;
+  int finished_rows = 0;
+  if (mode == EP_CMD_PER_TOKEN) {
+    const unsigned long long so = (unsigned long long)t * a.row_bytes;
+    const unsigned long long dof = (unsigned long long)m.row * a.row_bytes;
+    ring_push(a.ring, ch, cmd_w0(EP_OP_WRITE, a.src, dr, le), a.row_bytes >> 4, (unsigned)(so >> 4),
+              (unsigned)(dof >> 4));
+    finished_rows = 1;
+  } else {
+    const int slot = m.row - a.base[e];
+    const int j = slot >> 5;
+    if (slot < 0 || j >= a.chunks_per_expert || slot >= c) {
+      dev_set_error(a.ring.error, EP_EBOUNDS);
+      return;
+    }
+    const int csize = min(kChunkRows, c - (j << 5));
+    int *cnt = a.chunk_cnt + (size_t)e * a.chunks_per_expert + j;
+    const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1 == csize) {
+      __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned long long off = (unsigned long long)(a.base[e] + (j << 5)) * a.row_bytes;
+      const unsigned len = (unsigned)csize * a.row_bytes;
+      if (mode == EP_CMD_CHUNK32_ORDERED) {
+        // High-throughput style: the chunk's Write and the Atomic that advances the receiver's tail
+        // take two consecutive sequence numbers of the communication channel (source, destination
+        // rank) and travel through that channel's FIFO; the receiver re-establishes the order.
+        const unsigned seq = __hip_atomic_fetch_add(a.ht_seq + (size_t)a.src * a.R + dr, 2u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned och = dr % a.ring.channels;
+        ring_push(a.ring, och, cmd_w0(EP_OP_ORDERED_WRITE, a.src, dr, le),
+                  ((unsigned)(csize - 1) << 26) | (len >> 4), seq, (unsigned)(off >> 4));
+        ring_push(a.ring, och, cmd_w0(EP_OP_ORDERED_ATOMIC, a.src, dr, 0), (unsigned)csize, seq + 1u,
+                  (unsigned)(a.src * a.R) + dr);
+        return;
+      }
+      ring_push(a.ring, ch, cmd_w0(EP_OP_WRITE, a.src, dr, le), ((unsigned)(csize - 1) << 26) | (len >> 4),
+                (unsigned)(off >> 4), (unsigned)(off >> 4));
+      finished_rows = csize;
+    }
+  }
+  if (finished_rows) {
+    const int done = __hip_atomic_fetch_add(a.expert_done + e, finished_rows, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT) + finished_rows;
+    if (done == c) {
+      __hip_atomic_store(a.expert_done + e, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (!(a.cmd_mode & EP_CMD_ATOMICS_FIRST)) push_count_atomic(a, e, c);
+    }
+  }
+}
+
+EP_DEV void emit_drain(const DispatchArgs &a, int lane) {
+  drain_all_channels(a.ring, a.waves_done, (unsigned)a.src, lane);
+}
+
+// ------------------------------------------------------------ dispatch bf16
+// A token's row is H/8 16-byte vectors.  Wavefront (token, part) reads its
+// slice of the row ONCE into registers (VPL vectors per lane) and stores it to
+// every destination row; destination rows are wave-uniform and come from the
+// lanes that hold the token's (expert, row) pairs.
+template <int VPL>
+__global__ void dispatch_bf16_kernel(DispatchArgs a) {
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int part = wave % a.parts;
+  const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
+  const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
+  const bool ordered = (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_CHUNK32_ORDERED;
+  if (ring_on && !ordered && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
+
+  const TokenMeta m = load_meta(a, t, lane);
+  unsigned long long vmask = __ballot(m.valid);
+  const int nvec = a.H >> 3;
+  const int v0 = part * VPL * 64 + lane;
+  if (vmask && !(a.cmd_mode & EP_CMD_NO_PLACEMENT)) {
+    const u32x4 *src = (const u32x4 *)a.x + (size_t)t * nvec;
+    u32x4 v[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (v0 + i * 64 < nvec) v[i] = __builtin_nontemporal_load(src + v0 + i * 64);
+    unsigned long long mm = vmask;
+    while (mm) {
+      const int k = __builtin_ctzll(mm);
+      mm &= mm - 1;
+      const int row = __builtin_amdgcn_readlane(m.row, k);
+      u32x4 *dst = (u32x4 *)a.recv + (size_t)row * nvec;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+        if (v0 + i * 64 < nvec) store_payload(dst + v0 + i * 64, v[i]);
+    }
+  }
+  if (!ring_on) return;
+  wait_for_own_stores();  // the rows are in memory before a counter or command mentions them
+  if (a.parts > 1) __syncthreads();
+  if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  if (a.cmd_mode & EP_CMD_DRAIN) emit_drain(a, lane);
+}
+
+// ------------------------------------------------------------- dispatch FP8
+template <int VPL>
+__global__ void dispatch_fp8_kernel(DispatchArgs a) {
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int part = wave % a.parts;
+  const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
+  const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
+  const bool ordered = (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_CHUNK32_ORDERED;
+  if (ring_on && !ordered && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
+
+  const TokenMeta m = load_meta(a, t, lane);
+  unsigned long long vmask = __ballot(m.valid);
+  const int npair = a.H >> 4;  // 16-channel groups per row
+  const int nblk = a.H >> 7;   // 128-channel blocks per row
+  const int p0 = part * VPL * 64 + lane;
+  if (vmask) {
+    const u32x4 *src = (const u32x4 *)a.x + (size_t)t * npair * 2;
+    u32x4 lo[VPL], hi[VPL], q[VPL];
+    float sc[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+      if (p0 + i * 64 < npair) {
+        lo[i] = __builtin_nontemporal_load(src + 2 * (p0 + i * 64));
+        hi[i] = __builtin_nontemporal_load(src + 2 * (p0 + i * 64) + 1);
+      } else {
+        lo[i] = u32x4{0, 0, 0, 0};
+        hi[i] = u32x4{0, 0, 0, 0};
+      }
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) quant16(lo[i], hi[i], q[i], sc[i]);
+    unsigned long long mm = vmask;
+    while (mm) {
+      const int k = __builtin_ctzll(mm);
+      mm &= mm - 1;
+      const int row = __builtin_amdgcn_readlane(m.row, k);
+      u32x4 *dq = (u32x4 *)a.recv + (size_t)row * npair;
+      float *ds = a.recv_scale + (size_t)row * nblk;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+        if (p0 + i * 64 < npair) {
+          store_payload(dq + p0 + i * 64, q[i]);
+          if ((lane & 7) == 0)
+            __hip_atomic_store(ds + ((p0 + i * 64) >> 3), sc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+  }
+  if (!ring_on) return;
+  wait_for_own_stores();
+  if (a.parts > 1) __syncthreads();
+  if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  if (a.cmd_mode & EP_CMD_DRAIN) emit_drain(a, lane);
+}
+
+// units = 16-byte vectors (bf16) or 16-channel groups (FP8) per row; returns how many of them one
+// lane carries.  The row then takes ceil(units / (64 * result)) waves, at most 16.
+static int split_for(int units, int T, const int *cands, int ncand) {
+  int best = cands[ncand - 1];
+  for (int i = 0; i < ncand; ++i)
+    if (cands[i] * 256 >= units) {
+      best = cands[i];
+      break;
+    }
+  for (int i = ncand - 1; i >= 0; --i) {
+    if (cands[i] >= best) continue;
+    const long long waves_now = (long long)T * ((units + best * 64 - 1) / (best * 64));
+    if (waves_now >= 4096) break;
+    if ((units + cands[i] * 64 - 1) / (cands[i] * 64) > 16) break;
+    best = cands[i];
+  }
+  while ((units + best * 64 - 1) / (best * 64) > 16) {  // very wide rows: stay within 16 waves per token
+    int next = best;
+    for (int i = 0; i < ncand; ++i)
+      if (cands[i] > best) {
+        next = cands[i];
+        break;
+      }
+    if (next == best) break;
+    best = next;
+  }
+  return best;
+}
+
+int tuned_dispatch_vpl(int H, int T) {
+  static const int c[] = {1, 2, 4, 7, 8, 14, 16};
+  const int forced = env_int("EP_DISPATCH_VPL", 0);
+  for (int v : c)
+    if (v == forced) return v;
+  // About four waves per token stream best (measured in the full path on 7168- and 4096-wide rows:
+  // the command tail of one wave then overlaps the stores of the others); with few tokens the row
+  // is split further until there are about 4096 waves (16 per compute unit).
+  return split_for(H / 8, T, c, 7);
+}
+
+static int tuned_dispatch_fp8_vpl(int H, int T) {
+  static const int c[] = {1, 2, 4};  // more than 4 groups per lane would spill at 128 VGPRs
+  const int forced = env_int("EP_DISPATCH_FP8_VPL", 0);
+  for (int v : c)
+    if (v == forced) return v;
+  return split_for(H / 16, T, c, 3);
+}
+
+template <int VPL>
+static void launch_dispatch_bf16_t(DispatchArgs a, hipStream_t st) {
+  const int nvec = a.H / 8;
+  a.parts = (nvec + VPL * 64 - 1) / (VPL * 64);
+  a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
+  const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
+  hipLaunchKernelGGL(dispatch_bf16_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st, a);
+}
+
+template <int VPL>
+static void launch_dispatch_fp8_t(DispatchArgs a, hipStream_t st) {
+  const int npair = a.H / 16;
+  a.parts = (npair + VPL * 64 - 1) / (VPL * 64);
+  a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
+  const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
+  hipLaunchKernelGGL(dispatch_fp8_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st, a);
+}
+
+int launch_dispatch(const DispatchArgs &a, int payload, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  // T == 0 with the ring on still launches one (idle) workgroup: it owes the zero-count atomics
+  if (a.T <= 0 && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_NONE) return 0;
+  if (payload == EP_BF16) {
+    const int vpl = tuned_dispatch_vpl(a.H, a.T);
+    if ((a.H / 8 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
+    switch (vpl) {
+      case 1: launch_dispatch_bf16_t<1>(a, st); break;
+      case 2: launch_dispatch_bf16_t<2>(a, st); break;
+      case 4: launch_dispatch_bf16_t<4>(a, st); break;
+      case 7: launch_dispatch_bf16_t<7>(a, st); break;
+      case 8: launch_dispatch_bf16_t<8>(a, st); break;
+      case 14: launch_dispatch_bf16_t<14>(a, st); break;
+      default: launch_dispatch_bf16_t<16>(a, st); break;
+    }
+  } else {
+    const int vpl = tuned_dispatch_fp8_vpl(a.H, a.T);
+    if ((a.H / 16 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
+    switch (vpl) {
+      case 1: launch_dispatch_fp8_t<1>(a, st); break;
+      case 2: launch_dispatch_fp8_t<2>(a, st); break;
+      default: launch_dispatch_fp8_t<4>(a, st); break;
+    }
+  }
+  return (int)hipGetLastError();
+}
+
+}  // namespace ep

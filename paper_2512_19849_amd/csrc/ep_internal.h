@@ -164,7 +164,7 @@ struct RecvWaitArgs {
   unsigned long long timeout_ticks;
 };
 
-// Launchers implemented in ep_kernels.hip.  All return a hipError_t as int.
+// Launchers implemented in the .hip files (layout, dispatch, combine, ht_ring, service).  All return a hipError_t as int.
 int launch_layout(const LayoutArgs &a, void *stream);
 int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
 int launch_combine(const CombineArgs &a, void *stream);
