@@ -8,7 +8,8 @@ import subprocess
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SRC = [os.path.join(ROOT, "paper_2512_19849_amd", "csrc", "ep_host.cpp"),
+SRC = [os.path.join(ROOT, "paper_2512_19849_amd", "csrc", "proxy.cpp"),
+       os.path.join(ROOT, "paper_2512_19849_amd", "csrc", "api.cpp"),
        os.path.join(ROOT, "tests", "native", "host_ring_driver.cpp")]
 
 
