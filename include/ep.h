@@ -290,8 +290,9 @@ int ep_counters(ep_handle *h, const int32_t **recv_count, const int32_t **d_recv
  * description of the HT kernel: rings of chunk slots, head and tail values).
  * The T tokens are cut into ht_slices slices of ceil(T/ht_slices) consecutive
  * tokens; a channel is (source, slice, destination rank) and owns a ring of
- * ht_ring_slots slots in d_ring.  One launch runs, per slice, a sender
- * workgroup and a receiver workgroup:
+ * ht_ring_slots slots in d_ring.  One launch runs one workgroup per slice, which
+ * plays both ends of the slice's channels in turns and never waits for the other
+ * end (so a workgroup depends on nothing but the proxy, whatever the grid size):
  *   sender   - copies each valid (token, k) row into the next free row of its
  *              channel's current chunk (slot = chunk number mod W, a 128-byte
  *              header of int32 destination rows, then 32 rows); it may use a slot

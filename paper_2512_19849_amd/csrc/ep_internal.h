@@ -138,7 +138,7 @@ struct CopyArgBatch {
   CopyDesc d[kCopyArgMax];
 };
 
-// Ring-buffer channels of the high-throughput mode: one sender and one receiver workgroup per slice.
+// Ring-buffer channels of the high-throughput mode: one workgroup per slice, sending and receiving in turns.
 struct HtRingArgs {
   const void *x;           // bf16 [T,H]
   const int32_t *idx;      // [T,K]

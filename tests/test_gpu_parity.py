@@ -1000,7 +1000,7 @@ def test_limits_round_trip(epmod, oracle, S, T, K, E, R, H):
     ("wide", 100, 0.0, 4, 2, 0, 4),   # 64 experts per token over 256 ranks: the widest routing the handle accepts
     ("long", 40, 0.0, 3, 1, 0, 2)])   # rows of 128 KiB: a row is many pieces, a slot 4 MiB
 def test_ht_ring_dispatch(epmod, oracle, cid, T, mask, slices, W, window, threads):
-    """Rows travel sender workgroup -> ring slot -> receiver workgroup -> packed receive buffer, slots are
+    """Rows travel sending step -> ring slot -> receiving step -> packed receive buffer, slots are
     reused under head/tail flow control, and all three message kinds pass through the proxy.  The receive
     buffer must equal the plain definition of dispatch; the messages the oracle's expected multiset; the
     proxy's trace the ring protocol (in-sequence application, no overwrite, no stale read)."""
