@@ -1139,9 +1139,10 @@ def test_ht_ring_dispatch_of_several_sources(epmod, oracle):
             assert np.array_equal(tail[s], per + np.zeros_like(tail[s])) and np.array_equal(head[s], tail[s])
 
 
-@pytest.mark.parametrize("cid,slices,W", [(4, 128, 2), (5, 64, 4)])
+@pytest.mark.parametrize("cid,slices,W", [(4, 128, 2), (5, 64, 4), (4, 1024, 1)])
 def test_ht_ring_dispatch_full_size(epmod, oracle, cid, slices, W):
-    """The full prefill-sized workloads through the rings, in the shape the timing suite launches."""
+    """The full prefill-sized workloads through the rings, in the shape the timing suite launches; the last case
+    has four times more workgroups than the chip holds at once (a workgroup depends on no other workgroup)."""
     cfg = g.config(cid, S=1)
     idx, _ = g.routing_all(cfg)
     x = g.activations(cfg)
