@@ -152,6 +152,43 @@ def run_suite(args) -> int:
                         rr[f"dispatch_fp8_{mode}_us"] = timed(
                             lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3, cmd_mode=cm),
                             after=r.wait)
+                if threads == 4 and chans == 8 and T <= 512:
+                    # one whole low-latency step - layout, per-token dispatch with commands through the proxy,
+                    # GPU-side wait for the posted counters, combine - launched call by call and replayed
+                    # from a HIP graph; host clock over 30 steps queued back to back, per step
+                    counts = torch.zeros((E,), dtype=torch.int32, device="cuda")
+
+                    def ll_step():
+                        L = r.layout(d_idx)
+                        r.dispatch(d_x, d_idx[0], L, recv, cmd_mode=ep.EP_CMD_PER_TOKEN)
+                        r.recv_wait(counts)
+                        r.combine(recv, d_w, L.dst_row[0], o)
+
+                    def host_timed(fn, n=30):
+                        for _ in range(3):
+                            fn()
+                        r.wait()
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        for _ in range(n):
+                            fn()
+                        r.wait()
+                        torch.cuda.synchronize()
+                        return round((time.perf_counter() - t0) / n * 1e6, 1)
+
+                    rr["ll_step_call_by_call_us"] = host_timed(ll_step)
+                    side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+                    with torch.cuda.stream(side):
+                        with torch.cuda.graph(graph, stream=side):
+                            ll_step()
+                    cap = r.captured()
+
+                    def ll_replay():
+                        r.expect(*cap)
+                        graph.replay()
+
+                    rr["ll_step_hip_graph_us"] = host_timed(ll_replay)
+                    del graph
                 if threads == 4:
                     # the proxy performs the writes (registered heaps): per token straight out of x,
                     # chunks out of a packed send heap; host clock from launch to the last counter

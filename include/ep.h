@@ -359,6 +359,19 @@ int ep_event_log(ep_handle *h, void *buf, size_t cap, size_t *n);
 int ep_host_push(ep_handle *h, int32_t channel, uint32_t w0, uint32_t w1, uint32_t w2,
                  uint32_t w3, uint64_t *idx);
 int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx);
+/* ep_captured / ep_expect - ring-on launches inside a HIP graph.  ep_dispatch,
+ * ep_ht_dispatch and ep_fifo_stress tell ep_wait at call time how many count
+ * Atomics (or Drains) their kernel is going to push.  On a stream that is being
+ * captured nothing runs at call time, so the call adds those numbers to a ledger
+ * instead: ep_captured returns it (and clears it when reset != 0) once the capture
+ * has ended, and the caller hands the numbers to ep_expect before (or right
+ * after) every launch of the graph, so that ep_wait covers the replayed work.
+ * Everything else these calls do is capturable as it is: their kernels clear
+ * their own scratch, and no memset or copy is issued on the stream.
+ * Host memory only; thread-compatible like the other calls. */
+int ep_captured(ep_handle *h, int64_t *atomics, int64_t *drains, int32_t reset);
+int ep_expect(ep_handle *h, int64_t atomics, int64_t drains);
+
 /* Tells the proxy how many count Atomics ep_wait should expect in addition
  * (ep_dispatch does this itself for its own). */
 int ep_host_expect_atomics(ep_handle *h, int32_t n);

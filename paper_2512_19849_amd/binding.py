@@ -68,7 +68,7 @@ EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_co
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
-           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters", "ep_fifo_stress"]
+           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters", "ep_fifo_stress", "ep_captured", "ep_expect"]
 
 _lib = None
 
@@ -119,6 +119,8 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_ht_dispatch.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp]
     L.ep_ring_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     L.ep_fifo_stress.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.ep_captured.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), i32]
+    L.ep_expect.argtypes = [vp, i64, i64]
     for name in EXPORTS:
         getattr(L, name).restype = C.c_int
     L.ep_last_error.argtypes = []
@@ -313,6 +315,17 @@ def ep_bw_probe(kind: int, src, dst, nbytes: int, stream=None) -> None:
 
 def ep_last_error() -> str:
     return (load_library().ep_last_error() or b"").decode(errors="replace")
+
+
+def ep_captured(h: int, reset: bool = True):
+    """(atomics, drains) that calls on capturing streams have put into the handle's ledger."""
+    a, d = C.c_int64(0), C.c_int64(0)
+    _check("ep_captured", load_library().ep_captured(h, C.byref(a), C.byref(d), 1 if reset else 0))
+    return int(a.value), int(d.value)
+
+
+def ep_expect(h: int, atomics: int, drains: int) -> None:
+    _check("ep_expect", load_library().ep_expect(h, atomics, drains))
 
 
 def ep_host_expect_atomics(h: int, n: int) -> None:

@@ -107,6 +107,24 @@ int dev_alloc_zero(T **p, size_t bytes) {
   return EP_OK;
 }
 
+// A launch entry point adds what its kernel will push to the counts ep_wait waits for - unless the
+// stream is being captured into a graph: then nothing runs now, and the counts go to a ledger the
+// caller reads with ep_captured and re-registers with ep_expect before every launch of the graph.
+void expect_more(ep_handle *h, void *stream, int64_t atomics, int64_t drains) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing((hipStream_t)stream, &st) != hipSuccess) {
+    (void)hipGetLastError();  // (the legacy stream cannot be asked while another stream captures)
+    st = hipStreamCaptureStatusNone;
+  }
+  if (st == hipStreamCaptureStatusActive) {
+    h->captured_atomics.fetch_add(atomics, std::memory_order_relaxed);
+    h->captured_drains.fetch_add(drains, std::memory_order_relaxed);
+  } else {
+    h->expected_atomics.fetch_add(atomics, std::memory_order_relaxed);
+    h->expected_drains.fetch_add(drains, std::memory_order_relaxed);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -413,9 +431,9 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
   if (mode != EP_CMD_NONE) {
     if (((uint64_t)T * a.row_bytes) >> 4 > 0xFFFFFFFFull) return EP_EINVAL;
     if (mode == EP_CMD_CHUNK32_ORDERED)
-      h->expected_drains.fetch_add(c.num_channels, std::memory_order_relaxed);
+      expect_more(h, stream, 0, c.num_channels);
     else
-      h->expected_atomics.fetch_add(dst_rank_filter < 0 ? c.num_experts : h->E_loc, std::memory_order_relaxed);
+      expect_more(h, stream, dst_rank_filter < 0 ? c.num_experts : h->E_loc, 0);
   }
   if (T == 0) {
     // nothing to launch; a ring-on dispatch of zero tokens still owes its (all zero) count atomics,
@@ -527,7 +545,7 @@ int ep_fifo_stress(ep_handle *h, int32_t pushers, int32_t cmds_per_pusher, uint6
   if (pushers < 1 || pushers > 65536 || cmds_per_pusher < 1 || cmds_per_pusher > (1 << 20)) return EP_EINVAL;
   if (!d_lat_sum || !d_lat_max) return EP_EINVAL;
   if (int e = dev_err(h)) return e;
-  h->expected_atomics.fetch_add((int64_t)pushers * cmds_per_pusher, std::memory_order_relaxed);
+  expect_more(h, stream, (int64_t)pushers * cmds_per_pusher, 0);
   return HIP_OK((hipError_t)launch_fifo_stress(h->ring, pushers, cmds_per_pusher, (unsigned long long *)d_lat_sum,
                                                (unsigned long long *)d_lat_max, stream))
              ? EP_OK
@@ -637,7 +655,7 @@ int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, con
   a.cum_rev = h->ring_cum_rev + first;
   a.waves_done = h->waves_done;
   a.fifo = h->ring;
-  h->expected_drains.fetch_add(c.num_channels, std::memory_order_relaxed);
+  expect_more(h, stream, 0, c.num_channels);
   return HIP_OK((hipError_t)launch_ht_ring(a, stream)) ? EP_OK : EP_EHIP;
 }
 
@@ -780,6 +798,25 @@ int ep_bw_probe(int32_t kind, const void *d_src, void *d_dst, int64_t bytes, voi
   if ((kind != 1 && !d_src) || !d_dst) return EP_EINVAL;  // kind 0 uses d_dst as a 16-byte sink
   if (((uintptr_t)d_src | (uintptr_t)d_dst) & 15) return EP_EINVAL;
   return HIP_OK((hipError_t)launch_bw_probe(kind, d_src, d_dst, bytes, stream)) ? EP_OK : EP_EHIP;
+}
+
+int ep_captured(ep_handle *h, int64_t *atomics, int64_t *drains, int32_t reset) {
+  if (!h || !atomics || !drains) return EP_EINVAL;
+  if (reset) {
+    *atomics = h->captured_atomics.exchange(0);
+    *drains = h->captured_drains.exchange(0);
+  } else {
+    *atomics = h->captured_atomics.load();
+    *drains = h->captured_drains.load();
+  }
+  return EP_OK;
+}
+
+int ep_expect(ep_handle *h, int64_t atomics, int64_t drains) {
+  if (!h || atomics < 0 || drains < 0) return EP_EINVAL;
+  h->expected_atomics.fetch_add(atomics, std::memory_order_relaxed);
+  h->expected_drains.fetch_add(drains, std::memory_order_relaxed);
+  return EP_OK;
 }
 
 int ep_host_expect_atomics(ep_handle *h, int32_t n) {

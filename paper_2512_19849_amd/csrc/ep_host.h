@@ -178,6 +178,8 @@ struct ep_handle {
   // proxy
   std::atomic<bool> stop{false};
   std::atomic<int64_t> expected_atomics{0};
+  // what calls on capturing streams would have added to the two expected_* counts (ep_captured)
+  std::atomic<int64_t> captured_atomics{0}, captured_drains{0};
   std::atomic<int> proxy_error{0};
   int nthreads = 0;
   ep::ProxyThread *threads = nullptr;

@@ -116,6 +116,14 @@ class EPRunner:
     def wait(self) -> None:
         ep.ep_wait(self.h)
 
+    def captured(self, reset: bool = True):
+        """What the ring-on launches captured into a HIP graph will push per replay: (atomics, drains)."""
+        return ep.ep_captured(self.h, reset)
+
+    def expect(self, atomics: int, drains: int) -> None:
+        """Before (or right after) launching such a graph: lets wait() cover the replayed work."""
+        ep.ep_expect(self.h, atomics, drains)
+
     def stats(self) -> dict:
         return ep.ep_stats(self.h)
 

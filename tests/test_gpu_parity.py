@@ -584,6 +584,89 @@ def test_ring_off_step_replays_from_a_hip_graph(epmod, oracle):
         assert r.stats()["device_error"] == 0
 
 
+@pytest.mark.parametrize("mode_name", ["per_token", "chunk32", "chunk32_ordered"])
+def test_ring_on_step_replays_from_a_hip_graph(epmod, oracle, mode_name):
+    """layout -> dispatch with commands through the proxy -> GPU-side wait for the posted counters -> combine,
+    captured once and replayed with new routing and activations, eager work and synchronisations in between.
+    A call on a capturing stream runs nothing, so what its kernel will push goes to the handle's ledger
+    (ep_captured) and is handed back with ep_expect at every launch of the graph; every replay must give what
+    the eager calls give (= the oracle's result), and ep_wait must cover the replayed commands."""
+    cfg = g.config(1)
+    mode = {"per_token": epmod.EP_CMD_PER_TOKEN, "chunk32": epmod.EP_CMD_CHUNK32,
+            "chunk32_ordered": epmod.EP_CMD_CHUNK32_ORDERED}[mode_name]
+    ordered = mode == epmod.EP_CMD_CHUNK32_ORDERED
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    T, rows = cfg.T, cfg.T * cfg.K
+    with _runner(epmod, cfg, num_proxy_threads=2, spin_timeout_ms=10000) as r:
+        d_idx = torch.zeros((1, T, cfg.K), dtype=torch.int32, device="cuda")
+        d_x = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        d_w = torch.zeros((T, cfg.K), dtype=torch.float32, device="cuda")
+        recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+        out = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        counts = torch.zeros((cfg.E,), dtype=torch.int32, device="cuda")
+
+        def step():
+            lay = r.layout(d_idx)
+            r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=mode)
+            if not ordered:                          # (the ordered mode announces rows per rank, not per expert)
+                r.recv_wait(counts)
+            r.combine(recv, d_w, lay.dst_row[0], out)
+            return lay
+
+        def load(seed):
+            c2 = g.EPConfig(cfg.name, T=cfg.T, H=cfg.H, E=cfg.E, K=cfg.K, R=cfg.R, S=1, seed=cfg.seed + seed)
+            idx, w = g.routing_all(c2)
+            x = g.activations(c2)
+            d_idx.copy_(_dev(idx))
+            d_w.copy_(_dev(w[0]))
+            d_x.copy_(bits_to_bf16(x))
+            return idx, w, x
+
+        load(0)
+        step()                                       # warm-up outside the capture (first-use initialisation)
+        r.wait()
+        torch.cuda.synchronize()
+        assert r.captured() == (0, 0)                # eager calls leave the ledger alone
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                lay = step()
+        cap = r.captured()
+        assert cap == ((0, 8) if ordered else (cfg.E, 0))   # 8 FIFOs to drain, or one count Atomic per expert
+        assert r.captured() == (0, 0)                # reading it cleared it
+        r.wait()                                     # nothing was launched by the capture: returns at once
+        for seed in (1, 2, 3):
+            idx, w, x = load(seed)
+            recv.fill_(7.0)                          # eager work between the replays
+            counts.fill_(-5)
+            r.expect(*cap)
+            graph.replay()
+            r.wait()                                 # covers the replayed commands
+            torch.cuda.synchronize()
+            want_lay = oracle.layout(idx, cfg.E, cfg.R)
+            got = lay.numpy()
+            for name, v in want_lay.items():
+                assert np.array_equal(got[name], v), (seed, name)
+            wrecv, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+            assert np.array_equal(bf16_to_bits(recv), wrecv), seed
+            wout = oracle.combine(wrecv, w[0], want_lay["dst_row"][0])
+            assert int(oracle.bf16_ulp_distance(bf16_to_bits(out), wout).max()) <= 1, seed
+            if not ordered:
+                assert np.array_equal(counts.cpu().numpy(), want_lay["count"][0]), seed
+                assert np.array_equal(r.counters()[0], want_lay["count"][0]), seed
+            # and the eager path on the same inputs
+            out.zero_()
+            step()
+            r.wait()
+            torch.cuda.synchronize()
+            assert int(oracle.bf16_ulp_distance(bf16_to_bits(out), wout).max()) <= 1
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        if not ordered:
+            assert st["atomics_applied"] == 7 * cfg.E   # warm-up + three replays + three eager steps
+
+
 def test_host_side_argument_errors(epmod):
     from paper_2512_19849_amd.runner import EPRunner
     with pytest.raises(epmod.EPError):

@@ -688,3 +688,19 @@ def test_sender_side_fence_holds_atomics_at_the_sender(ep, oracle, window):
         oracle.check_pacing_trace(ev, 0, E_loc)
     finally:
         ep.ep_proxy_stop(h)
+
+
+def test_capture_ledger_and_expectations_on_a_host_handle(ep):
+    """ep_captured / ep_expect are host bookkeeping: the ledger starts empty, ep_expect makes ep_wait wait for
+    that many more count Atomics, negative numbers are refused."""
+    h = _start(ep, num_channels=2, ring_entries=16, num_proxy_threads=1)
+    try:
+        assert ep.ep_captured(h) == (0, 0)
+        ep.ep_expect(h, 1, 0)
+        with pytest.raises(ep.EPError):
+            ep.ep_expect(h, -1, 0)
+        _atomic(ep, h, 0, 0, 0, 0, 0, 4)              # a count of zero rows for (source 0, rank 0, expert 0)
+        ep.ep_wait(h)
+        assert ep.ep_stats(h)["atomics_applied"] == 1
+    finally:
+        ep.ep_proxy_stop(h)
