@@ -584,7 +584,7 @@ def test_ring_off_step_replays_from_a_hip_graph(epmod, oracle):
         assert r.stats()["device_error"] == 0
 
 
-@pytest.mark.parametrize("mode_name", ["per_token", "chunk32", "chunk32_ordered"])
+@pytest.mark.parametrize("mode_name", ["per_token", "chunk32", "chunk32_ordered", "ring_channels"])
 def test_ring_on_step_replays_from_a_hip_graph(epmod, oracle, mode_name):
     """layout -> dispatch with commands through the proxy -> GPU-side wait for the posted counters -> combine,
     captured once and replayed with new routing and activations, eager work and synchronisations in between.
@@ -593,21 +593,27 @@ def test_ring_on_step_replays_from_a_hip_graph(epmod, oracle, mode_name):
     the eager calls give (= the oracle's result), and ep_wait must cover the replayed commands."""
     cfg = g.config(1)
     mode = {"per_token": epmod.EP_CMD_PER_TOKEN, "chunk32": epmod.EP_CMD_CHUNK32,
-            "chunk32_ordered": epmod.EP_CMD_CHUNK32_ORDERED}[mode_name]
-    ordered = mode == epmod.EP_CMD_CHUNK32_ORDERED
+            "chunk32_ordered": epmod.EP_CMD_CHUNK32_ORDERED, "ring_channels": None}[mode_name]
+    channels = mode is None                          # ep_ht_dispatch: rows through ring slots, ends with Drains
+    ordered = channels or mode == epmod.EP_CMD_CHUNK32_ORDERED
     from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
     T, rows = cfg.T, cfg.T * cfg.K
-    with _runner(epmod, cfg, num_proxy_threads=2, spin_timeout_ms=10000) as r:
+    kw = dict(ht_slices=3, ht_ring_slots=1) if channels else {}
+    with _runner(epmod, cfg, num_proxy_threads=2, spin_timeout_ms=10000, **kw) as r:
         d_idx = torch.zeros((1, T, cfg.K), dtype=torch.int32, device="cuda")
         d_x = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
         d_w = torch.zeros((T, cfg.K), dtype=torch.float32, device="cuda")
         recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
         out = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
         counts = torch.zeros((cfg.E,), dtype=torch.int32, device="cuda")
+        ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda") if channels else None
 
         def step():
             lay = r.layout(d_idx)
-            r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=mode)
+            if channels:
+                r.ht_dispatch(d_x, d_idx[0], lay, ring, recv)
+            else:
+                r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=mode)
             if not ordered:                          # (the ordered mode announces rows per rank, not per expert)
                 r.recv_wait(counts)
             r.combine(recv, d_w, lay.dst_row[0], out)
