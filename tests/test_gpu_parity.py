@@ -1380,6 +1380,71 @@ def test_seeded_sweep_of_small_shapes_through_every_dispatch_mode(epmod, oracle)
             assert np.array_equal(lay.numpy()["dst_row"], want_lay["dst_row"]), tag
 
 
+def test_seeded_sweep_of_ring_buffer_channels(epmod, oracle):
+    """Forty seeded shapes through ep_ht_dispatch alone, three dispatches per handle (the second with fewer
+    tokens; sequence numbers, tails and heads carry over), with what the other sweeps do not reach: top-k up to
+    48 (one lane per destination of a token), rows longer than one register piece (hidden 9216), FP8 rows,
+    64 to 1024 threads per workgroup, rings of one to three slots, every entry masked."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    import os
+    rng = np.random.default_rng(20251220)
+    old_threads = os.environ.get("EP_HT_THREADS")
+    try:
+        for case in range(40):
+            R = int(rng.choice([1, 2, 4, 8, 16, 32]))
+            E = R * int(rng.choice([1, 2, 3, 8]))
+            K = int(rng.integers(1, min(E, 48) + 1)) if rng.random() < 0.3 else int(rng.integers(1, min(E, 9) + 1))
+            H = 128 * int(rng.choice([1, 2, 5, 8, 24, 56, 72]))
+            T = int(rng.integers(1, 500))
+            os.environ["EP_HT_THREADS"] = str(int(rng.choice([64, 256, 512, 1024])))
+            cfg = g.EPConfig(f"rsweep{case}", T=T, H=H, E=E, K=K, R=R, S=1, seed=3000 + case)
+            kw = dict(num_proxy_threads=int(rng.integers(1, 5)), num_channels=int(rng.choice([1, 3, 8, 16])),
+                      ring_entries=int(rng.choice([8, 64, 4096])), reorder_window=int(rng.choice([0, 3, 50])),
+                      reorder_seed=case, ht_slices=int(rng.integers(1, 12)), ht_ring_slots=int(rng.integers(1, 4)),
+                      heap_rows=T * K + 1, spin_timeout_ms=5000)
+            tag = f"case {case}: R={R} E={E} K={K} H={H} T={T} threads={os.environ['EP_HT_THREADS']} {kw}"
+            with _runner(epmod, cfg, **kw) as r:
+                ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+                for rep in range(3):
+                    Tr = T if rep != 1 else int(rng.integers(1, T + 1))
+                    idx = np.stack([rng.permutation(E)[:K] for _ in range(Tr)]).astype(np.int32)[None]
+                    if rng.random() < 0.5:
+                        idx = g.mask_random(idx, float(rng.choice([0.05, 0.5, 1.0])), seed=case * 7 + rep)
+                    x = g.activations(cfg, 0, T=Tr)
+                    rows = int((idx >= 0).sum()) + 1
+                    want_lay = oracle.layout(idx, E, R)
+                    d_idx, d_x = _dev(idx), bits_to_bf16(x)
+                    lay = r.layout(d_idx)
+                    if rng.random() < 0.6:
+                        want, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows, -1,
+                                                       fill=0xBFC0)
+                        recv = torch.full((rows, H), -1.5, dtype=torch.bfloat16, device="cuda")
+                        r.ht_dispatch(d_x, d_idx[0], lay, ring, recv)
+                        r.wait()
+                        torch.cuda.synchronize()
+                        assert np.array_equal(bf16_to_bits(recv), want), f"bf16, dispatch {rep}; {tag}"
+                    else:
+                        wq, ws, _ = oracle.dispatch_fp8(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+                        rq = torch.zeros((rows, H), dtype=torch.uint8, device="cuda")
+                        rs = torch.zeros((rows, H // 128), dtype=torch.float32, device="cuda")
+                        r.ht_dispatch(d_x, d_idx[0], lay, ring, rq, recv_scale=rs)
+                        r.wait()
+                        torch.cuda.synchronize()
+                        dr = want_lay["dst_row"][0]
+                        hit = np.zeros(rows, bool)
+                        hit[dr[dr >= 0]] = True
+                        assert np.array_equal(rq.cpu().numpy()[hit], wq[hit]), f"FP8 codes, dispatch {rep}; {tag}"
+                        assert np.array_equal(rs.cpu().numpy()[hit], ws[hit]), f"FP8 scales, dispatch {rep}; {tag}"
+                        assert not rq.cpu().numpy()[~hit].any(), f"FP8 rows nobody owns, dispatch {rep}; {tag}"
+                    st = r.stats()
+                    assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0, tag
+    finally:
+        if old_threads is None:
+            os.environ.pop("EP_HT_THREADS", None)
+        else:
+            os.environ["EP_HT_THREADS"] = old_threads
+
+
 def test_seeded_sweep_of_sources_payloads_and_the_way_back(epmod, oracle):
     """Twenty-five seeded shapes with several sources: the layout over all of them, then for a random
     source and (sometimes) a single destination rank: FP8 dispatch in a random command mode, FP8 through
