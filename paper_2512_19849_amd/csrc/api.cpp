@@ -183,7 +183,8 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     if (!rc) rc = dev_alloc_zero(&h->chunk_cnt, (size_t)E * h->chunks_per_expert * 4);
     if (!rc) rc = dev_alloc_zero(&h->expert_done, (size_t)E * 4);
     if (!rc) rc = dev_alloc_zero(&h->ticket, 4);
-    if (!rc) rc = dev_alloc_zero(&h->waves_done, 4);
+    // grid-completion counters of the Drain epilogue: one per 64 workgroups (grids reach 2^19 workgroups) + 1
+    if (!rc) rc = dev_alloc_zero(&h->waves_done, (size_t)(1 + (1 << 19) / 64 + 1) * 4);
     if (!rc) rc = dev_alloc_zero(&h->ht_seq, (size_t)S * cfg->num_ranks * 4);
     if (nring) {
       if (!rc) rc = dev_alloc_zero(&h->ring_seq_fwd, nring * 4);

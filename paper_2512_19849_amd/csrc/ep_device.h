@@ -108,18 +108,31 @@ EP_DEV void store_payload(u32x4 *p, const u32x4 &v) { *(volatile global_u32x4 *)
 // All stores of this wave are acknowledged after this (compiler and hardware barrier).
 EP_DEV void wait_for_own_stores() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
 
-// Kernel epilogue with EP_CMD_DRAIN: the last wavefront of the grid pushes a
-// Drain on every channel and blocks on Check-completion for each (Section 3.1:
-// Drain and Barrier are blocking on the GPU side).
-EP_DEV void drain_all_channels(const RingDev &ring, unsigned *waves_done, unsigned src, int lane) {
-  const unsigned total = gridDim.x * (blockDim.x >> 6);
-  unsigned done = 0;
-  wait_for_own_stores();  // this wave's commands are in their rings before it reports done
-  if (lane == 0)
-    done = __hip_atomic_fetch_add(waves_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-  done = __builtin_amdgcn_readfirstlane(done);
-  if (done != total) return;
-  if (lane == 0) __hip_atomic_store(waves_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Kernel epilogue with EP_CMD_DRAIN: the last workgroup of the grid to finish pushes a Drain on
+// every channel and blocks on Check-completion for each (Section 3.1: Drain and Barrier are blocking
+// on the GPU side).  Every wave of every workgroup must call this.
+// "Last to finish" is counted per workgroup and in two levels (groups of kDrainGroup workgroups,
+// then groups): atomics on ONE address serialise in the L2 at about 8 ns each, and one count per
+// wave of a 32768-wave grid added 270 us to the kernel.  done_cnt: [1 + groups] scratch, zero
+// between launches (the counters reset themselves).
+constexpr unsigned kDrainGroup = 64;
+EP_DEV void drain_all_channels(const RingDev &ring, unsigned *done_cnt, unsigned src, int lane) {
+  wait_for_own_stores();  // this wave's commands are in their rings ...
+  __syncthreads();        // ... and so are those of every wave of the workgroup
+  if (threadIdx.x >= 64) return;
+  unsigned last = 0;
+  if (lane == 0) {
+    const unsigned group = blockIdx.x / kDrainGroup, ngroups = (gridDim.x + kDrainGroup - 1) / kDrainGroup;
+    const unsigned gsize = min(kDrainGroup, gridDim.x - group * kDrainGroup);
+    if (__hip_atomic_fetch_add(&done_cnt[1 + group], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == gsize) {
+      __hip_atomic_store(&done_cnt[1 + group], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (__hip_atomic_fetch_add(&done_cnt[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == ngroups) {
+        __hip_atomic_store(&done_cnt[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = 1;
+      }
+    }
+  }
+  if (!__builtin_amdgcn_readfirstlane(last)) return;
   for (unsigned c = lane; c < ring.channels; c += 64) {
     const unsigned long long idx = ring_push(ring, c, cmd_w0(EP_OP_DRAIN, src, 0, 0), 0u, 0u, 0u);
     if (idx != ~0ull) ring_wait_completion(ring, c, idx);

@@ -17,6 +17,7 @@
 #include <atomic>
 #include <deque>
 #include <map>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -64,6 +65,57 @@ struct WireEvent {
   uint16_t slice;     // ring-buffer channels: the token slice (part of the connection's identity)
 };
 
+// Messages of one sequenced channel that arrived ahead of their turn (the control buffer of Section 3.3,
+// per channel).  Those within kWin numbers of the next expected one sit in a window indexed by number
+// mod kWin - no allocation per message, which matters when most messages of a busy channel arrive
+// early; anything further ahead (or behind: a protocol error that a Drain reports) goes to a map.
+struct ReorderBuf {
+  static constexpr uint32_t kWin = 256;
+  struct Win {
+    WireEvent ev[kWin];
+    uint64_t have[kWin / 64] = {};
+  };
+  std::unique_ptr<Win> win;  // allocated with the first early message
+  std::map<uint32_t, WireEvent> far;
+  uint32_t count = 0;
+
+  bool empty() const { return count == 0; }
+  void put(uint32_t next, uint32_t seq, const WireEvent &e) {
+    if (seq - next < kWin) {  // (unsigned: a number behind `next` is "far")
+      if (!win) win.reset(new Win());
+      const uint32_t i = seq % kWin;
+      if (!((win->have[i / 64] >> (i % 64)) & 1)) ++count;
+      win->ev[i] = e;
+      win->have[i / 64] |= 1ull << (i % 64);
+    } else if (far.emplace(seq, e).second) {
+      ++count;
+    }
+  }
+  // Removes the message numbered seq, if it is here.  seq is always the channel's next number, so a
+  // window slot can only hold that very number (a later one with the same index was not yet within
+  // kWin of the next number when it arrived, and went to the map).
+  bool take(uint32_t seq, WireEvent &out) {
+    if (count == 0) return false;
+    const uint32_t i = seq % kWin;
+    if (win && ((win->have[i / 64] >> (i % 64)) & 1)) {
+      out = win->ev[i];
+      win->have[i / 64] &= ~(1ull << (i % 64));
+      --count;
+      return true;
+    }
+    if (!far.empty()) {
+      auto it = far.find(seq);
+      if (it != far.end()) {
+        out = it->second;
+        far.erase(it);
+        --count;
+        return true;
+      }
+    }
+    return false;
+  }
+};
+
 // A message on its way out of the sender half: the notice the receiver will get, and (registered
 // heaps) the copies that have to complete first.  Packed per-token Writes are one message with
 // several source segments of one row each and one contiguous destination.
@@ -107,7 +159,7 @@ struct alignas(64) ProxyThread {
   bool gpu_ready = false;
   // ordered (high-throughput) channels: next sequence number and early arrivals per (source, destination rank)
   std::vector<uint32_t> next_seq;
-  std::vector<std::map<uint32_t, WireEvent>> early;
+  std::vector<ReorderBuf> early;
   // pacing: messages in flight per destination rank, and those waiting at the sender for room
   std::vector<int32_t> in_flight;
   std::vector<std::deque<Outbound>> held;
@@ -118,7 +170,7 @@ struct alignas(64) ProxyThread {
   std::vector<uint32_t> open_key;
   // ring-buffer channels: the same per (source, slice, destination rank, direction)
   std::vector<uint32_t> ring_next;
-  std::vector<std::map<uint32_t, WireEvent>> ring_early;
+  std::vector<ReorderBuf> ring_early;
   uint64_t rng = 0;
   // statistics (written by the owner thread only, read racy-but-atomically)
   std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},

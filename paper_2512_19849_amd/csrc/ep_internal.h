@@ -71,7 +71,7 @@ struct DispatchArgs {
   int32_t chunks_per_expert;
   int32_t *chunk_cnt;      // scratch [E * chunks_per_expert], zero between calls
   int32_t *expert_done;    // scratch [E], zero between calls
-  unsigned *waves_done;    // scratch, zero between calls
+  unsigned *waves_done;    // scratch of the Drain epilogue [1 + workgroups / 64], zero between calls
   unsigned *ht_seq;        // scratch [S*R]: next sequence number of each communication channel
   int32_t R;
   RingDev ring;

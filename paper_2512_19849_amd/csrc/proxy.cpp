@@ -105,19 +105,15 @@ void deliver_ordered(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
   if (seq + 0x8000u < next) seq += 0x10000u;
   else if (seq >= next + 0x8000u && seq >= 0x10000u) seq -= 0x10000u;
   log_event(h, P, (ev.imm >> 31) ? 5 : 4, ev.src, ev.dst_rank, seq);
+  ReorderBuf &q = P.early[chan];
   if (seq != next) {
-    P.early[chan].emplace(seq, ev);
+    q.put(next, seq, ev);
     bump(P.ordered_parked, 1);
     return;
   }
   apply_ordered(h, P, chan, ev, seq);
   ++next;
-  std::map<uint32_t, WireEvent> &q = P.early[chan];
-  for (auto it = q.find(next); it != q.end(); it = q.find(next)) {
-    apply_ordered(h, P, chan, it->second, next);
-    q.erase(it);
-    ++next;
-  }
+  for (WireEvent held; q.take(next, held); ++next) apply_ordered(h, P, chan, held, next);
 }
 
 // Ring-buffer channels (Section 3.3): the same in-sequence rule per channel (source, slice,
@@ -151,19 +147,15 @@ void deliver_ring(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
   const uint32_t seq = rebuild_seq(next, (ev.imm >> 15) & 0xFFFFu);
   const uint32_t where = ((uint32_t)ev.slice << 8) | ev.dst_rank;
   log_event(h, P, ev.ordered == 3 ? 10 : ((ev.imm >> 31) ? 9 : 8), ev.src, where, seq);
+  ReorderBuf &q = P.ring_early[dir];
   if (seq != next) {
-    P.ring_early[dir].emplace(seq, ev);
+    q.put(next, seq, ev);
     bump(P.ordered_parked, 1);
     return;
   }
   apply_ring(h, P, chan, ev, seq);
   ++next;
-  std::map<uint32_t, WireEvent> &q = P.ring_early[dir];
-  for (auto it = q.find(next); it != q.end(); it = q.find(next)) {
-    apply_ring(h, P, chan, it->second, next);
-    q.erase(it);
-    ++next;
-  }
+  for (WireEvent held; q.take(next, held); ++next) apply_ring(h, P, chan, held, next);
 }
 
 // The "network" between the two halves.  With reorder_window == 0 immediates

@@ -379,6 +379,33 @@ def test_partial_ordering_sequence_gap_is_reported(ep, oracle):
         ep.ep_proxy_stop(h)
 
 
+def test_partial_ordering_long_run_ahead_of_a_late_message(ep, oracle):
+    """The first message of a channel arrives last, behind 1400 later ones (more than the receiver's
+    reorder window holds, so both the window and its overflow are in play), twice in a row on the same
+    channel; nothing is applied before it, everything in sequence after it."""
+    R = 4
+    h = _start(ep, num_src=1, ring_entries=4096)
+    try:
+        base = 0
+        for rnd, n in enumerate((1400, 700)):
+            for q in range(2, n, 2):
+                _owrite(ep, h, 2, 0, 2, base + q, 1, 2048, 0)
+                _oatomic(ep, h, 2, 0, 2, base + q + 1, 3, R)
+            _oatomic(ep, h, 2, 0, 2, base + 1, 3, R)
+            time.sleep(0.05)
+            assert ep.ep_tail_counters(h, 1, R)[0, 2] == rnd * 2100   # nothing new announced yet
+            _owrite(ep, h, 2, 0, 2, base, 1, 2048, 0)                     # the late one
+            _drain_all(ep, h, 4)
+            base += n
+            assert ep.ep_tail_counters(h, 1, R)[0, 2] == 3 * base // 2
+        st = ep.ep_stats(h)
+        assert st["proxy_error"] == 0 and st["rejected"] == 0 and st["ordered_parked"] == 1399 + 699
+        res = oracle.check_order_trace(ep.ep_event_log(h))
+        assert res["applied"] == 2100 and res["waited"] == 1399 + 699
+    finally:
+        ep.ep_proxy_stop(h)
+
+
 def test_partial_ordering_sequence_numbers_wrap_16_bits(ep, oracle):
     """The immediate carries 16 bits of the number; the receiver rebuilds the full value."""
     R = 4
