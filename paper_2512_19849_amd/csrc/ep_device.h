@@ -46,7 +46,8 @@ EP_DEV unsigned long long ring_push(const RingDev &r, unsigned c, unsigned w0, u
   do {
     if (!done) {
       if (idx - head < r.entries) {
-        *(volatile __attribute__((address_space(1))) u32x4 *)slot = v;  // one 16-byte store straight to host memory (system scope)
+        // one 16-byte store straight to host memory (system scope); not waited for here, see store_payload
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(slot), "v"(v) : "memory");
         done = true;
       } else {
         // Full: wait for the proxy to pop.  Thousands of lanes can be waiting on one channel, and
@@ -102,11 +103,20 @@ EP_DEV bool ring_wait_completion(const RingDev &r, unsigned c, unsigned long lon
 // is needed, and the counters can be relaxed device-scope atomics.  Measured on MI355X the
 // write-through stores stream as fast as non-temporal ones, whereas a device-scope release fence
 // per wave (L2 write-back) made the dispatch 4-8x slower.
-typedef __attribute__((address_space(1))) u32x4 global_u32x4;
-EP_DEV void store_payload(u32x4 *p, const u32x4 &v) { *(volatile global_u32x4 *)p = v; }
+// The store is written out as the instruction itself: the way to get these cache bits from C++ is
+// a volatile access, and the compiler follows EVERY volatile store with a wait for all outstanding
+// memory operations - a wave would then hand the memory system one kilobyte at a time (dispatch
+// 91 -> 87 us without those waits).  The compiler does not count these stores, so the wait that
+// orders them is explicit as well.
+EP_DEV void store_payload(u32x4 *p, const u32x4 &v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+}
 
-// All stores of this wave are acknowledged after this (compiler and hardware barrier).
-EP_DEV void wait_for_own_stores() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+// All stores of this wave are acknowledged after this (hardware wait, then a compiler barrier).
+EP_DEV void wait_for_own_stores() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0); expcnt and lgkmcnt left alone
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+}
 
 // Kernel epilogue with EP_CMD_DRAIN: the last workgroup of the grid to finish pushes a Drain on
 // every channel and blocks on Check-completion for each (Section 3.1: Drain and Barrier are blocking
