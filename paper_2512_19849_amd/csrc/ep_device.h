@@ -82,7 +82,11 @@ EP_DEV unsigned long long ring_push(const RingDev &r, unsigned c, unsigned w0, u
 
 // Check-completion(Idx): has the proxy popped command idx of channel c?
 // Blocks (bounded) until it has; used after a Drain.
+EP_DEV void wait_for_own_stores();
 EP_DEV bool ring_wait_completion(const RingDev &r, unsigned c, unsigned long long idx) {
+  // the command has to have left before it can be popped: a poll issued together with the Push store
+  // only finds the old head, and the next poll comes a sleep and a PCIe round trip later
+  wait_for_own_stores();
   const unsigned long long t0 = wall_clock64();
   for (;;) {
     unsigned long long head =
