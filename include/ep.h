@@ -359,6 +359,22 @@ int ep_event_log(ep_handle *h, void *buf, size_t cap, size_t *n);
 int ep_host_push(ep_handle *h, int32_t channel, uint32_t w0, uint32_t w1, uint32_t w2,
                  uint32_t w3, uint64_t *idx);
 int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx);
+/* ep_profile / ep_profile_read - kernel-exact durations of the three compute
+ * calls, for callers that want them without an external profiler.  While
+ * profiling is on, every ep_layout / ep_dispatch / ep_combine launch carries a
+ * pair of HIP events that receive the begin timestamp of the call's first kernel
+ * and the end timestamp of its last one from the launches themselves (nothing
+ * extra is put on the stream, unlike a pair of recorded events, which delays
+ * the kernel between them by a few microseconds).  ep_profile_read waits for the
+ * timed launches of one call (0 layout, 1 dispatch, 2 combine), returns their
+ * summed duration in milliseconds and their number, and forgets them when
+ * reset != 0.  Launches on a capturing stream are not timed.  on = 0 switches
+ * profiling off; on = n >= 1 switches it on and makes sure n pairs of events are
+ * at hand, so that up to n timed launches create none (n <= 65536).  Events are
+ * reused after a read with reset and freed when the handle stops. */
+int ep_profile(ep_handle *h, int32_t on);
+int ep_profile_read(ep_handle *h, int32_t call, double *total_ms, int32_t *launches, int32_t reset);
+
 /* ep_captured / ep_expect - ring-on launches inside a HIP graph.  ep_dispatch,
  * ep_ht_dispatch and ep_fifo_stress tell ep_wait at call time how many count
  * Atomics (or Drains) their kernel is going to push.  On a stream that is being

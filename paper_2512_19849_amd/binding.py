@@ -68,7 +68,7 @@ EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_co
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
-           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters", "ep_fifo_stress", "ep_captured", "ep_expect"]
+           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters", "ep_fifo_stress", "ep_captured", "ep_expect", "ep_profile", "ep_profile_read"]
 
 _lib = None
 
@@ -121,6 +121,8 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_fifo_stress.argtypes = [vp, i32, i32, vp, vp, vp]
     L.ep_captured.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), i32]
     L.ep_expect.argtypes = [vp, i64, i64]
+    L.ep_profile.argtypes = [vp, i32]
+    L.ep_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32), i32]
     for name in EXPORTS:
         getattr(L, name).restype = C.c_int
     L.ep_last_error.argtypes = []
@@ -315,6 +317,18 @@ def ep_bw_probe(kind: int, src, dst, nbytes: int, stream=None) -> None:
 
 def ep_last_error() -> str:
     return (load_library().ep_last_error() or b"").decode(errors="replace")
+
+
+def ep_profile(h: int, on) -> None:
+    """on: False/0 off; True/1 on; n > 1 on, with n event pairs made ahead of the launches."""
+    _check("ep_profile", load_library().ep_profile(h, int(on)))
+
+
+def ep_profile_read(h: int, call: int, reset: bool = True):
+    """(summed kernel time in ms, launches) of the timed ep_layout (0) / ep_dispatch (1) / ep_combine (2) calls."""
+    ms, n = C.c_double(0.0), C.c_int32(0)
+    _check("ep_profile_read", load_library().ep_profile_read(h, call, C.byref(ms), C.byref(n), 1 if reset else 0))
+    return float(ms.value), int(n.value)
 
 
 def ep_captured(h: int, reset: bool = True):

@@ -107,6 +107,48 @@ int dev_alloc_zero(T **p, size_t bytes) {
   return EP_OK;
 }
 
+// ep_profile: a fresh pair of events for one launch of call `which` (0 layout, 1 dispatch, 2 combine); false
+// (and the launch goes untimed) when profiling is off, the stream is being captured, or no event can be made.
+bool make_spare_events(ep_handle *h, size_t n) {
+  while (h->spare_events.size() < n) {
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    h->spare_events.push_back(e);
+  }
+  return true;
+}
+
+bool timing_for(ep_handle *h, int which, void *stream, LaunchTiming *t) {
+  if (!h->profiling) return false;
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing((hipStream_t)stream, &st) != hipSuccess) (void)hipGetLastError();
+  if (st == hipStreamCaptureStatusActive) return false;
+  if (h->spare_events.size() < 2 && !make_spare_events(h, 2)) return false;
+  hipEvent_t a = h->spare_events.back();
+  h->spare_events.pop_back();
+  hipEvent_t b = h->spare_events.back();
+  h->spare_events.pop_back();
+  h->timed[which].emplace_back(a, b);
+  t->start = a;
+  t->stop = b;
+  return true;
+}
+
+void drop_timed(ep_handle *h) {
+  for (auto &v : h->timed) {
+    for (auto &p : v) {
+      (void)hipEventDestroy(p.first);
+      (void)hipEventDestroy(p.second);
+    }
+    v.clear();
+  }
+  for (hipEvent_t e : h->spare_events) (void)hipEventDestroy(e);
+  h->spare_events.clear();
+}
+
 // A launch entry point adds what its kernel will push to the counts ep_wait waits for - unless the
 // stream is being captured into a graph: then nothing runs now, and the counts go to a ledger the
 // caller reads with ep_captured and re-registers with ep_expect before every launch of the graph.
@@ -278,6 +320,7 @@ int ep_proxy_stop(ep_handle *h) {
     if (P.descs) (void)hipHostFree(P.descs);
   }
   if (h->copy_stream) (void)hipStreamDestroy(h->copy_stream);
+  drop_timed(h);
   free_all(h);
   return rc;
 }
@@ -353,7 +396,9 @@ int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t *d_cou
   a.slot = d_slot;
   a.dst_row = d_dst_row;
   a.error = h->ring.error;
-  return HIP_OK((hipError_t)launch_layout(a, stream)) ? EP_OK : EP_EHIP;
+  LaunchTiming tm{nullptr, nullptr};
+  const bool timed = T > 0 && timing_for(h, 0, stream, &tm);
+  return HIP_OK((hipError_t)launch_layout(a, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
 }
 
 static uint32_t row_bytes_of(int H, int payload) {
@@ -442,7 +487,9 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
     if (mode == EP_CMD_NONE) return EP_OK;
     a.T = 0;
   }
-  return HIP_OK((hipError_t)launch_dispatch(a, payload, stream)) ? EP_OK : EP_EHIP;
+  LaunchTiming tm{nullptr, nullptr};
+  const bool timed = timing_for(h, 1, stream, &tm);
+  return HIP_OK((hipError_t)launch_dispatch(a, payload, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
 }
 
 int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32_t *d_dst_row, int32_t T,
@@ -463,7 +510,9 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32
   a.K = h->cfg.top_k;
   a.H = h->cfg.hidden;
   a.error = h->ring.error;
-  return HIP_OK((hipError_t)launch_combine(a, stream)) ? EP_OK : EP_EHIP;
+  LaunchTiming tm{nullptr, nullptr};
+  const bool timed = timing_for(h, 2, stream, &tm);
+  return HIP_OK((hipError_t)launch_combine(a, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
 }
 
 int ep_dedup(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t ranks_per_group, int32_t *d_group_idx,
@@ -799,6 +848,40 @@ int ep_bw_probe(int32_t kind, const void *d_src, void *d_dst, int64_t bytes, voi
   if ((kind != 1 && !d_src) || !d_dst) return EP_EINVAL;  // kind 0 uses d_dst as a 16-byte sink
   if (((uintptr_t)d_src | (uintptr_t)d_dst) & 15) return EP_EINVAL;
   return HIP_OK((hipError_t)launch_bw_probe(kind, d_src, d_dst, bytes, stream)) ? EP_OK : EP_EHIP;
+}
+
+int ep_profile(ep_handle *h, int32_t on) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (on < 0 || on > 65536) return EP_EINVAL;
+  // events are made here, ahead of the launches that use them (creating one costs microseconds)
+  if (on > 0 && !make_spare_events(h, 2 * (size_t)on)) return EP_EHIP;
+  h->profiling = on != 0;
+  return EP_OK;
+}
+
+int ep_profile_read(ep_handle *h, int32_t call, double *total_ms, int32_t *launches, int32_t reset) {
+  if (!h || call < 0 || call > 2 || !total_ms || !launches) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  double sum = 0.0;
+  int n = 0;
+  for (auto &p : h->timed[call]) {
+    float ms = 0.0f;
+    // the stop event completes with the launch's last kernel
+    if (!HIP_OK(hipEventSynchronize(p.second)) || !HIP_OK(hipEventElapsedTime(&ms, p.first, p.second))) return EP_EHIP;
+    sum += ms;
+    ++n;
+  }
+  *total_ms = sum;
+  *launches = n;
+  if (reset) {
+    for (auto &p : h->timed[call]) {
+      h->spare_events.push_back(p.first);
+      h->spare_events.push_back(p.second);
+    }
+    h->timed[call].clear();
+  }
+  return EP_OK;
 }
 
 int ep_captured(ep_handle *h, int64_t *atomics, int64_t *drains, int32_t reset) {

@@ -107,29 +107,30 @@ int tuned_combine_vpl(int H) {
 }
 
 template <int VPL>
-static void launch_combine_t(CombineArgs a, hipStream_t st) {
+static void launch_combine_t(CombineArgs a, hipStream_t st, const LaunchTiming *tm) {
   const int nvec = a.H / 8;
   a.parts = (nvec + VPL * 64 - 1) / (VPL * 64);
   const long long items = (long long)a.T * a.parts;
   const unsigned grid = (unsigned)((items + 3) / 4);
+  void *ev0 = tm ? tm->start : nullptr, *ev1 = tm ? tm->stop : nullptr;
   switch (a.K) {
-    case 1: hipLaunchKernelGGL((combine_kernel<VPL, 1>), dim3(grid), dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((combine_kernel<VPL, 2>), dim3(grid), dim3(256), 0, st, a); break;
-    case 4: hipLaunchKernelGGL((combine_kernel<VPL, 4>), dim3(grid), dim3(256), 0, st, a); break;
-    case 6: hipLaunchKernelGGL((combine_kernel<VPL, 6>), dim3(grid), dim3(256), 0, st, a); break;
-    case 8: hipLaunchKernelGGL((combine_kernel<VPL, 8>), dim3(grid), dim3(256), 0, st, a); break;
-    default: hipLaunchKernelGGL((combine_kernel<VPL, 0>), dim3(grid), dim3(256), 0, st, a); break;
+    case 1: launch_kernel(combine_kernel<VPL, 1>, dim3(grid), dim3(256), 0, st, ev0, ev1, a); break;
+    case 2: launch_kernel(combine_kernel<VPL, 2>, dim3(grid), dim3(256), 0, st, ev0, ev1, a); break;
+    case 4: launch_kernel(combine_kernel<VPL, 4>, dim3(grid), dim3(256), 0, st, ev0, ev1, a); break;
+    case 6: launch_kernel(combine_kernel<VPL, 6>, dim3(grid), dim3(256), 0, st, ev0, ev1, a); break;
+    case 8: launch_kernel(combine_kernel<VPL, 8>, dim3(grid), dim3(256), 0, st, ev0, ev1, a); break;
+    default: launch_kernel(combine_kernel<VPL, 0>, dim3(grid), dim3(256), 0, st, ev0, ev1, a); break;
   }
 }
 
-int launch_combine(const CombineArgs &a, void *stream) {
+int launch_combine(const CombineArgs &a, void *stream, const LaunchTiming *timing) {
   hipStream_t st = (hipStream_t)stream;
   if (a.T <= 0) return 0;
   if ((a.H / 8 + 63) / 64 > 65535) return (int)hipErrorInvalidValue;
   switch (tuned_combine_vpl(a.H)) {
-    case 2: launch_combine_t<2>(a, st); break;
-    case 4: launch_combine_t<4>(a, st); break;
-    default: launch_combine_t<1>(a, st); break;
+    case 2: launch_combine_t<2>(a, st, timing); break;
+    case 4: launch_combine_t<4>(a, st, timing); break;
+    default: launch_combine_t<1>(a, st, timing); break;
   }
   return (int)hipGetLastError();
 }

@@ -257,24 +257,26 @@ static int tuned_dispatch_fp8_vpl(int H, int T) {
 }
 
 template <int VPL>
-static void launch_dispatch_bf16_t(DispatchArgs a, hipStream_t st) {
+static void launch_dispatch_bf16_t(DispatchArgs a, hipStream_t st, const LaunchTiming *tm) {
   const int nvec = a.H / 8;
   a.parts = (nvec + VPL * 64 - 1) / (VPL * 64);
   a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
   const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
-  hipLaunchKernelGGL(dispatch_bf16_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st, a);
+  launch_kernel(dispatch_bf16_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st,
+                tm ? tm->start : nullptr, tm ? tm->stop : nullptr, a);
 }
 
 template <int VPL>
-static void launch_dispatch_fp8_t(DispatchArgs a, hipStream_t st) {
+static void launch_dispatch_fp8_t(DispatchArgs a, hipStream_t st, const LaunchTiming *tm) {
   const int npair = a.H / 16;
   a.parts = (npair + VPL * 64 - 1) / (VPL * 64);
   a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
   const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
-  hipLaunchKernelGGL(dispatch_fp8_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st, a);
+  launch_kernel(dispatch_fp8_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st,
+                tm ? tm->start : nullptr, tm ? tm->stop : nullptr, a);
 }
 
-int launch_dispatch(const DispatchArgs &a, int payload, void *stream) {
+int launch_dispatch(const DispatchArgs &a, int payload, void *stream, const LaunchTiming *timing) {
   hipStream_t st = (hipStream_t)stream;
   // T == 0 with the ring on still launches one (idle) workgroup: it owes the zero-count atomics
   if (a.T <= 0 && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_NONE) return 0;
@@ -282,21 +284,21 @@ int launch_dispatch(const DispatchArgs &a, int payload, void *stream) {
     const int vpl = tuned_dispatch_vpl(a.H, a.T);
     if ((a.H / 8 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
     switch (vpl) {
-      case 1: launch_dispatch_bf16_t<1>(a, st); break;
-      case 2: launch_dispatch_bf16_t<2>(a, st); break;
-      case 4: launch_dispatch_bf16_t<4>(a, st); break;
-      case 7: launch_dispatch_bf16_t<7>(a, st); break;
-      case 8: launch_dispatch_bf16_t<8>(a, st); break;
-      case 14: launch_dispatch_bf16_t<14>(a, st); break;
-      default: launch_dispatch_bf16_t<16>(a, st); break;
+      case 1: launch_dispatch_bf16_t<1>(a, st, timing); break;
+      case 2: launch_dispatch_bf16_t<2>(a, st, timing); break;
+      case 4: launch_dispatch_bf16_t<4>(a, st, timing); break;
+      case 7: launch_dispatch_bf16_t<7>(a, st, timing); break;
+      case 8: launch_dispatch_bf16_t<8>(a, st, timing); break;
+      case 14: launch_dispatch_bf16_t<14>(a, st, timing); break;
+      default: launch_dispatch_bf16_t<16>(a, st, timing); break;
     }
   } else {
     const int vpl = tuned_dispatch_fp8_vpl(a.H, a.T);
     if ((a.H / 16 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
     switch (vpl) {
-      case 1: launch_dispatch_fp8_t<1>(a, st); break;
-      case 2: launch_dispatch_fp8_t<2>(a, st); break;
-      default: launch_dispatch_fp8_t<4>(a, st); break;
+      case 1: launch_dispatch_fp8_t<1>(a, st, timing); break;
+      case 2: launch_dispatch_fp8_t<2>(a, st, timing); break;
+      default: launch_dispatch_fp8_t<4>(a, st, timing); break;
     }
   }
   return (int)hipGetLastError();

@@ -4,6 +4,7 @@
 #ifndef EP_DEVICE_H_
 #define EP_DEVICE_H_
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdlib.h>
 
 #include "ep_internal.h"
@@ -161,6 +162,16 @@ EP_DEV int wave_inclusive_scan(int v, int lane) {
     if (lane >= d) v += u;
   }
   return v;
+}
+
+// One launch, with the kernel's own begin / end timestamps delivered into the caller's events when asked for.
+template <class Kernel, class Args>
+static inline void launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, void *ev_start,
+                                 void *ev_stop, const Args &a) {
+  if (ev_start || ev_stop)
+    hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, st, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, 0, a);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, a);
 }
 
 // Launch-shape overrides for experiments (EP_* environment variables).

@@ -21,6 +21,7 @@
 #include <mutex>
 #include <new>
 #include <thread>
+#include <utility>
 #include <vector>
 
 #include "ep_internal.h"
@@ -230,6 +231,11 @@ struct ep_handle {
   // proxy
   std::atomic<bool> stop{false};
   std::atomic<int64_t> expected_atomics{0};
+  // ep_profile: while on, ep_layout / ep_dispatch / ep_combine launch with a pair of events that receive their
+  // kernels' own begin and end timestamps; ep_profile_read adds the pairs up
+  bool profiling = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> timed[3];
+  std::vector<hipEvent_t> spare_events;  // made ahead of time (ep_profile) or handed back by ep_profile_read
   // what calls on capturing streams would have added to the two expected_* counts (ep_captured)
   std::atomic<int64_t> captured_atomics{0}, captured_drains{0};
   std::atomic<int> proxy_error{0};

@@ -165,9 +165,15 @@ struct RecvWaitArgs {
 };
 
 // Launchers implemented in the .hip files (layout, dispatch, combine, ht_ring, service).  All return a hipError_t as int.
-int launch_layout(const LayoutArgs &a, void *stream);
-int launch_dispatch(const DispatchArgs &a, int payload, void *stream);
-int launch_combine(const CombineArgs &a, void *stream);
+// Optional kernel-exact timing of a launch (ep_profile): HIP events that receive the begin timestamp of the
+// launch's first kernel and the end timestamp of its last one from the dispatch packets themselves, with no
+// extra work on the stream.  Events are hipEvent_t, kept as plain pointers here.
+struct LaunchTiming {
+  void *start, *stop;
+};
+int launch_layout(const LayoutArgs &a, void *stream, const LaunchTiming *timing = nullptr);
+int launch_dispatch(const DispatchArgs &a, int payload, void *stream, const LaunchTiming *timing = nullptr);
+int launch_combine(const CombineArgs &a, void *stream, const LaunchTiming *timing = nullptr);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
 int launch_barrier(const RingDev &ring, void *stream);
 int launch_fifo_stress(const RingDev &ring, int pushers, int per_pusher, unsigned long long *lat_sum,

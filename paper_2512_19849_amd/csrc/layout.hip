@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void layout_finish_kernel(LayoutArgs a) {
   a.dst_row[i] = a.expert_offset[e] + before + rank;
 }
 
-int launch_layout(const LayoutArgs &a, void *stream) {
+int launch_layout(const LayoutArgs &a, void *stream, const LaunchTiming *timing) {
   hipStream_t st = (hipStream_t)stream;
   // Workgroups are 1024 threads so that the last one has many hands for the scan, but only a few
   // wavefronts of each own a tile: the LDS atomics of one tile then compete with few others.
@@ -230,12 +230,14 @@ int launch_layout(const LayoutArgs &a, void *stream) {
   const int nblk = (a.ntiles + W - 1) / W;
   const int grid1 = a.S * (nblk > 0 ? nblk : 1);
   const size_t lds = (size_t)W * a.E * sizeof(unsigned long long);
-  hipLaunchKernelGGL(layout_count_kernel, dim3(grid1), dim3(kBlock), lds, st, b);
+  const long long n = (long long)a.S * a.T * a.K;  // entries the second kernel finishes
+  launch_kernel(layout_count_kernel, dim3(grid1), dim3(kBlock), lds, st, timing ? timing->start : nullptr,
+                timing && n <= 0 ? timing->stop : nullptr, b);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return (int)err;
-  const long long n = (long long)a.S * a.T * a.K;
   if (n > 0) {
-    hipLaunchKernelGGL(layout_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+    launch_kernel(layout_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, nullptr,
+                  timing ? timing->stop : nullptr, a);
     err = hipGetLastError();
   }
   return (int)err;

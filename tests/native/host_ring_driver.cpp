@@ -8,9 +8,9 @@
 #include <thread>
 #include <vector>
 namespace ep {
-int launch_layout(const LayoutArgs&, void*) { return 0; }
-int launch_dispatch(const DispatchArgs&, int, void*) { return 0; }
-int launch_combine(const CombineArgs&, void*) { return 0; }
+int launch_layout(const LayoutArgs&, void*, const LaunchTiming*) { return 0; }
+int launch_dispatch(const DispatchArgs&, int, void*, const LaunchTiming*) { return 0; }
+int launch_combine(const CombineArgs&, void*, const LaunchTiming*) { return 0; }
 int launch_fill_u32(uint32_t*, uint32_t, long long, void*) { return 0; }
 int tuned_dispatch_vpl(int, int) { return 1; }
 int tuned_combine_vpl(int) { return 1; }

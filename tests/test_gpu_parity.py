@@ -673,6 +673,56 @@ def test_ring_on_step_replays_from_a_hip_graph(epmod, oracle, mode_name):
             assert st["atomics_applied"] == 7 * cfg.E   # warm-up + three replays + three eager steps
 
 
+def test_profile_reports_the_kernels_own_durations(epmod, oracle):
+    """ep_profile: timed launches give the same results, their durations are positive, add up per call, are not
+    longer than what recorded events around the same calls see, and nothing is timed while profiling is off."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    cfg = g.config(4, S=1)
+    T = 1024
+    idx, w = g.routing_all(cfg, T)
+    x = g.activations(cfg, 0, T=T)
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    wrecv, _ = oracle.dispatch_bf16(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, idx.size)
+    wout = oracle.combine(wrecv, w[0], want_lay["dst_row"][0])
+    with _runner(epmod, cfg, T) as r:
+        d_idx, d_x, d_w = _dev(idx), bits_to_bf16(x), _dev(w[0])
+        recv = torch.zeros((idx.size, cfg.H), dtype=torch.bfloat16, device="cuda")
+        out = torch.zeros((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+
+        def step():
+            lay = r.layout(d_idx)
+            r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_CHUNK32)
+            r.combine(recv, d_w, lay.dst_row[0], out)
+            r.wait()
+            return lay
+
+        step()
+        torch.cuda.synchronize()
+        assert [epmod.ep_profile_read(r.h, c)[1] for c in (0, 1, 2)] == [0, 0, 0]
+        epmod.ep_profile(r.h, 8)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(3):
+            lay = step()
+        b.record()
+        epmod.ep_profile(r.h, False)
+        step()                                       # not timed
+        torch.cuda.synchronize()
+        assert np.array_equal(lay.numpy()["dst_row"], want_lay["dst_row"])
+        assert np.array_equal(bf16_to_bits(recv), wrecv) and np.array_equal(bf16_to_bits(out), wout)
+        total = 0.0
+        for call in (0, 1, 2):
+            ms, n = epmod.ep_profile_read(r.h, call, reset=False)
+            assert n == 3 and 0.003 < ms / n < 5.0, (call, ms, n)
+            assert epmod.ep_profile_read(r.h, call) == (ms, n)            # unchanged until reset
+            assert epmod.ep_profile_read(r.h, call) == (0.0, 0)
+            total += ms
+        assert total <= a.elapsed_time(b)            # the kernels ran inside the bracket
+        with pytest.raises(epmod.EPError):
+            epmod.ep_profile_read(r.h, 3)
+        assert r.stats()["device_error"] == 0
+
+
 def test_host_side_argument_errors(epmod):
     from paper_2512_19849_amd.runner import EPRunner
     with pytest.raises(epmod.EPError):

@@ -731,3 +731,14 @@ def test_capture_ledger_and_expectations_on_a_host_handle(ep):
         assert ep.ep_stats(h)["atomics_applied"] == 1
     finally:
         ep.ep_proxy_stop(h)
+
+
+def test_profile_calls_refuse_a_host_only_handle(ep):
+    h = _start(ep)
+    try:
+        with pytest.raises(ep.EPError):
+            ep.ep_profile(h, True)
+        with pytest.raises(ep.EPError):
+            ep.ep_profile_read(h, 0)
+    finally:
+        ep.ep_proxy_stop(h)
