@@ -117,6 +117,17 @@ def run_suite(args) -> int:
                     rr["dispatch_bf16_ring_off_us"] = timed(
                         lambda: r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=ep.EP_CMD_NONE))
                     rr["combine_us"] = timed(lambda: r.combine(recv, d_w, lay.dst_row[0], o))
+                    # the kernels' own durations (ep_profile), warm, beside the event-to-event figures above
+                    for call, label, fn in ((0, "layout", lambda: r.layout(d_idx)),
+                                            (1, "dispatch_bf16_ring_off",
+                                             lambda: r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=ep.EP_CMD_NONE)),
+                                            (2, "combine", lambda: r.combine(recv, d_w, lay.dst_row[0], o))):
+                        ep.ep_profile(r.h, 16)
+                        for _ in range(16):
+                            fn()
+                        ep.ep_profile(r.h, False)
+                        ms, n = ep.ep_profile_read(r.h, call)
+                        rr[f"{label}_kernel_us"] = round(ms / n * 1e3, 2)
                     if small:
                         rr["layout_cold_us"] = timed(lambda: r.layout(d_idx), cold=True)
                         rr["dispatch_bf16_ring_off_cold_us"] = timed(
