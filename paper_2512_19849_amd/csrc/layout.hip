@@ -215,8 +215,139 @@ __global__ __launch_bounds__(256) void layout_finish_kernel(LayoutArgs a) {
   a.dst_row[i] = a.expert_offset[e] + before + rank;
 }
 
+// ------------------------------------------------- small routing tables: one launch
+// A dozen flat tiles (768 tokens over all sources - a low-latency decode step) fit one workgroup:
+// wave f owns tile f, the bit masks of all tiles stay in LDS, one thread per expert walks the tiles
+// for the prefixes, and every wave finishes its own entries.  Nothing goes through memory between
+// the steps, which for such sizes is most of what the two kernels above spend (their floor is the
+// chain of round trips between them, about 12 us whatever the size).
+constexpr int kSmallTiles = 16;
+
+__global__ __launch_bounds__(1024) void layout_small_kernel(LayoutArgs a) {
+  extern __shared__ unsigned long long q_lds[];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int E = a.E, K = a.K, F = a.S * a.ntiles;
+  unsigned long long *mask = q_lds;                                         // [F][E]
+  unsigned short *pre = (unsigned short *)(q_lds + (size_t)kSmallTiles * E);  // [F][E] entries of e in earlier tiles
+  int *s_off = (int *)(pre + (size_t)kSmallTiles * E);                      // [E + 1]
+  int *s_tot = s_off + E + 1;                                               // [E]
+  for (int i = tid; i < F * E; i += blockDim.x) mask[i] = 0ull;
+  __syncthreads();
+
+  const int f = wave, s = f < F ? f / a.ntiles : 0, tile = f < F ? f - s * a.ntiles : 0;
+  const int t = tile * kLayoutTile + lane;
+  const bool active = f < F && t < a.T;
+  const size_t ebase = ((size_t)s * a.T + (active ? t : 0)) * K;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int ev[8], rk[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) ev[k] = (active && k < K) ? a.idx[ebase + k] : -1;
+  if (f < F) {  // (wave-uniform)
+    unsigned long long *m = mask + (size_t)f * E;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int e = ev[k];
+      bool pend = e >= 0 && e < E;
+      if (!pend && e != -1) dev_set_error(a.error, EP_EBOUNDS);
+      // the two most common experts of the wave are written by one lane each (see the count kernel)
+#pragma unroll
+      for (int round = 0; round < 2; ++round) {
+        const unsigned long long pm = __ballot(pend);
+        if (pm == 0) break;
+        const int leader = __builtin_ctzll(pm);
+        const int e0 = __builtin_amdgcn_readlane(e, leader);
+        const unsigned long long same = __ballot(pend && e == e0);
+        if (lane == leader) atomicOr(&m[e0], same);
+        pend = pend && e != e0;
+      }
+      if (pend) atomicOr(&m[e], 1ull << lane);
+    }
+  }
+  __syncthreads();
+  if (f < F) {
+    const unsigned long long *m = mask + (size_t)f * E;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) rk[k] = (ev[k] >= 0 && ev[k] < E) ? __popcll(m[ev[k]] & below) : 0;
+  }
+  // exclusive prefix over the flat tiles, one thread per expert; counts per source on the way
+  for (int e = tid; e < E; e += blockDim.x) {
+    int run = 0, src_first = 0;
+    for (int g = 0; g < F; ++g) {
+      if (g > 0 && g % a.ntiles == 0) {
+        a.count[(size_t)(g / a.ntiles - 1) * E + e] = run - src_first;
+        src_first = run;
+      }
+      pre[(size_t)g * E + e] = (unsigned short)run;
+      run += __popcll(mask[(size_t)g * E + e]);
+    }
+    a.count[(size_t)(a.S - 1) * E + e] = run - src_first;
+    s_tot[e] = run;
+    a.expert_total[e] = run;
+  }
+  __syncthreads();
+  if (wave == 0) {  // exclusive scan over experts: 64 lanes x contiguous runs
+    const int per = (E + 63) / 64;
+    const int lo = min(E, lane * per), hi = min(E, lo + per);
+    int sum = 0;
+    for (int i = lo; i < hi; ++i) sum += s_tot[i];
+    const int incl = wave_inclusive_scan(sum, lane);
+    int run = incl - sum;
+    for (int i = lo; i < hi; ++i) {
+      s_off[i] = run;
+      a.expert_offset[i] = run;
+      run += s_tot[i];
+    }
+    if (lane == 63) {
+      s_off[E] = incl;
+      a.expert_offset[E] = incl;
+    }
+  }
+  __syncthreads();
+  if (active) {
+    const unsigned short *bp = pre + (size_t)f * E, *fp = pre + (size_t)s * a.ntiles * E;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (k < K) {
+        const int e = ev[k];
+        if (e >= 0 && e < E) {
+          const int before = bp[e];
+          a.slot[ebase + k] = before - (int)fp[e] + rk[k];
+          a.dst_row[ebase + k] = s_off[e] + before + rk[k];
+        } else {
+          a.slot[ebase + k] = -1;
+          a.dst_row[ebase + k] = -1;
+        }
+      }
+  }
+  for (int i = tid; i < a.S * E; i += blockDim.x) {
+    const int ss = i / E, e = i - ss * E;
+    a.base[i] = s_off[e] + (int)pre[(size_t)ss * a.ntiles * E + e];
+  }
+  for (int r = tid; r <= a.R; r += blockDim.x) {
+    const int o = s_off[r * a.E_loc];  // r == R reads the end sentinel s_off[E]
+    a.rank_offset[r] = o;
+    if (r < a.R) a.rank_total[r] = s_off[(r + 1) * a.E_loc] - o;
+  }
+}
+
+// LDS bytes of the one-launch form, or 0 when the shape does not fit it.
+static size_t small_layout_lds(const LayoutArgs &a) {
+  const long long F = (long long)a.S * a.ntiles;
+  // measured on MI355X (E = 256, top-8): 4.3 us against 11.7 for one tile, 8.5 / 15.7 for 4, 11.3 / 15.4 for 8,
+  // 13.7 / 16.0 for 12; with all 16 waves busy the LDS atomics of the tiles slow each other down and
+  // nothing is gained (16.5 / 15.8)
+  if (a.T <= 0 || a.K > 8 || F <= 0 || F > 12) return 0;
+  const size_t bytes = (size_t)kSmallTiles * a.E * (8 + 2) + (size_t)(2 * a.E + 1) * 4;
+  return bytes <= 64 * 1024 ? bytes : 0;
+}
+
 int launch_layout(const LayoutArgs &a, void *stream, const LaunchTiming *timing) {
   hipStream_t st = (hipStream_t)stream;
+  if (const size_t lds = env_int("EP_LAYOUT_SMALL", 1) ? small_layout_lds(a) : 0) {
+    launch_kernel(layout_small_kernel, dim3(1), dim3(1024), lds, st, timing ? timing->start : nullptr,
+                  timing ? timing->stop : nullptr, a);
+    return (int)hipGetLastError();
+  }
   // Workgroups are 1024 threads so that the last one has many hands for the scan, but only a few
   // wavefronts of each own a tile: the LDS atomics of one tile then compete with few others.
   const int kBlock = 1024;

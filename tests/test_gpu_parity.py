@@ -72,6 +72,40 @@ def test_layout_special_shapes(epmod, oracle):
             _check_layout(oracle, lay.numpy(), idx, 16, 4)
 
 
+@pytest.mark.parametrize("one_launch", ["1", "0"])
+def test_layout_small_tables_both_forms(epmod, oracle, one_launch, monkeypatch):
+    """Routing tables of up to a dozen 64-token tiles take a one-launch, one-workgroup form of the layout, larger
+    ones the two-kernel form: shapes on both sides of that line (sources x tiles = 12 / 13, ragged last tiles,
+    several sources with few tiles each, 384 experts = the most the one-launch form holds, masked and fully masked
+    entries, one expert for everybody), each with the one-launch form allowed and switched off."""
+    monkeypatch.setenv("EP_LAYOUT_SMALL", one_launch)
+    rng = np.random.default_rng(12)
+    for (S, T, K, E, R, maskp) in [(1, 768, 8, 256, 16, 0.0), (1, 769, 8, 256, 16, 0.0), (4, 130, 3, 24, 4, 0.2),
+                                   (5, 130, 3, 24, 4, 0.2), (12, 64, 2, 16, 4, 0.0), (13, 1, 1, 4, 2, 0.0),
+                                   (1, 700, 8, 384, 8, 0.5), (1, 640, 5, 392, 8, 0.0), (2, 333, 7, 64, 64, 1.0),
+                                   (3, 200, 1, 1, 1, 0.1), (1, 1, 8, 8, 1, 0.0)]:
+        idx = np.stack([np.stack([rng.permutation(E)[:K] for _ in range(T)]) for _ in range(S)]).astype(np.int32)
+        if maskp:
+            idx = g.mask_random(idx, maskp, seed=S * 100 + T)
+        cfg = g.EPConfig("small", T=T, H=128, E=E, K=K, R=R, S=S)
+        with _runner(epmod, cfg) as r:
+            for rep in range(2):
+                lay = r.layout(_dev(idx))
+                torch.cuda.synchronize()
+                _check_layout(oracle, lay.numpy(), idx, E, R)
+            assert r.stats()["device_error"] == 0
+    # an expert id out of range is reported by whichever form runs, and the entry is dropped
+    cfg = g.EPConfig("small", T=100, H=128, E=8, K=2, R=2, S=1)
+    idx = np.stack([rng.permutation(8)[:2] for _ in range(100)]).astype(np.int32)[None]
+    idx[0, 41, 1] = 8
+    with _runner(epmod, cfg) as r:
+        lay = r.layout(_dev(idx))
+        torch.cuda.synchronize()
+        got = lay.numpy()
+        assert got["slot"][0, 41, 1] == -1 and got["dst_row"][0, 41, 1] == -1
+        assert r.stats()["device_error"] == epmod.EP_EBOUNDS
+
+
 # ---------------------------------------------------------- dispatch bf16
 def _dispatch_case(epmod, oracle, cfg, T, mask, cmd_mode, rank_filter=-1, src=0, extra_rows=3, proxy_writes=False,
                    extra_flags=0, **kw):
