@@ -371,7 +371,8 @@ int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx);
  * reset != 0.  Launches on a capturing stream are not timed.  on = 0 switches
  * profiling off; on = n >= 1 switches it on and makes sure n pairs of events are
  * at hand, so that up to n timed launches create none (n <= 65536).  Events are
- * reused after a read with reset and freed when the handle stops. */
+ * reused after a read with reset and freed when the handle stops; at most 65536
+ * unread launches per call are kept, later ones run untimed. */
 int ep_profile(ep_handle *h, int32_t on);
 int ep_profile_read(ep_handle *h, int32_t call, double *total_ms, int32_t *launches, int32_t reset);
 

@@ -122,7 +122,7 @@ bool make_spare_events(ep_handle *h, size_t n) {
 }
 
 bool timing_for(ep_handle *h, int which, void *stream, LaunchTiming *t) {
-  if (!h->profiling) return false;
+  if (!h->profiling || h->timed[which].size() >= 65536) return false;  // (never read: stop collecting)
   hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
   if (hipStreamIsCapturing((hipStream_t)stream, &st) != hipSuccess) (void)hipGetLastError();
   if (st == hipStreamCaptureStatusActive) return false;
