@@ -281,6 +281,8 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
   for (int i = 0; i < h->nthreads; ++i) {
     ProxyThread &P = h->threads[i];
     P.tid = i;
+    P.plain_writes = cfg->max_outstanding == 0 && cfg->pack_rows <= 1 && cfg->reorder_window == 0 &&
+                     !(cfg->flags & (EP_FLAG_LOG_EVENTS | EP_FLAG_SENDER_FENCE));
     for (int c = i; c < C; c += h->nthreads) {
       P.channels.push_back(c);
       P.head.push_back(0);

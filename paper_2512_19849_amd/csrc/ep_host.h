@@ -134,6 +134,9 @@ struct Outbound {
 
 struct alignas(64) ProxyThread {
   int tid = 0;
+  // no pacing, packing, reordering transport, sender-side fence or event log configured: a Write whose
+  // payload is already in place has nothing between its command and its arrival notice
+  bool plain_writes = false;
   std::thread th;
   std::vector<int> channels;
   std::vector<uint64_t> head;  // consumer index per owned channel (private copy)

@@ -274,6 +274,20 @@ void send_msg(ep_handle *h, ProxyThread &P, const Outbound &m) {
   launch_msg(h, P, m);
 }
 
+// A notice that needs no copy before it: with nothing configured between the two halves it is
+// delivered on the spot, else it takes the general way out (pacing, transport, ...).
+inline void send_notice(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
+  if (P.plain_writes) {
+    ++P.in_flight[ev.dst_rank];  // (deliver takes it off again)
+    if (P.max_in_flight.load(std::memory_order_relaxed) == 0) P.max_in_flight.store(1, std::memory_order_relaxed);
+    deliver(h, P, ev);
+    return;
+  }
+  Outbound m;
+  m.notice = ev;
+  send_msg(h, P, m);
+}
+
 // Sender-side fence (the alternative weighed in Section 3.3, "Where to enforce the delivery
 // semantics"): a count Atomic leaves only when the rows it vouches for have completed.  Sender and
 // receiver halves share the arrival counts, so "completed" is the arrival of the rows' notices.
@@ -380,6 +394,24 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       bump(P.writes, 1);
       bump(P.write_bytes, len);
       bump(P.write_rows, rows);
+      if (P.plain_writes && !dbase) {
+        // The common case, taken out of the general path below (which does the same in more steps):
+        // the payload is in place, nothing is configured between the sender half and the receiver
+        // half, so the Write's arrival is counted here and now, and count Atomics that were waiting
+        // for it are applied.
+        bump(P.write_msgs, 1);
+        if (P.max_in_flight.load(std::memory_order_relaxed) == 0) P.max_in_flight.store(1, std::memory_order_relaxed);
+        const uint32_t e = dr * (uint32_t)h->E_loc + le;
+        const size_t key = (size_t)src * c.num_experts + e;
+        P.seen[key] += (int32_t)rows;
+        std::deque<int32_t> &q = P.parked[key];
+        while (!q.empty() && P.seen[key] >= q.front()) {
+          const int32_t v = q.front();
+          q.pop_front();
+          apply_atomic(h, P, src, e, v);
+        }
+        break;
+      }
       // Without registered heaps the payload already sits in the destination partition (the kernel
       // stored it) and what remains of the peer write is its arrival notice; with them this thread
       // performs the write and the notice follows its completion.
@@ -441,9 +473,7 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
         release_sender_parked(h, P, src, dr, le, key);
         break;
       }
-      Outbound m;
-      m.notice = WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint8_t)dr, 0};
-      send_msg(h, P, m);
+      send_notice(h, P, WireEvent{(1u << 31) | (le << 19) | w1, (uint16_t)src, (uint8_t)dr, 0});
       break;
     }
     case EP_OP_ORDERED_WRITE: {
@@ -461,6 +491,11 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
       bump(P.writes, 1);
       bump(P.write_bytes, len);
       bump(P.write_rows, rows);
+      if (!dbase) {  // the kernel placed the rows: only the notice travels
+        bump(P.write_msgs, 1);
+        send_notice(h, P, WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 1});
+        break;
+      }
       Outbound m;
       m.notice = WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 1};
       m.nseg = dbase ? 1 : 0;  // packed chunk: same offset on both sides
@@ -479,9 +514,7 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
         return;
       }
       bump(P.atomics, 1);
-      Outbound m;
-      m.notice = WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | w1, (uint16_t)src, (uint8_t)dr, 1};
-      send_msg(h, P, m);
+      send_notice(h, P, WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | w1, (uint16_t)src, (uint8_t)dr, 1});
       break;
     }
     case EP_OP_RING: {
@@ -507,10 +540,8 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
         bump(P.writes, 1);
         bump(P.write_bytes, len);
         bump(P.write_rows, rows);
-        Outbound m;
-        m.notice = WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 2, (uint16_t)slice};
         bump(P.write_msgs, 1);
-        send_msg(h, P, m);
+        send_notice(h, P, WireEvent{((w2 & 0xFFFFu) << 15) | rows, (uint16_t)src, (uint8_t)dr, 2, (uint16_t)slice});
       } else {
         const uint32_t value = w1 & 0x3FFFFFFFu;
         if (value > 0x7FFFu) {
@@ -518,10 +549,8 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
           return;
         }
         bump(P.atomics, 1);
-        Outbound m;
-        m.notice = WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | value, (uint16_t)src, (uint8_t)dr,
-                             (uint8_t)(kind == EP_RING_TAIL ? 2 : 3), (uint16_t)slice};
-        send_msg(h, P, m);
+        send_notice(h, P, WireEvent{(1u << 31) | ((w2 & 0xFFFFu) << 15) | value, (uint16_t)src, (uint8_t)dr,
+                                    (uint8_t)(kind == EP_RING_TAIL ? 2 : 3), (uint16_t)slice});
       }
       break;
     }
