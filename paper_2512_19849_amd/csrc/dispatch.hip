@@ -64,8 +64,8 @@ EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
   if (mode == EP_CMD_PER_TOKEN) {
     const unsigned long long so = (unsigned long long)t * a.row_bytes;
     const unsigned long long dof = (unsigned long long)m.row * a.row_bytes;
-    ring_push(a.ring, ch, cmd_w0(EP_OP_WRITE, a.src, dr, le), a.row_bytes >> 4, (unsigned)(so >> 4),
-              (unsigned)(dof >> 4));
+    ring_push_grouped(a.ring, ch, cmd_w0(EP_OP_WRITE, a.src, dr, le), a.row_bytes >> 4, (unsigned)(so >> 4),
+                      (unsigned)(dof >> 4));
     finished_rows = 1;
   } else {
     const int slot = m.row - a.base[e];

@@ -29,10 +29,39 @@ EP_DEV int lane_id() { return threadIdx.x & 63; }
 // room using the device-resident cached copy of the head and re-reading the
 // host copy over PCIe only when that cache says "full", then publish the
 // 16-byte command with a single store.  Returns Idx, or ~0 after a timeout.
+EP_DEV unsigned long long ring_publish(const RingDev &r, unsigned c, unsigned long long idx, unsigned w0, unsigned w1,
+                                       unsigned w2, unsigned w3);
 EP_DEV unsigned long long ring_push(const RingDev &r, unsigned c, unsigned w0, unsigned w1,
                                     unsigned w2, unsigned w3) {
   const unsigned long long idx =
       __hip_atomic_fetch_add(&r.tail[c], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return ring_publish(r, c, idx, w0, w1, w2, w3);
+}
+
+// Push for the case where many lanes of a wave push at once (one command per row): lanes that aim at
+// the same channel share ONE atomic on its tail - the first of them reserves a run of Idx for all,
+// the others take their place in the run.  Atomics on one address serialise in the L2, and a
+// per-token dispatch sends tens of thousands of commands through a handful of tails.
+EP_DEV unsigned long long ring_push_grouped(const RingDev &r, unsigned c, unsigned w0, unsigned w1, unsigned w2,
+                                            unsigned w3) {
+  const int me = lane_id();
+  unsigned long long same = 0ull;
+  for (unsigned long long m = __ballot(true); m; m &= m - 1) {
+    const int j = __builtin_ctzll(m);
+    if ((unsigned)__builtin_amdgcn_readlane((int)c, j) == c) same |= 1ull << j;
+  }
+  const int leader = __builtin_ctzll(same);
+  unsigned long long base = 0ull;
+  if (me == leader)
+    base = __hip_atomic_fetch_add(&r.tail[c], (unsigned long long)__popcll(same), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
+  base = ((unsigned long long)(unsigned)__shfl((int)(base >> 32), leader) << 32) | (unsigned)__shfl((int)base, leader);
+  return ring_publish(r, c, base + (unsigned long long)__popcll(same & ((1ull << me) - 1ull)), w0, w1, w2, w3);
+}
+
+// Second half of a Push: wait for room for the reserved Idx, then publish the command.
+EP_DEV unsigned long long ring_publish(const RingDev &r, unsigned c, unsigned long long idx, unsigned w0, unsigned w1,
+                                       unsigned w2, unsigned w3) {
   const unsigned gen = (((unsigned)(idx >> r.log2_entries)) & 1u) ^ 1u;
   const u32x4 v = {w0 | (gen << 31), w1, w2, w3 | (gen << 31)};
   u32x4 *slot = (u32x4 *)r.slots + (size_t)c * r.entries + (size_t)(idx & (r.entries - 1));
