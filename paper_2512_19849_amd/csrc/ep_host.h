@@ -176,10 +176,13 @@ struct alignas(64) ProxyThread {
   std::vector<uint32_t> ring_next;
   std::vector<ReorderBuf> ring_early;
   uint64_t rng = 0;
+  // What ep_wait spins on, in a cache line of its own: the waiting thread re-reads it all the time, and
+  // anything the owner writes per command in the same line would miss on every write.
+  alignas(64) std::atomic<uint64_t> applied{0}, drains{0};
   // statistics (written by the owner thread only, read racy-but-atomically)
-  std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, drains{0}, write_bytes{0}, write_rows{0},
-      applied{0}, deferred{0}, rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0}, barriers{0},
-      copy_batches{0}, copied_bytes{0}, write_msgs{0}, paced{0}, max_in_flight{0}, sender_held{0};
+  alignas(64) std::atomic<uint64_t> cmds{0}, writes{0}, atomics{0}, write_bytes{0}, write_rows{0}, deferred{0},
+      rejected{0}, first_poll_ns{0}, last_apply_ns{0}, ordered_parked{0}, barriers{0}, copy_batches{0},
+      copied_bytes{0}, write_msgs{0}, paced{0}, max_in_flight{0}, sender_held{0};
   std::mutex log_mu;
   std::vector<uint32_t> cmd_log, event_log;
 };
