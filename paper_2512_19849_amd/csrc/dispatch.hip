@@ -52,6 +52,16 @@ EP_DEV void emit_leading_atomics(const DispatchArgs &a, int lane) {
 // an expert pushes the Write for the run.  Whoever completes the expert pushes
 // its count Atomic (Section 3.3: the receiver holds it until that many rows
 // arrived).  The scratch counters return to zero by themselves.
+// `rows` more rows of expert e (c in all) have been handed to the channel; whoever hands over the
+// last one pushes the expert's count Atomic.
+EP_DEV void account_rows(const DispatchArgs &a, int e, int c, int rows) {
+  const int done = __hip_atomic_fetch_add(a.expert_done + e, rows, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + rows;
+  if (done == c) {
+    __hip_atomic_store(a.expert_done + e, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!(a.cmd_mode & EP_CMD_ATOMICS_FIRST)) push_count_atomic(a, e, c);
+  }
+}
+
 EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
   const int e = m.e;
   const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
@@ -99,13 +109,31 @@ EP_DEV void emit_row_cmds(const DispatchArgs &a, const TokenMeta &m, int t) {
       finished_rows = csize;
     }
   }
-  if (finished_rows) {
-    const int done = __hip_atomic_fetch_add(a.expert_done + e, finished_rows, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT) + finished_rows;
-    if (done == c) {
-      __hip_atomic_store(a.expert_done + e, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (!(a.cmd_mode & EP_CMD_ATOMICS_FIRST)) push_count_atomic(a, e, c);
-    }
+  if (finished_rows) account_rows(a, e, c, finished_rows);
+}
+
+// One command per row, several tokens per workgroup: the tokens' (expert, row) pairs meet in LDS
+// and the first wave pushes for all of them, sorted by channel, so that the commands of a channel
+// leave as one run of consecutive slots written by neighbouring lanes (see ring_push_sorted).
+EP_DEV void emit_block_cmds(const DispatchArgs &a, const TokenMeta &m, int part, int wave, int lane) {
+  extern __shared__ u32x4 s_dyn[];
+  int2 *s_pairs = (int2 *)s_dyn;  // [tokens_per_block][K], then the 2 KB of ring_push_sorted
+  if (part == 0 && lane < a.K) s_pairs[(wave / a.parts) * a.K + lane] = make_int2(m.valid ? m.e : -1, m.row);
+  __syncthreads();  // every wave has waited for its own stores before it came here
+  if (wave != 0) return;
+  const int n = a.tokens_per_block * a.K;
+  u32x4 *scratch = (u32x4 *)(s_pairs + ((n + 1) & ~1));
+  for (int i0 = 0; i0 < n; i0 += 64) {
+    const int i = i0 + lane;
+    const int2 p = i < n ? s_pairs[i] : make_int2(-1, -1);
+    const bool active = p.x >= 0;
+    const int e = active ? p.x : 0;
+    const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
+    const unsigned long long so = (unsigned long long)(blockIdx.x * a.tokens_per_block + i / a.K) * a.row_bytes;
+    const unsigned long long dof = (unsigned long long)p.y * a.row_bytes;
+    ring_push_sorted(a.ring, active, (unsigned)e % a.ring.channels, cmd_w0(EP_OP_WRITE, a.src, dr, le),
+                     a.row_bytes >> 4, (unsigned)(so >> 4), (unsigned)(dof >> 4), scratch);
+    if (active) account_rows(a, e, a.count[e], 1);
   }
 }
 
@@ -150,8 +178,12 @@ __global__ void dispatch_bf16_kernel(DispatchArgs a) {
   }
   if (!ring_on) return;
   wait_for_own_stores();  // the rows are in memory before a counter or command mentions them
-  if (a.parts > 1) __syncthreads();
-  if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  if (a.block_cmds) {
+    emit_block_cmds(a, m, part, wave, lane);
+  } else {
+    if (a.parts > 1) __syncthreads();
+    if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  }
   if (a.cmd_mode & EP_CMD_DRAIN) emit_drain(a, lane);
 }
 
@@ -203,8 +235,12 @@ __global__ void dispatch_fp8_kernel(DispatchArgs a) {
   }
   if (!ring_on) return;
   wait_for_own_stores();
-  if (a.parts > 1) __syncthreads();
-  if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  if (a.block_cmds) {
+    emit_block_cmds(a, m, part, wave, lane);
+  } else {
+    if (a.parts > 1) __syncthreads();
+    if (part == 0 && m.valid) emit_row_cmds(a, m, t);
+  }
   if (a.cmd_mode & EP_CMD_DRAIN) emit_drain(a, lane);
 }
 
@@ -256,13 +292,28 @@ static int tuned_dispatch_fp8_vpl(int H, int T) {
   return split_for(H / 16, T, c, 3);
 }
 
+// One command per row: as many tokens per workgroup as 16 waves hold (their commands are pushed
+// together, see emit_block_cmds).  Returns the dynamic LDS bytes of the launch.
+static size_t block_cmds_setup(DispatchArgs &a) {
+  a.block_cmds = 0;
+  if ((a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_PER_TOKEN) return 0;
+  int waves = env_int("EP_PER_TOKEN_WAVES", 16);
+  if (waves < 4 || waves > 16) waves = 16;
+  const int tpb = waves / a.parts;
+  if (tpb < 2) return 0;
+  a.tokens_per_block = tpb;
+  a.block_cmds = 1;
+  return (size_t)((tpb * a.K + 1) & ~1) * sizeof(int2) + 2048;
+}
+
 template <int VPL>
 static void launch_dispatch_bf16_t(DispatchArgs a, hipStream_t st, const LaunchTiming *tm) {
   const int nvec = a.H / 8;
   a.parts = (nvec + VPL * 64 - 1) / (VPL * 64);
   a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
+  const size_t lds = block_cmds_setup(a);
   const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
-  launch_kernel(dispatch_bf16_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st,
+  launch_kernel(dispatch_bf16_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), lds, st,
                 tm ? tm->start : nullptr, tm ? tm->stop : nullptr, a);
 }
 
@@ -271,8 +322,9 @@ static void launch_dispatch_fp8_t(DispatchArgs a, hipStream_t st, const LaunchTi
   const int npair = a.H / 16;
   a.parts = (npair + VPL * 64 - 1) / (VPL * 64);
   a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
+  const size_t lds = block_cmds_setup(a);
   const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
-  launch_kernel(dispatch_fp8_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), 0, st,
+  launch_kernel(dispatch_fp8_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), lds, st,
                 tm ? tm->start : nullptr, tm ? tm->stop : nullptr, a);
 }
 

@@ -59,6 +59,47 @@ EP_DEV unsigned long long ring_push_grouped(const RingDev &r, unsigned c, unsign
   return ring_publish(r, c, base + (unsigned long long)__popcll(same & ((1ull << me) - 1ull)), w0, w1, w2, w3);
 }
 
+// Push for a whole wave whose lanes hold one command each (or none: `active`), called by all 64
+// lanes together.  Runs of Idx are reserved per channel as in ring_push_grouped; then the commands
+// change lanes through LDS (`scratch`, 2 KB) so that lane order is (channel, Idx) order: neighbouring
+// lanes store neighbouring slots, and the memory pipeline turns the slots of one 64-byte line into one
+// write.  A line of host memory that the proxy is polling costs the PCIe root a round of coherence
+// traffic per write that lands in it, whatever the size of the write.
+EP_DEV void ring_push_sorted(const RingDev &r, bool active, unsigned c, unsigned w0, unsigned w1, unsigned w2,
+                             unsigned w3, u32x4 *scratch) {
+  const int me = lane_id();
+  const unsigned long long act = __ballot(active);
+  unsigned long long same = 0ull;
+  int less = 0;
+  for (unsigned long long m = act; m;) {  // once per distinct channel
+    const unsigned cj = (unsigned)__builtin_amdgcn_readlane((int)c, __builtin_ctzll(m));
+    const unsigned long long mj = __ballot(active && c == cj);
+    if (cj == c) same = mj;
+    if (cj < c) less += __popcll(mj);
+    m &= ~mj;
+  }
+  const int leader = (active && same) ? __builtin_ctzll(same) : 0;
+  const int before = __popcll(same & ((1ull << me) - 1ull));
+  unsigned long long base = 0ull;
+  if (active && me == leader)
+    base = __hip_atomic_fetch_add(&r.tail[c], (unsigned long long)__popcll(same), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
+  base = ((unsigned long long)(unsigned)__shfl((int)(base >> 32), leader) << 32) | (unsigned)__shfl((int)base, leader);
+  if (active) {
+    const unsigned long long idx = base + (unsigned long long)before;
+    scratch[less + before] = u32x4{w0, w1, w2, w3};
+    scratch[64 + less + before] = u32x4{c, (unsigned)idx, (unsigned)(idx >> 32), 0u};
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  if (me < __popcll(act)) {
+    const u32x4 w = scratch[me], q = scratch[64 + me];
+    ring_publish(r, q.x, ((unsigned long long)q.z << 32) | q.y, w.x, w.y, w.z, w.w);
+  }
+  __builtin_amdgcn_wave_barrier();  // (the next round writes the scratch again)
+}
+
 // Second half of a Push: wait for room for the reserved Idx, then publish the command.
 EP_DEV unsigned long long ring_publish(const RingDev &r, unsigned c, unsigned long long idx, unsigned w0, unsigned w1,
                                        unsigned w2, unsigned w3) {

@@ -176,6 +176,8 @@ struct alignas(64) ProxyThread {
   std::vector<uint32_t> ring_next;
   std::vector<ReorderBuf> ring_early;
   uint64_t rng = 0;
+  uint64_t applied_unpublished = 0;  // atomics applied but not yet added to `applied` (owner thread only)
+  bool stamp_apply = false;          // last_apply_ns is due
   // What ep_wait spins on, in a cache line of its own: the waiting thread re-reads it all the time, and
   // anything the owner writes per command in the same line would miss on every write.
   alignas(64) std::atomic<uint64_t> applied{0}, drains{0};

@@ -68,6 +68,7 @@ struct DispatchArgs {
   uint32_t row_bytes;      // bytes of one token in a message
   int32_t parts;           // wavefronts per token
   int32_t tokens_per_block;
+  int32_t block_cmds;      // the workgroup's first wave pushes the commands of all its tokens
   int32_t chunks_per_expert;
   int32_t *chunk_cnt;      // scratch [E * chunks_per_expert], zero between calls
   int32_t *expert_done;    // scratch [E], zero between calls

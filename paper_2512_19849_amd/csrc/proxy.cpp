@@ -21,8 +21,8 @@ void apply_atomic(ep_handle *h, ProxyThread &P, uint32_t src, uint32_t e, int32_
   __atomic_store_n(&h->recv_count[key], value, __ATOMIC_RELEASE);
   __atomic_store_n(&h->recv_flag[key], value + 1, __ATOMIC_RELEASE);
   log_event(h, P, 3, src, e, (uint32_t)value);
-  P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
-  P.applied.store(P.applied.load(std::memory_order_relaxed) + 1, std::memory_order_release);
+  ++P.applied_unpublished;  // (ep_wait's counter and the clock are brought up to date once per polled batch)
+  P.stamp_apply = true;
   if (!P.sender_parked.empty()) {  // sender-side fence: the next Atomic of this expert may go now
     P.atomic_flying[key] = 0;
     if (!P.sender_parked[key].empty())
@@ -91,7 +91,7 @@ void apply_ordered(ep_handle *h, ProxyThread &P, size_t chan, const WireEvent &e
     const int32_t now = __atomic_load_n(&h->recv_tail[chan], __ATOMIC_RELAXED) + (int32_t)value;
     __atomic_store_n(&h->recv_tail[chan], now, __ATOMIC_RELEASE);
     log_event(h, P, 7, ev.src, ev.dst_rank, seq);
-    P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
+    P.stamp_apply = true;
   } else {
     log_event(h, P, 6, ev.src, ev.dst_rank, seq);
   }
@@ -136,7 +136,7 @@ void apply_ring(ep_handle *h, ProxyThread &P, size_t chan, const WireEvent &ev, 
   int32_t *ctr = (ev.ordered == 2 ? h->ring_tail : h->ring_head) + chan;
   __atomic_store_n(ctr, __atomic_load_n(ctr, __ATOMIC_RELAXED) + (int32_t)value, __ATOMIC_RELEASE);
   log_event(h, P, ev.ordered == 2 ? 12 : 13, ev.src, where, seq);
-  P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
+  P.stamp_apply = true;
 }
 
 void deliver_ring(ep_handle *h, ProxyThread &P, const WireEvent &ev) {
@@ -618,6 +618,20 @@ void process_cmd(ep_handle *h, ProxyThread &P, int fifo, uint32_t w0, uint32_t w
 }
 }  // namespace
 
+// The atomics applied since the last call become visible to ep_wait, and the statistics' clock of
+// the last application is set.  Once per polled batch rather than per atomic: the counter's cache
+// line is in the waiting thread's hands most of the time, and every store to it has to fetch it back.
+static inline void publish_applied(ProxyThread &P) {
+  if (P.stamp_apply) {
+    P.stamp_apply = false;
+    P.last_apply_ns.store(now_ns(), std::memory_order_relaxed);
+  }
+  if (P.applied_unpublished) {
+    P.applied.store(P.applied.load(std::memory_order_relaxed) + P.applied_unpublished, std::memory_order_release);
+    P.applied_unpublished = 0;
+  }
+}
+
 void proxy_main(ep_handle *h, ProxyThread *Pp) {
   ProxyThread &P = *Pp;
   const uint32_t mask = h->entries - 1;
@@ -646,6 +660,7 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
         // Pop: publish the new head where the GPU can read it
         P.head[ci] = hd;
         __atomic_store_n(&h->head[(size_t)ch * kHeadStride], hd, __ATOMIC_RELEASE);
+        publish_applied(P);
         any = true;
       }
     }
@@ -668,11 +683,15 @@ void proxy_main(ep_handle *h, ProxyThread *Pp) {
       flush_window(h, P);
       pump_held(h, P);
     }
+    publish_applied(P);  // (what arrivals from the transport or finished copies have released)
     if (any) {
       idle = 0;
       continue;
     }
-    if (!P.window.empty()) flush_window(h, P);  // nothing new: let in-flight immediates land
+    if (!P.window.empty()) {  // nothing new: let in-flight immediates land
+      flush_window(h, P);
+      publish_applied(P);
+    }
     if (P.held_total) continue;
     if (++idle < 4096) {
       _mm_pause();
