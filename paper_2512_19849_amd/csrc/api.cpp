@@ -491,7 +491,12 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
   }
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = timing_for(h, 1, stream, &tm);
-  return HIP_OK((hipError_t)launch_dispatch(a, payload, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
+  const bool ok = HIP_OK((hipError_t)launch_dispatch(a, payload, stream, timed ? &tm : nullptr));
+  const bool all_rows = ok && payload == EP_BF16 && dst_rank_filter < 0 && !(cmd_mode & EP_CMD_NO_PLACEMENT) && T > 0;
+  h->fresh_buf.store(all_rows ? d_recv : nullptr, std::memory_order_relaxed);
+  h->fresh_T.store(T, std::memory_order_relaxed);
+  h->fresh_stream.store(stream, std::memory_order_relaxed);
+  return ok ? EP_OK : EP_EHIP;
 }
 
 int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32_t *d_dst_row, int32_t T,
@@ -512,6 +517,16 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32
   a.K = h->cfg.top_k;
   a.H = h->cfg.hidden;
   a.error = h->ring.error;
+  a.fresh_from = T;
+  if (d_y && h->fresh_buf.exchange(nullptr, std::memory_order_relaxed) == d_y &&
+      h->fresh_T.load(std::memory_order_relaxed) == T && h->fresh_stream.load(std::memory_order_relaxed) == stream) {
+    // the dispatch kernel stored the tokens' rows in token order: the rows of the last tokens are what the
+    // memory-side cache (256 MB) still holds
+    const int64_t per_token = (int64_t)a.K * a.H * 2;
+    const int64_t budget = (int64_t)combine_fresh_mb() << 20;
+    const int64_t n = per_token > 0 ? budget / per_token : 0;
+    a.fresh_from = n >= T ? 0 : T - (int32_t)n;
+  }
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = timing_for(h, 2, stream, &tm);
   return HIP_OK((hipError_t)launch_combine(a, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
@@ -578,6 +593,7 @@ int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, con
   a.K = h->cfg.top_k;
   a.H = h->cfg.hidden;
   a.error = h->ring.error;
+  h->fresh_buf.store(nullptr, std::memory_order_relaxed);
   return HIP_OK((hipError_t)launch_combine_partial(a, stream)) ? EP_OK : EP_EHIP;
 }
 
@@ -708,6 +724,7 @@ int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, con
   a.waves_done = h->waves_done;
   a.fifo = h->ring;
   expect_more(h, stream, 0, c.num_channels);
+  h->fresh_buf.store(nullptr, std::memory_order_relaxed);
   return HIP_OK((hipError_t)launch_ht_ring(a, stream)) ? EP_OK : EP_EHIP;
 }
 

@@ -249,6 +249,13 @@ struct ep_handle {
   std::atomic<int> proxy_error{0};
   int nthreads = 0;
   ep::ProxyThread *threads = nullptr;
+  // What the last launch of this handle wrote, if it was a bf16 ep_dispatch of all its rows: the
+  // receive buffer, the token count and the stream.  An ep_combine that reads the same buffer for
+  // the same tokens on the same stream directly afterwards knows which rows are still in the
+  // memory-side cache (the last tokens') and reads those first, with cached loads.
+  std::atomic<const void *> fresh_buf{nullptr};
+  std::atomic<int32_t> fresh_T{0};
+  std::atomic<void *> fresh_stream{nullptr};
   uint64_t timeout_ns = 0;
 };
 

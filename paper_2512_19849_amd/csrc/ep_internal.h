@@ -86,6 +86,10 @@ struct CombineArgs {
   long long y_rows;
   int32_t T, K, H, parts;
   int *error;
+  // Tokens >= fresh_from had their rows written last, by the kernel that ran just before on this
+  // stream (ep_combine knows this when it follows ep_dispatch into the same buffer): those rows
+  // are read with cached loads and first, the rest with streaming loads.  fresh_from == T: none.
+  int32_t fresh_from;
 };
 
 struct DedupArgs {
@@ -190,5 +194,6 @@ int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void 
 // Tunables (read once from the environment, for sweeps): vectors per lane.
 int tuned_dispatch_vpl(int H, int T);
 int tuned_combine_vpl(int H);
+int combine_fresh_mb();  // bytes (MiB) of just-dispatched rows that ep_combine takes to be cache-resident
 
 }  // namespace ep

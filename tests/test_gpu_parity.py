@@ -508,6 +508,37 @@ def test_combine_parity(epmod, oracle, cid, T, mask):
         assert r.stats()["device_error"] == 0
 
 
+@pytest.mark.parametrize("fresh_mb", [0, 1, 4096])
+def test_combine_directly_after_dispatch_reads_the_fresh_rows_first(epmod, oracle, fresh_mb, monkeypatch):
+    """A combine that follows a bf16 dispatch into the same buffer walks the tokens backwards and reads the rows
+    of the last tokens with cached loads (none, some, or all of them, by the byte budget); a second combine of
+    the same inputs takes the plain order.  Both equal the oracle's sum, bit for bit."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    monkeypatch.setenv("EP_COMBINE_FRESH_MB", str(fresh_mb))
+    cfg = g.config(5, S=1)
+    T = 333                                                      # 333 x 8 x 8 KiB = 2.6 MiB of rows
+    idx, w = g.routing_all(cfg, T)
+    idx = g.mask_random(idx, 0.1, seed=77)
+    lay_want = oracle.layout(idx, cfg.E, cfg.R)
+    rows = int((idx >= 0).sum()) + 1
+    x = g.activations(cfg, 0, T=T)
+    want_recv, _ = oracle.dispatch_bf16(x, idx[0], lay_want["dst_row"][0], cfg.E_loc, rows, -1, fill=0)
+    with _runner(epmod, cfg, T) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
+        outs = [torch.full((T, cfg.H), 3.0, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+        r.dispatch(bits_to_bf16(x), d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_CHUNK32)
+        r.combine(recv, _dev(w[0]), lay.dst_row[0], outs[0])       # directly after the dispatch
+        r.combine(recv, _dev(w[0]), lay.dst_row[0], outs[1])       # nothing fresh any more
+        r.wait()
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_to_bits(recv), want_recv)
+        for out in outs:
+            assert _combine_check(oracle, bf16_to_bits(out), want_recv, w[0], lay_want["dst_row"][0], cfg.K) == 0
+        assert r.stats()["device_error"] == 0
+
+
 @pytest.mark.parametrize("K,vpl", [(1, 1), (3, 2), (5, 4), (6, 1), (8, 4), (2, 2), (4, 1)])
 def test_combine_generic_k_and_splits(epmod, oracle, K, vpl, monkeypatch):
     monkeypatch.setenv("EP_COMBINE_VPL", str(vpl))
