@@ -196,7 +196,13 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
  *   out[t,:] = bf16( sum_k w[t,k] * y[dst_row[t,k], :] )
  * fp32 accumulator starting at +0, k ascending, fused multiply-add, one final
  * round-to-nearest-even; k with dst_row == -1 are skipped.  d_y bf16
- * [y_rows,H]; d_topk_w fp32 [T,K]; d_dst_row int32 [T,K]; d_out bf16 [T,H]. */
+ * [y_rows,H]; d_topk_w fp32 [T,K]; d_dst_row int32 [T,K]; d_out bf16 [T,H].
+ * Performance only, never the result: when the call follows a bf16 ep_dispatch of
+ * all rows into d_y itself, for the same T, on the same stream and handle, with no
+ * other launch of the handle in between, the rows of the last tokens are taken to be
+ * still in the memory-side cache and are read first, with cached loads (how many:
+ * EP_COMBINE_FRESH_MB MiB worth, default 192, 0 = never); in every other case all
+ * rows are read with streaming loads in token order. */
 int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w,
                const int32_t *d_dst_row, int32_t T, int64_t y_rows,
                void *d_out, void *stream);
