@@ -172,6 +172,18 @@ def test_dispatch_bf16_every_row_split(epmod, oracle, vpl, monkeypatch):
     _dispatch_case(epmod, oracle, g.config(1), 33, 0.0, epmod.EP_CMD_PER_TOKEN)
 
 
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_per_token_commands_every_push_form(epmod, oracle, waves, monkeypatch):
+    """One command per row leaves through the push of the token's own wave (a workgroup that holds one token:
+    lanes of a channel share the tail atomic) or through the workgroup's first wave (several tokens: commands
+    sorted by channel); both must hand the proxy the same multiset of commands, with rings of 8 and of 4096 slots."""
+    monkeypatch.setenv("EP_PER_TOKEN_WAVES", str(waves))
+    for cid, T, entries in ((4, 70, 4096), (4, 70, 8), (2, None, 64), (1, 33, 8)):
+        cfg = g.config(cid)
+        out = _dispatch_case(epmod, oracle, cfg, T, 0.05, epmod.EP_CMD_PER_TOKEN, ring_entries=entries)
+        _check_commands(epmod, oracle, cfg, out, "per_token")
+
+
 # ------------------------------------------------------ commands and proxy
 def _check_commands(epmod, oracle, cfg, out, mode_name, payload="bf16", src=0, rank_filter=-1):
     want = oracle.expected_cmds(out["idx"][src], out["lay"], src, cfg.E_loc, cfg.H, payload, mode_name, rank_filter)
