@@ -489,10 +489,18 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
     if (mode == EP_CMD_NONE) return EP_OK;
     a.T = 0;
   }
+  if (T > 0 && !(cmd_mode & EP_CMD_NO_PLACEMENT)) {
+    a.reverse = (h->last_recv.load(std::memory_order_relaxed) == d_recv && dispatch_alternates())
+                    ? !h->last_reverse.load(std::memory_order_relaxed)
+                    : 0;
+    h->last_recv.store(d_recv, std::memory_order_relaxed);
+    h->last_reverse.store(a.reverse, std::memory_order_relaxed);
+  }
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = timing_for(h, 1, stream, &tm);
   const bool ok = HIP_OK((hipError_t)launch_dispatch(a, payload, stream, timed ? &tm : nullptr));
   const bool all_rows = ok && payload == EP_BF16 && dst_rank_filter < 0 && !(cmd_mode & EP_CMD_NO_PLACEMENT) && T > 0;
+  h->fresh_reverse.store(a.reverse, std::memory_order_relaxed);
   h->fresh_buf.store(all_rows ? d_recv : nullptr, std::memory_order_relaxed);
   h->fresh_T.store(T, std::memory_order_relaxed);
   h->fresh_stream.store(stream, std::memory_order_relaxed);
@@ -526,6 +534,7 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32
     const int64_t budget = (int64_t)combine_fresh_mb() << 20;
     const int64_t n = per_token > 0 ? budget / per_token : 0;
     a.fresh_from = n >= T ? 0 : T - (int32_t)n;
+    a.fresh_head = h->fresh_reverse.load(std::memory_order_relaxed);
   }
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = timing_for(h, 2, stream, &tm);

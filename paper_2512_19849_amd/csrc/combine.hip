@@ -30,11 +30,13 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const long long item = (long long)blockIdx.x * 4 + wave;
   const int t_launch = (int)(item / a.parts), part = (int)(item % a.parts);
   if (t_launch >= a.T) return;
-  // With fresh rows the grid walks the tokens backwards: the rows written last are read before
-  // the rest of the traffic pushes them out of the memory-side cache.
-  const bool any_fresh = a.fresh_from < a.T;
-  const int t = any_fresh ? a.T - 1 - t_launch : t_launch;
-  const bool fresh = t >= a.fresh_from;
+  // With fresh rows the grid starts at the end of the token range where they are (the last tokens,
+  // or the first ones when the kernel that wrote them went backwards) and takes the newest first:
+  // the rows written last are read before the rest of the traffic pushes them out of the
+  // memory-side cache.
+  const int n_fresh = a.T - a.fresh_from;
+  const int t = (n_fresh > 0 && !a.fresh_head) ? a.T - 1 - t_launch : t_launch;
+  const bool fresh = a.fresh_head ? t < n_fresh : t >= a.fresh_from;
   const int K = KT > 0 ? KT : a.K;
   int row = -1;
   float wt = 0.0f;

@@ -11,6 +11,11 @@ struct TokenMeta {
   bool valid;  // this (t, k) is dispatched by this call
 };
 
+// Which group of tokens this workgroup takes: launch order, or the mirror image of it.
+EP_DEV int token_block(const DispatchArgs &a) {
+  return a.reverse ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
+}
+
 EP_DEV TokenMeta load_meta(const DispatchArgs &a, int t, int lane) {
   TokenMeta m{-1, -1, false};
   if (t < a.T && lane < a.K) {
@@ -129,7 +134,7 @@ EP_DEV void emit_block_cmds(const DispatchArgs &a, const TokenMeta &m, int part,
     const bool active = p.x >= 0;
     const int e = active ? p.x : 0;
     const unsigned dr = (unsigned)(e / a.E_loc), le = (unsigned)(e - (int)dr * a.E_loc);
-    const unsigned long long so = (unsigned long long)(blockIdx.x * a.tokens_per_block + i / a.K) * a.row_bytes;
+    const unsigned long long so = (unsigned long long)(token_block(a) * a.tokens_per_block + i / a.K) * a.row_bytes;
     const unsigned long long dof = (unsigned long long)p.y * a.row_bytes;
     ring_push_sorted(a.ring, active, (unsigned)e % a.ring.channels, cmd_w0(EP_OP_WRITE, a.src, dr, le),
                      a.row_bytes >> 4, (unsigned)(so >> 4), (unsigned)(dof >> 4), scratch);
@@ -150,7 +155,7 @@ template <int VPL>
 __global__ void dispatch_bf16_kernel(DispatchArgs a) {
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int part = wave % a.parts;
-  const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
+  const int t = token_block(a) * a.tokens_per_block + wave / a.parts;
   const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
   const bool ordered = (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_CHUNK32_ORDERED;
   if (ring_on && !ordered && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
@@ -192,7 +197,7 @@ template <int VPL>
 __global__ void dispatch_fp8_kernel(DispatchArgs a) {
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int part = wave % a.parts;
-  const int t = blockIdx.x * a.tokens_per_block + wave / a.parts;
+  const int t = token_block(a) * a.tokens_per_block + wave / a.parts;
   const bool ring_on = (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE;
   const bool ordered = (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_CHUNK32_ORDERED;
   if (ring_on && !ordered && blockIdx.x == 0 && wave == 0) emit_leading_atomics(a, lane);
@@ -272,6 +277,8 @@ static int split_for(int units, int T, const int *cands, int ncand) {
   }
   return best;
 }
+
+bool dispatch_alternates() { return env_int("EP_DISPATCH_ALTERNATE", 1) != 0; }
 
 int tuned_dispatch_vpl(int H, int T) {
   static const int c[] = {1, 2, 4, 7, 8, 14, 16};

@@ -256,6 +256,13 @@ struct ep_handle {
   std::atomic<const void *> fresh_buf{nullptr};
   std::atomic<int32_t> fresh_T{0};
   std::atomic<void *> fresh_stream{nullptr};
+  std::atomic<int32_t> fresh_reverse{0};  // ... and whether that dispatch took the tokens backwards
+  // A dispatch into the buffer of the previous dispatch starts at the other end of the token range:
+  // the rows touched last in the previous step (written last, then read through the cache by the
+  // combine) are the ones the memory-side cache still holds, and they are overwritten in place
+  // instead of being pushed out by the first rows of a dispatch that starts at the far end.
+  std::atomic<const void *> last_recv{nullptr};
+  std::atomic<int32_t> last_reverse{0};
   uint64_t timeout_ns = 0;
 };
 

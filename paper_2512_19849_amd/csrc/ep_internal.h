@@ -69,6 +69,7 @@ struct DispatchArgs {
   int32_t parts;           // wavefronts per token
   int32_t tokens_per_block;
   int32_t block_cmds;      // the workgroup's first wave pushes the commands of all its tokens
+  int32_t reverse;         // workgroups take the tokens from the last one down (see ep_dispatch)
   int32_t chunks_per_expert;
   int32_t *chunk_cnt;      // scratch [E * chunks_per_expert], zero between calls
   int32_t *expert_done;    // scratch [E], zero between calls
@@ -89,7 +90,10 @@ struct CombineArgs {
   // Tokens >= fresh_from had their rows written last, by the kernel that ran just before on this
   // stream (ep_combine knows this when it follows ep_dispatch into the same buffer): those rows
   // are read with cached loads and first, the rest with streaming loads.  fresh_from == T: none.
+  // fresh_head: that kernel went through the tokens backwards, so the fresh ones are the FIRST
+  // T - fresh_from tokens instead (and the grid keeps the ascending order).
   int32_t fresh_from;
+  int32_t fresh_head;
 };
 
 struct DedupArgs {
@@ -194,6 +198,7 @@ int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void 
 // Tunables (read once from the environment, for sweeps): vectors per lane.
 int tuned_dispatch_vpl(int H, int T);
 int tuned_combine_vpl(int H);
+bool dispatch_alternates();  // EP_DISPATCH_ALTERNATE != 0 (default on)
 int combine_fresh_mb();  // bytes (MiB) of just-dispatched rows that ep_combine takes to be cache-resident
 
 }  // namespace ep

@@ -15,6 +15,7 @@ int launch_fill_u32(uint32_t*, uint32_t, long long, void*) { return 0; }
 int tuned_dispatch_vpl(int, int) { return 1; }
 int tuned_combine_vpl(int) { return 1; }
 int combine_fresh_mb() { return 0; }
+bool dispatch_alternates() { return false; }
 int launch_recv_wait(const RecvWaitArgs&, void*) { return 0; }
 int launch_barrier(const RingDev&, void*) { return 0; }
 int launch_dedup(const DedupArgs&, void*) { return 0; }

@@ -539,15 +539,20 @@ def test_combine_directly_after_dispatch_reads_the_fresh_rows_first(epmod, oracl
         d_idx = _dev(idx)
         lay = r.layout(d_idx)
         recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")
-        outs = [torch.full((T, cfg.H), 3.0, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
-        r.dispatch(bits_to_bf16(x), d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_CHUNK32)
-        r.combine(recv, _dev(w[0]), lay.dst_row[0], outs[0])       # directly after the dispatch
-        r.combine(recv, _dev(w[0]), lay.dst_row[0], outs[1])       # nothing fresh any more
-        r.wait()
-        torch.cuda.synchronize()
-        assert np.array_equal(bf16_to_bits(recv), want_recv)
-        for out in outs:
-            assert _combine_check(oracle, bf16_to_bits(out), want_recv, w[0], lay_want["dst_row"][0], cfg.K) == 0
+        # three rounds into the same buffer: the dispatch takes the tokens forwards, backwards, forwards, and
+        # the combine that follows finds the fresh rows at the end, at the start, at the end of the token range
+        for rnd, mode in enumerate((epmod.EP_CMD_CHUNK32, epmod.EP_CMD_PER_TOKEN, epmod.EP_CMD_NONE)):
+            recv.fill_(-2.0)
+            recv[rows - 1].zero_()                                   # (the spare row nobody writes)
+            outs = [torch.full((T, cfg.H), 3.0, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+            r.dispatch(bits_to_bf16(x), d_idx[0], lay, recv, cmd_mode=mode)
+            r.combine(recv, _dev(w[0]), lay.dst_row[0], outs[0])       # directly after the dispatch
+            r.combine(recv, _dev(w[0]), lay.dst_row[0], outs[1])       # nothing fresh any more
+            r.wait()
+            torch.cuda.synchronize()
+            assert np.array_equal(bf16_to_bits(recv), want_recv), rnd
+            for out in outs:
+                assert _combine_check(oracle, bf16_to_bits(out), want_recv, w[0], lay_want["dst_row"][0], cfg.K) == 0
         assert r.stats()["device_error"] == 0
 
 
