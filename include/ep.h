@@ -184,7 +184,11 @@ int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T,
  * destination expert mod C): Writes at the granularity cmd_mode selects, after
  * the rows they describe are stored, and per destination expert one Atomic
  * carrying count[e] (also when 0).  A full channel blocks the pushing wave
- * until the proxy pops (bounded by spin_timeout_ms). */
+ * until the proxy pops (bounded by spin_timeout_ms).
+ * Performance only, never the result: a dispatch into the d_recv of the previous
+ * dispatch of this handle hands the tokens to its workgroups from the other end of
+ * the token range than that one did (the rows the memory-side cache still holds are
+ * then overwritten first); EP_DISPATCH_ALTERNATE=0 keeps the ascending order. */
 int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
                 const int32_t *d_dst_row, const int32_t *d_count, const int32_t *d_base,
                 int32_t T, int32_t src_rank, int32_t dst_rank_filter,
