@@ -536,7 +536,7 @@ def main() -> int:
                                f"{cfg.routing} routing, payload {payload}, commands {cmd_mode_name}",
                    "rows": rows, "proxy_threads": threads, "channels": args.channels, "gpu_wait": args.gpu_wait,
                    "ring_entries": args.ring_entries,
-                   "combine_fresh_mb": int(os.environ.get("EP_COMBINE_FRESH_MB", "192"))},
+                   "combine_fresh_mb": int(os.environ.get("EP_COMBINE_FRESH_MB", "224"))},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "kernels_ms": {"layout": round(lay_ms, 4), "dispatch": round(disp_ms, 4), "combine": round(comb_ms, 4)},

@@ -205,7 +205,7 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
  * all rows into d_y itself, for the same T, on the same stream and handle, with no
  * other launch of the handle in between, the rows of the last tokens are taken to be
  * still in the memory-side cache and are read first, with cached loads (how many:
- * EP_COMBINE_FRESH_MB MiB worth, default 192, 0 = never); in every other case all
+ * EP_COMBINE_FRESH_MB MiB worth, default 224, 0 = never); in every other case all
  * rows are read with streaming loads in token order. */
 int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w,
                const int32_t *d_dst_row, int32_t T, int64_t y_rows,

@@ -116,13 +116,15 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
 }
 
 // How much of what a dispatch has just written a combine that follows it directly may expect in the
-// memory-side cache (256 MB on MI355X).  Measured on the prefill workload (448 MiB of rows), whole step:
-// 0.1996 ms with streaming loads only (combine 102 us), 0.1947 with the last 160 MiB as cached loads,
-// 0.1907 with 192 MiB (combine 85 us; the next dispatch pays 3 us of it back), 0.192 with 208-256 MiB;
-// with ALL loads cached combine takes 111 us (the loads push each other out), and without the reversed
-// token order the cached loads find nothing.  EP_COMBINE_FRESH_MB overrides, 0 switches it off.
+// memory-side cache (256 MB on MI355X).  Measured on the prefill workload (448 MiB of rows), whole step,
+// every dispatch in ascending order: 0.1996 ms with streaming loads only (combine 102 us), 0.1947 with the
+// last 160 MiB as cached loads, 0.1907 with 192 MiB (combine 85 us), 0.192 with 208-256 MiB; with
+// dispatches that alternate their direction: 0.1871 / 0.1865 / 0.1853 / 0.1858 / 0.1836 ms with 160 / 192 /
+// 208 / 224 / 256 MiB and 0.1931 with 320 MiB (512 MiB of rows: 0.2164 / 0.2148 / 0.2134 / 0.2126 / 0.2136 /
+// 0.2221).  With ALL loads cached combine takes 111 us (the loads push each other out), and in ascending
+// order the cached loads find nothing.  EP_COMBINE_FRESH_MB overrides, 0 switches it off.
 int combine_fresh_mb() {
-  const int mb = env_int("EP_COMBINE_FRESH_MB", 192);
+  const int mb = env_int("EP_COMBINE_FRESH_MB", 224);
   return mb < 0 ? 0 : (mb > 4096 ? 4096 : mb);
 }
 
