@@ -85,9 +85,19 @@ enum ep_flags {
   EP_FLAG_LOG_CMDS = 1,   /* proxy keeps every polled command (ep_cmd_log)          */
   EP_FLAG_LOG_EVENTS = 2, /* proxy keeps the receiver-side event trace (ep_event_log) */
   EP_FLAG_HOST_ONLY = 4,  /* no device: ring + proxy only, producer is ep_host_push  */
-  EP_FLAG_SENDER_FENCE = 8 /* the alternative Section 3.3 weighs against the receiver-side fence: the SENDER half
+  EP_FLAG_SENDER_FENCE = 8, /* the alternative Section 3.3 weighs against the receiver-side fence: the SENDER half
                               holds a count Atomic back until the Writes it vouches for have completed, then
                               sends it; the receiver never has to buffer one.  Costs the sender a round trip. */
+  EP_FLAG_CACHE_HINTS = 16 /* performance only, never the result; OFF unless asked for.  The caller promises that
+                              every ep_combine of this handle reads the very buffer the preceding bf16 ep_dispatch
+                              wrote (an identity expert, or experts that overwrite their rows in place right
+                              before the combine), so that the rows of the tokens dispatched last are still in
+                              the 256 MB memory-side cache: ep_combine then reads those rows first and with
+                              cached loads (EP_COMBINE_FRESH_MB MiB worth at ep_proxy_start, default 224), and a
+                              dispatch into the buffer of the previous dispatch hands the tokens to its
+                              workgroups from the other end of the token range.  Without the flag every
+                              dispatch walks the tokens in ascending order and every combine reads all rows
+                              with streaming loads, whatever ran before it. */
 };
 
 typedef struct ep_config {
@@ -148,8 +158,10 @@ typedef struct ep_stats_t {
  * *out receives the handle.  EP_EINVAL / EP_ENOMEM / EP_EHIP on failure. */
 int ep_proxy_start(const ep_config *cfg, ep_handle **out);
 
-/* ep_proxy_stop - waits for enqueued device work of the handle, stops and
- * joins the proxy threads, frees everything.  The handle is dead afterwards. */
+/* ep_proxy_stop - end of the proxy's life (Section 3.2: one proxy per GPU, created
+ * with the communicator and torn down with it): waits for enqueued device work of
+ * the handle, stops and joins the proxy threads, frees everything.  The handle is
+ * dead afterwards. */
 int ep_proxy_stop(ep_handle *h);
 
 /* ep_layout - routing is only known at run time, so sizes and destinations of the
@@ -184,11 +196,7 @@ int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T,
  * destination expert mod C): Writes at the granularity cmd_mode selects, after
  * the rows they describe are stored, and per destination expert one Atomic
  * carrying count[e] (also when 0).  A full channel blocks the pushing wave
- * until the proxy pops (bounded by spin_timeout_ms).
- * Performance only, never the result: a dispatch into the d_recv of the previous
- * dispatch of this handle hands the tokens to its workgroups from the other end of
- * the token range than that one did (the rows the memory-side cache still holds are
- * then overwritten first); EP_DISPATCH_ALTERNATE=0 keeps the ascending order. */
+ * until the proxy pops (bounded by spin_timeout_ms). */
 int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
                 const int32_t *d_dst_row, const int32_t *d_count, const int32_t *d_base,
                 int32_t T, int32_t src_rank, int32_t dst_rank_filter,
@@ -201,17 +209,15 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
  * fp32 accumulator starting at +0, k ascending, fused multiply-add, one final
  * round-to-nearest-even; k with dst_row == -1 are skipped.  d_y bf16
  * [y_rows,H]; d_topk_w fp32 [T,K]; d_dst_row int32 [T,K]; d_out bf16 [T,H].
- * Performance only, never the result: when the call follows a bf16 ep_dispatch of
- * all rows into d_y itself, for the same T, on the same stream and handle, with no
- * other launch of the handle in between, the rows of the last tokens are taken to be
- * still in the memory-side cache and are read first, with cached loads (how many:
- * EP_COMBINE_FRESH_MB MiB worth, default 224, 0 = never); in every other case all
- * rows are read with streaming loads in token order. */
+ * All rows are read with streaming loads in token order (see EP_FLAG_CACHE_HINTS
+ * for the one exception a caller can ask for). */
 int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w,
                const int32_t *d_dst_row, int32_t T, int64_t y_rows,
                void *d_out, void *stream);
 
-/* ep_wait - host-blocks until the proxy has applied the count Atomic of every
+/* ep_wait - the host-side view of completion (Section 3.3: an Atomic is applied
+ * only when the Writes it vouches for have arrived; Section 4.1: completion is a
+ * counter in host memory): host-blocks until the proxy has applied the count Atomic of every
  * destination expert of every dispatch enqueued so far (the data of those
  * dispatches is then in place and its counters are posted), or returns the
  * sticky device/proxy error, or EP_ETIMEOUT after spin_timeout_ms. */
@@ -342,12 +348,16 @@ int ep_ring_counters(ep_handle *h, const int32_t **ring_tail, const int32_t **ri
  * ordered Atomics (EP_CMD_CHUNK32_ORDERED), added up in sequence order. */
 int ep_tail_counters(ep_handle *h, const int32_t **recv_tail);
 
-/* ep_stats / ep_reset_stats - proxy and ring statistics.  Reset also zeroes
- * the completion counters; call it only when ep_wait has returned. */
+/* ep_stats / ep_reset_stats - proxy and ring statistics: what Section 5.3 measures
+ * of the channel (commands per second through the FIFOs, commands per proxy
+ * thread) and what Section 3.3 describes of the receiver (Atomics that had to wait
+ * in the control buffer).  Reset also zeroes the completion counters; call it only
+ * when ep_wait has returned. */
 int ep_stats(ep_handle *h, ep_stats_t *out);
 int ep_reset_stats(ep_handle *h);
 
-/* ep_cmd_log - copies up to cap commands (16 bytes each, as polled, thread by
+/* ep_cmd_log - the TransferCmds of Section 3.1 as the proxy's Poll saw them, for
+ * replaying a dispatch from its commands alone: copies up to cap commands (16 bytes each, as polled, thread by
  * thread, in-channel order preserved) into buf; *n = number available.
  * Needs EP_FLAG_LOG_CMDS; call after ep_wait.
  * ep_event_log - same for the receiver-side trace (4 x uint32 per record:
@@ -369,23 +379,6 @@ int ep_event_log(ep_handle *h, void *buf, size_t cap, size_t *n);
 int ep_host_push(ep_handle *h, int32_t channel, uint32_t w0, uint32_t w1, uint32_t w2,
                  uint32_t w3, uint64_t *idx);
 int ep_host_check_completion(ep_handle *h, int32_t channel, uint64_t idx);
-/* ep_profile / ep_profile_read - kernel-exact durations of the three compute
- * calls, for callers that want them without an external profiler.  While
- * profiling is on, every ep_layout / ep_dispatch / ep_combine launch carries a
- * pair of HIP events that receive the begin timestamp of the call's first kernel
- * and the end timestamp of its last one from the launches themselves (nothing
- * extra is put on the stream, unlike a pair of recorded events, which delays
- * the kernel between them by a few microseconds).  ep_profile_read waits for the
- * timed launches of one call (0 layout, 1 dispatch, 2 combine), returns their
- * summed duration in milliseconds and their number, and forgets them when
- * reset != 0.  Launches on a capturing stream are not timed.  on = 0 switches
- * profiling off; on = n >= 1 switches it on and makes sure n pairs of events are
- * at hand, so that up to n timed launches create none (n <= 65536).  Events are
- * reused after a read with reset and freed when the handle stops; at most 65536
- * unread launches per call are kept, later ones run untimed. */
-int ep_profile(ep_handle *h, int32_t on);
-int ep_profile_read(ep_handle *h, int32_t call, double *total_ms, int32_t *launches, int32_t reset);
-
 /* ep_captured / ep_expect - ring-on launches inside a HIP graph.  ep_dispatch,
  * ep_ht_dispatch and ep_fifo_stress tell ep_wait at call time how many count
  * Atomics (or Drains) their kernel is going to push.  On a stream that is being
@@ -402,24 +395,6 @@ int ep_expect(ep_handle *h, int64_t atomics, int64_t drains);
 /* Tells the proxy how many count Atomics ep_wait should expect in addition
  * (ep_dispatch does this itself for its own). */
 int ep_host_expect_atomics(ep_handle *h, int32_t n);
-
-/* ep_fifo_stress - closed-loop load test of the GPU->CPU channel (the FIFO stress
- * test of Section 5.3): `pushers` wavefronts (lane 0 of each; channel = pusher
- * mod C) each push `cmds_per_pusher` commands, one after the other, waiting with
- * Check-completion until the proxy has popped each before pushing the next.  The
- * command is a count Atomic of value 0 for (source 0, expert 0): harmless, applied
- * at once (ep_wait accounts for them; do not run it while a dispatch of source 0
- * is being awaited).  d_lat_sum / d_lat_max (device, uint64 [pushers]) receive
- * each pusher's summed and largest push->popped time in ticks of 10 ns. */
-int ep_fifo_stress(ep_handle *h, int32_t pushers, int32_t cmds_per_pusher, uint64_t *d_lat_sum, uint64_t *d_lat_max,
-                   void *stream);
-
-/* ep_bw_probe - plain streaming kernels for measuring this device's bandwidth
- * ceilings next to the path's kernels (no part of the method): kind 0 reads
- * `bytes` from d_src (16-byte non-temporal loads, one per lane), kind 1 writes
- * `bytes` to d_dst, kind 2 copies d_src to d_dst.  bytes must be a multiple of
- * 16; buffers are caller-owned device memory.  Needs no handle. */
-int ep_bw_probe(int32_t kind, const void *d_src, void *d_dst, int64_t bytes, void *stream);
 
 /* ep_last_error - text describing the most recent failed HIP runtime call made
  * by the library on the calling thread ("" if none).  Static storage. */

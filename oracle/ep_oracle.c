@@ -116,8 +116,8 @@ int oracle_layout(const int32_t *idx, int S, int T, int K, int E, int R,
 
 /* ----------------------------------------------------------- dispatch bf16
  * Step (2): every valid (t, k) copies the token's hidden vector into its
- * receive row: recv[dst_row[t,k], :] = x[t, :]  (Section 2.1: "activations
- * must be dispatched ... to the GPUs that host the selected experts").
+ * receive row: recv[dst_row[t,k], :] = x[t, :]  (Section 2.1, the dispatch
+ * phase: a token's activation goes to every rank that hosts one of its experts).
  * rank_filter >= 0 keeps only entries whose expert lives on that rank
  * (expert e lives on rank e / E_loc).  write_count (optional, [recv_rows])
  * is bumped once per row written so a test can see double writes.
@@ -127,7 +127,7 @@ int oracle_dispatch_bf16(const uint16_t *x, const int32_t *idx, const int32_t *d
                          int T, int K, int H, int E_loc, int rank_filter,
                          uint16_t *recv, long recv_rows, uint8_t *write_count) {
   int bad = 0;
-#pragma omp parallel for num_threads(g_threads) schedule(static)
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(|:bad)
   for (int t = 0; t < T; ++t)
     for (int k = 0; k < K; ++k) {
       int e = idx[(long)t * K + k];
@@ -221,7 +221,7 @@ int oracle_dispatch_fp8(const uint16_t *x, const int32_t *idx, const int32_t *ds
                         uint8_t *write_count) {
   int nb = H / 128;
   int bad = 0;
-#pragma omp parallel for num_threads(g_threads) schedule(static)
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(|:bad)
   for (int t = 0; t < T; ++t) {
     uint8_t qrow[H];
     float srow[nb];
@@ -267,7 +267,7 @@ void oracle_dequant_rows(const uint8_t *q, const float *scale, long rows, int H,
 int oracle_combine(const uint16_t *y, const float *w, const int32_t *dst_row,
                    int T, int K, int H, long rows, uint16_t *out) {
   int bad = 0;
-#pragma omp parallel for num_threads(g_threads) schedule(static)
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(|:bad)
   for (int t = 0; t < T; ++t)
     for (int h = 0; h < H; ++h) {
       float acc = 0.0f;
@@ -287,7 +287,7 @@ int oracle_combine(const uint16_t *y, const float *w, const int32_t *dst_row,
 int oracle_combine_f64(const uint16_t *y, const float *w, const int32_t *dst_row,
                        int T, int K, int H, long rows, double *out, double *abs_sum) {
   int bad = 0;
-#pragma omp parallel for num_threads(g_threads) schedule(static)
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(|:bad)
   for (int t = 0; t < T; ++t)
     for (int h = 0; h < H; ++h) {
       double acc = 0.0, mag = 0.0;
@@ -363,7 +363,7 @@ int oracle_combine_partial(const uint16_t *y, const float *w, const int32_t *dst
                            const int32_t *dst_row_g, int T, int K, int H, long rows, long rows_g,
                            uint16_t *partial) {
   int bad = 0;
-#pragma omp parallel for num_threads(g_threads) schedule(static)
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(|:bad)
   for (int t = 0; t < T; ++t)
     for (int j = 0; j < K; ++j) {
       if (first_k[(long)t * K + j] != j) continue; /* not the first entry of its group */

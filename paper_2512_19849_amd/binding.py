@@ -19,7 +19,7 @@ EP_OK, EP_EINVAL, EP_ENOMEM, EP_ESTATE, EP_EHIP, EP_ETIMEOUT, EP_EBOUNDS = 0, -1
 EP_BF16, EP_FP8_E4M3 = 0, 1
 EP_CMD_PER_TOKEN, EP_CMD_CHUNK32, EP_CMD_NONE, EP_CMD_CHUNK32_ORDERED = 0, 1, 2, 3
 EP_CMD_ATOMICS_FIRST, EP_CMD_DRAIN, EP_CMD_NO_PLACEMENT = 0x100, 0x200, 0x400
-EP_FLAG_LOG_CMDS, EP_FLAG_LOG_EVENTS, EP_FLAG_HOST_ONLY, EP_FLAG_SENDER_FENCE = 1, 2, 4, 8
+EP_FLAG_LOG_CMDS, EP_FLAG_LOG_EVENTS, EP_FLAG_HOST_ONLY, EP_FLAG_SENDER_FENCE, EP_FLAG_CACHE_HINTS = 1, 2, 4, 8, 16
 EP_OP_WRITE, EP_OP_ATOMIC, EP_OP_DRAIN, EP_OP_BARRIER, EP_OP_ORDERED_WRITE, EP_OP_ORDERED_ATOMIC = 1, 2, 3, 4, 5, 6
 EP_OP_RING = 7
 EP_RING_WRITE, EP_RING_TAIL, EP_RING_HEAD = 0, 1, 2

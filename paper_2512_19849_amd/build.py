@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libep.so")
 SOURCES = ["layout.hip", "dispatch.hip", "combine.hip", "ht_ring.hip", "service.hip", "proxy.cpp", "api.cpp"]
-HEADERS = ["ep_internal.h", "ep_device.h", "ep_host.h", os.path.join("..", "..", "include", "ep.h")]
+HEADERS = ["ep_internal.h", "ep_device.h", "ep_host.h", os.path.join("..", "..", "include", "ep.h"),
+           os.path.join("..", "..", "include", "ep_diag.h")]
 
 
 def hipcc() -> str:

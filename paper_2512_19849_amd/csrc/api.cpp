@@ -20,6 +20,26 @@ namespace {
 
 bool is_pow2(uint32_t v) { return v && !(v & (v - 1)); }
 
+int env_int(const char *name, int dflt) {
+  const char *s = getenv(name);
+  return (s && *s) ? atoi(s) : dflt;
+}
+
+// The EP_* launch-shape overrides, read once per handle; no launch looks at the environment.
+Tunables read_tunables() {
+  Tunables t;
+  t.dispatch_vpl = env_int("EP_DISPATCH_VPL", t.dispatch_vpl);
+  t.dispatch_fp8_vpl = env_int("EP_DISPATCH_FP8_VPL", t.dispatch_fp8_vpl);
+  t.per_token_waves = env_int("EP_PER_TOKEN_WAVES", t.per_token_waves);
+  t.combine_vpl = env_int("EP_COMBINE_VPL", t.combine_vpl);
+  t.layout_small = env_int("EP_LAYOUT_SMALL", t.layout_small);
+  t.layout_tpb = env_int("EP_LAYOUT_TPB", t.layout_tpb);
+  t.ht_threads = env_int("EP_HT_THREADS", t.ht_threads);
+  const int mb = env_int("EP_COMBINE_FRESH_MB", t.combine_fresh_mb);
+  t.combine_fresh_mb = mb < 0 ? 0 : (mb > 4096 ? 4096 : mb);
+  return t;
+}
+
 int validate(const ep_config &c) {
   if (c.num_ranks < 1 || c.num_ranks > 256) return EP_EINVAL;
   if (c.num_experts < 1 || c.num_experts > kMaxExperts || c.num_experts % c.num_ranks) return EP_EINVAL;
@@ -179,6 +199,8 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
   ep_handle *h = new (std::nothrow) ep_handle();
   if (!h) return EP_ENOMEM;
   h->cfg = *cfg;
+  h->tune = read_tunables();
+  h->cache_hints = (cfg->flags & EP_FLAG_CACHE_HINTS) != 0;
   h->host_only = (cfg->flags & EP_FLAG_HOST_ONLY) != 0;
   h->E_loc = cfg->num_experts / cfg->num_ranks;
   if (h->cfg.heap_rows == 0) h->cfg.heap_rows = (int64_t)cfg->num_src * cfg->max_tokens * cfg->top_k;
@@ -400,7 +422,7 @@ int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t *d_cou
   a.error = h->ring.error;
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = T > 0 && timing_for(h, 0, stream, &tm);
-  return HIP_OK((hipError_t)launch_layout(a, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
+  return HIP_OK((hipError_t)launch_layout(a, h->tune, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
 }
 
 static uint32_t row_bytes_of(int H, int payload) {
@@ -489,8 +511,8 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
     if (mode == EP_CMD_NONE) return EP_OK;
     a.T = 0;
   }
-  if (T > 0 && !(cmd_mode & EP_CMD_NO_PLACEMENT)) {
-    a.reverse = (h->last_recv.load(std::memory_order_relaxed) == d_recv && dispatch_alternates())
+  if (h->cache_hints && T > 0 && !(cmd_mode & EP_CMD_NO_PLACEMENT)) {
+    a.reverse = h->last_recv.load(std::memory_order_relaxed) == d_recv
                     ? !h->last_reverse.load(std::memory_order_relaxed)
                     : 0;
     h->last_recv.store(d_recv, std::memory_order_relaxed);
@@ -498,8 +520,9 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
   }
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = timing_for(h, 1, stream, &tm);
-  const bool ok = HIP_OK((hipError_t)launch_dispatch(a, payload, stream, timed ? &tm : nullptr));
-  const bool all_rows = ok && payload == EP_BF16 && dst_rank_filter < 0 && !(cmd_mode & EP_CMD_NO_PLACEMENT) && T > 0;
+  const bool ok = HIP_OK((hipError_t)launch_dispatch(a, payload, h->tune, stream, timed ? &tm : nullptr));
+  const bool all_rows = ok && h->cache_hints && payload == EP_BF16 && dst_rank_filter < 0 &&
+                        !(cmd_mode & EP_CMD_NO_PLACEMENT) && T > 0;
   h->fresh_reverse.store(a.reverse, std::memory_order_relaxed);
   h->fresh_buf.store(all_rows ? d_recv : nullptr, std::memory_order_relaxed);
   h->fresh_T.store(T, std::memory_order_relaxed);
@@ -526,19 +549,19 @@ int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w, const int32
   a.H = h->cfg.hidden;
   a.error = h->ring.error;
   a.fresh_from = T;
-  if (d_y && h->fresh_buf.exchange(nullptr, std::memory_order_relaxed) == d_y &&
+  if (h->cache_hints && d_y && h->fresh_buf.exchange(nullptr, std::memory_order_relaxed) == d_y &&
       h->fresh_T.load(std::memory_order_relaxed) == T && h->fresh_stream.load(std::memory_order_relaxed) == stream) {
     // the dispatch kernel stored the tokens' rows in token order: the rows of the last tokens are what the
     // memory-side cache (256 MB) still holds
     const int64_t per_token = (int64_t)a.K * a.H * 2;
-    const int64_t budget = (int64_t)combine_fresh_mb() << 20;
+    const int64_t budget = (int64_t)h->tune.combine_fresh_mb << 20;
     const int64_t n = per_token > 0 ? budget / per_token : 0;
     a.fresh_from = n >= T ? 0 : T - (int32_t)n;
     a.fresh_head = h->fresh_reverse.load(std::memory_order_relaxed);
   }
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = timing_for(h, 2, stream, &tm);
-  return HIP_OK((hipError_t)launch_combine(a, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
+  return HIP_OK((hipError_t)launch_combine(a, h->tune, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
 }
 
 int ep_dedup(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t ranks_per_group, int32_t *d_group_idx,
@@ -734,7 +757,7 @@ int ep_ht_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, con
   a.fifo = h->ring;
   expect_more(h, stream, 0, c.num_channels);
   h->fresh_buf.store(nullptr, std::memory_order_relaxed);
-  return HIP_OK((hipError_t)launch_ht_ring(a, stream)) ? EP_OK : EP_EHIP;
+  return HIP_OK((hipError_t)launch_ht_ring(a, h->tune, stream)) ? EP_OK : EP_EHIP;
 }
 
 int ep_tail_counters(ep_handle *h, const int32_t **recv_tail) {

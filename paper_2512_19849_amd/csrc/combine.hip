@@ -115,25 +115,10 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   }
 }
 
-// How much of what a dispatch has just written a combine that follows it directly may expect in the
-// memory-side cache (256 MB on MI355X).  Measured on the prefill workload (448 MiB of rows), whole step,
-// every dispatch in ascending order: 0.1996 ms with streaming loads only (combine 102 us), 0.1947 with the
-// last 160 MiB as cached loads, 0.1907 with 192 MiB (combine 85 us), 0.192 with 208-256 MiB; with
-// dispatches that alternate their direction: 0.1871 / 0.1865 / 0.1853 / 0.1858 / 0.1836 ms with 160 / 192 /
-// 208 / 224 / 256 MiB and 0.1931 with 320 MiB (512 MiB of rows: 0.2164 / 0.2148 / 0.2134 / 0.2126 / 0.2136 /
-// 0.2221).  With ALL loads cached combine takes 111 us (the loads push each other out), and in ascending
-// order the cached loads find nothing.  EP_COMBINE_FRESH_MB overrides, 0 switches it off.
-int combine_fresh_mb() {
-  const int mb = env_int("EP_COMBINE_FRESH_MB", 224);
-  return mb < 0 ? 0 : (mb > 4096 ? 4096 : mb);
-}
-
-int tuned_combine_vpl(int H) {
+static int tuned_combine_vpl(int forced) {
   static const int c[] = {1, 2, 4};
-  const int forced = env_int("EP_COMBINE_VPL", 0);
   for (int v : c)
     if (v == forced) return v;
-  (void)H;
   return 1;  // one 16-byte column slice per lane: fewest registers, most waves in flight (measured best)
 }
 
@@ -154,11 +139,11 @@ static void launch_combine_t(CombineArgs a, hipStream_t st, const LaunchTiming *
   }
 }
 
-int launch_combine(const CombineArgs &a, void *stream, const LaunchTiming *timing) {
+int launch_combine(const CombineArgs &a, const Tunables &tune, void *stream, const LaunchTiming *timing) {
   hipStream_t st = (hipStream_t)stream;
   if (a.T <= 0) return 0;
   if ((a.H / 8 + 63) / 64 > 65535) return (int)hipErrorInvalidValue;
-  switch (tuned_combine_vpl(a.H)) {
+  switch (tuned_combine_vpl(tune.combine_vpl)) {
     case 2: launch_combine_t<2>(a, st, timing); break;
     case 4: launch_combine_t<4>(a, st, timing); break;
     default: launch_combine_t<1>(a, st, timing); break;

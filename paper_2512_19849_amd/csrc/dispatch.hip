@@ -278,11 +278,8 @@ static int split_for(int units, int T, const int *cands, int ncand) {
   return best;
 }
 
-bool dispatch_alternates() { return env_int("EP_DISPATCH_ALTERNATE", 1) != 0; }
-
-int tuned_dispatch_vpl(int H, int T) {
+static int tuned_dispatch_vpl(int H, int T, int forced) {
   static const int c[] = {1, 2, 4, 7, 8, 14, 16};
-  const int forced = env_int("EP_DISPATCH_VPL", 0);
   for (int v : c)
     if (v == forced) return v;
   // About four waves per token stream best (measured in the full path on 7168- and 4096-wide rows:
@@ -291,9 +288,8 @@ int tuned_dispatch_vpl(int H, int T) {
   return split_for(H / 8, T, c, 7);
 }
 
-static int tuned_dispatch_fp8_vpl(int H, int T) {
+static int tuned_dispatch_fp8_vpl(int H, int T, int forced) {
   static const int c[] = {1, 2, 4};  // more than 4 groups per lane would spill at 128 VGPRs
-  const int forced = env_int("EP_DISPATCH_FP8_VPL", 0);
   for (int v : c)
     if (v == forced) return v;
   return split_for(H / 16, T, c, 3);
@@ -301,10 +297,9 @@ static int tuned_dispatch_fp8_vpl(int H, int T) {
 
 // One command per row: as many tokens per workgroup as 16 waves hold (their commands are pushed
 // together, see emit_block_cmds).  Returns the dynamic LDS bytes of the launch.
-static size_t block_cmds_setup(DispatchArgs &a) {
+static size_t block_cmds_setup(DispatchArgs &a, int waves) {
   a.block_cmds = 0;
   if ((a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_PER_TOKEN) return 0;
-  int waves = env_int("EP_PER_TOKEN_WAVES", 16);
   if (waves < 4 || waves > 16) waves = 16;
   const int tpb = waves / a.parts;
   if (tpb < 2) return 0;
@@ -314,50 +309,51 @@ static size_t block_cmds_setup(DispatchArgs &a) {
 }
 
 template <int VPL>
-static void launch_dispatch_bf16_t(DispatchArgs a, hipStream_t st, const LaunchTiming *tm) {
+static void launch_dispatch_bf16_t(DispatchArgs a, const Tunables &tune, hipStream_t st, const LaunchTiming *tm) {
   const int nvec = a.H / 8;
   a.parts = (nvec + VPL * 64 - 1) / (VPL * 64);
   a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
-  const size_t lds = block_cmds_setup(a);
+  const size_t lds = block_cmds_setup(a, tune.per_token_waves);
   const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
   launch_kernel(dispatch_bf16_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), lds, st,
                 tm ? tm->start : nullptr, tm ? tm->stop : nullptr, a);
 }
 
 template <int VPL>
-static void launch_dispatch_fp8_t(DispatchArgs a, hipStream_t st, const LaunchTiming *tm) {
+static void launch_dispatch_fp8_t(DispatchArgs a, const Tunables &tune, hipStream_t st, const LaunchTiming *tm) {
   const int npair = a.H / 16;
   a.parts = (npair + VPL * 64 - 1) / (VPL * 64);
   a.tokens_per_block = a.parts >= 4 ? 1 : 4 / a.parts;
-  const size_t lds = block_cmds_setup(a);
+  const size_t lds = block_cmds_setup(a, tune.per_token_waves);
   const int grid = max(1, (a.T + a.tokens_per_block - 1) / a.tokens_per_block);
   launch_kernel(dispatch_fp8_kernel<VPL>, dim3(grid), dim3(64 * a.parts * a.tokens_per_block), lds, st,
                 tm ? tm->start : nullptr, tm ? tm->stop : nullptr, a);
 }
 
-int launch_dispatch(const DispatchArgs &a, int payload, void *stream, const LaunchTiming *timing) {
+int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, void *stream,
+                    const LaunchTiming *timing) {
   hipStream_t st = (hipStream_t)stream;
   // T == 0 with the ring on still launches one (idle) workgroup: it owes the zero-count atomics
   if (a.T <= 0 && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_NONE) return 0;
   if (payload == EP_BF16) {
-    const int vpl = tuned_dispatch_vpl(a.H, a.T);
+    const int vpl = tuned_dispatch_vpl(a.H, a.T, tune.dispatch_vpl);
     if ((a.H / 8 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
     switch (vpl) {
-      case 1: launch_dispatch_bf16_t<1>(a, st, timing); break;
-      case 2: launch_dispatch_bf16_t<2>(a, st, timing); break;
-      case 4: launch_dispatch_bf16_t<4>(a, st, timing); break;
-      case 7: launch_dispatch_bf16_t<7>(a, st, timing); break;
-      case 8: launch_dispatch_bf16_t<8>(a, st, timing); break;
-      case 14: launch_dispatch_bf16_t<14>(a, st, timing); break;
-      default: launch_dispatch_bf16_t<16>(a, st, timing); break;
+      case 1: launch_dispatch_bf16_t<1>(a, tune, st, timing); break;
+      case 2: launch_dispatch_bf16_t<2>(a, tune, st, timing); break;
+      case 4: launch_dispatch_bf16_t<4>(a, tune, st, timing); break;
+      case 7: launch_dispatch_bf16_t<7>(a, tune, st, timing); break;
+      case 8: launch_dispatch_bf16_t<8>(a, tune, st, timing); break;
+      case 14: launch_dispatch_bf16_t<14>(a, tune, st, timing); break;
+      default: launch_dispatch_bf16_t<16>(a, tune, st, timing); break;
     }
   } else {
-    const int vpl = tuned_dispatch_fp8_vpl(a.H, a.T);
+    const int vpl = tuned_dispatch_fp8_vpl(a.H, a.T, tune.dispatch_fp8_vpl);
     if ((a.H / 16 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;
     switch (vpl) {
-      case 1: launch_dispatch_fp8_t<1>(a, st, timing); break;
-      case 2: launch_dispatch_fp8_t<2>(a, st, timing); break;
-      default: launch_dispatch_fp8_t<4>(a, st, timing); break;
+      case 1: launch_dispatch_fp8_t<1>(a, tune, st, timing); break;
+      case 2: launch_dispatch_fp8_t<2>(a, tune, st, timing); break;
+      default: launch_dispatch_fp8_t<4>(a, tune, st, timing); break;
     }
   }
   return (int)hipGetLastError();

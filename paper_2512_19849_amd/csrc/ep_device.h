@@ -5,7 +5,6 @@
 #define EP_DEVICE_H_
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
-#include <stdlib.h>
 
 #include "ep_internal.h"
 
@@ -242,12 +241,6 @@ static inline void launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t ld
     hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, st, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, 0, a);
   else
     hipLaunchKernelGGL(kernel, grid, block, lds, st, a);
-}
-
-// Launch-shape overrides for experiments (EP_* environment variables).
-static inline int env_int(const char *name, int dflt) {
-  const char *s = getenv(name);
-  return (s && *s) ? atoi(s) : dflt;
 }
 
 // ------------------------------------------------------------ FP8 quantiser

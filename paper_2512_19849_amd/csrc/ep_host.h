@@ -194,6 +194,8 @@ struct alignas(64) ProxyThread {
 // The opaque handle of include/ep.h.
 struct ep_handle {
   ep_config cfg{};
+  ep::Tunables tune{};       // EP_* overrides, read once in ep_proxy_start
+  bool cache_hints = false;  // EP_FLAG_CACHE_HINTS
   bool host_only = false;
   int E_loc = 0;
   uint64_t heap_bytes = 0;
@@ -249,6 +251,8 @@ struct ep_handle {
   std::atomic<int> proxy_error{0};
   int nthreads = 0;
   ep::ProxyThread *threads = nullptr;
+  // Only with EP_FLAG_CACHE_HINTS (the caller's promise that ep_combine reads the buffer ep_dispatch
+  // wrote, with nothing but in-place work on it in between):
   // What the last launch of this handle wrote, if it was a bf16 ep_dispatch of all its rows: the
   // receive buffer, the token count and the stream.  An ep_combine that reads the same buffer for
   // the same tokens on the same stream directly afterwards knows which rows are still in the

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/ep.h"
+#include "../../include/ep_diag.h"
 
 namespace ep {
 
@@ -173,6 +174,20 @@ struct RecvWaitArgs {
   unsigned long long timeout_ticks;
 };
 
+// Launch-shape overrides for sweeps and for tests that want every code path: read ONCE per handle, in
+// ep_proxy_start, from EP_* environment variables (0 = the library's own choice).  No launch reads the
+// environment.
+struct Tunables {
+  int dispatch_vpl = 0;      // EP_DISPATCH_VPL: 16-byte vectors per lane of a bf16 row
+  int dispatch_fp8_vpl = 0;  // EP_DISPATCH_FP8_VPL: 16-channel groups per lane of an FP8 row
+  int per_token_waves = 16;  // EP_PER_TOKEN_WAVES: wavefronts per workgroup of a per-token dispatch
+  int combine_vpl = 0;       // EP_COMBINE_VPL: 16-byte column slices per lane
+  int layout_small = 1;      // EP_LAYOUT_SMALL: 0 keeps small routing tables on the two-kernel form
+  int layout_tpb = 4;        // EP_LAYOUT_TPB: tiles per workgroup of the count kernel
+  int ht_threads = 1024;     // EP_HT_THREADS: threads per workgroup of the ring-buffer channels
+  int combine_fresh_mb = 224;  // EP_COMBINE_FRESH_MB: see EP_FLAG_CACHE_HINTS
+};
+
 // Launchers implemented in the .hip files (layout, dispatch, combine, ht_ring, service).  All return a hipError_t as int.
 // Optional kernel-exact timing of a launch (ep_profile): HIP events that receive the begin timestamp of the
 // launch's first kernel and the end timestamp of its last one from the dispatch packets themselves, with no
@@ -180,25 +195,20 @@ struct RecvWaitArgs {
 struct LaunchTiming {
   void *start, *stop;
 };
-int launch_layout(const LayoutArgs &a, void *stream, const LaunchTiming *timing = nullptr);
-int launch_dispatch(const DispatchArgs &a, int payload, void *stream, const LaunchTiming *timing = nullptr);
-int launch_combine(const CombineArgs &a, void *stream, const LaunchTiming *timing = nullptr);
+int launch_layout(const LayoutArgs &a, const Tunables &tune, void *stream, const LaunchTiming *timing = nullptr);
+int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, void *stream,
+                    const LaunchTiming *timing = nullptr);
+int launch_combine(const CombineArgs &a, const Tunables &tune, void *stream, const LaunchTiming *timing = nullptr);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
 int launch_barrier(const RingDev &ring, void *stream);
 int launch_fifo_stress(const RingDev &ring, int pushers, int per_pusher, unsigned long long *lat_sum,
                        unsigned long long *lat_max, void *stream);
-int launch_ht_ring(const HtRingArgs &a, void *stream);
+int launch_ht_ring(const HtRingArgs &a, const Tunables &tune, void *stream);
 int launch_copy_batch(const CopyBatchArgs &b, void *stream);
 int launch_dedup(const DedupArgs &a, void *stream);
 int launch_gather_index(const GatherIndexArgs &a, void *stream);
 int launch_combine_partial(const CombinePartialArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
 int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void *stream);
-
-// Tunables (read once from the environment, for sweeps): vectors per lane.
-int tuned_dispatch_vpl(int H, int T);
-int tuned_combine_vpl(int H);
-bool dispatch_alternates();  // EP_DISPATCH_ALTERNATE != 0 (default on)
-int combine_fresh_mb();  // bytes (MiB) of just-dispatched rows that ep_combine takes to be cache-resident
 
 }  // namespace ep

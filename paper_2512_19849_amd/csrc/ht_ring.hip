@@ -359,8 +359,8 @@ __global__ __launch_bounds__(1024) void ht_ring_kernel(HtRingArgs a) {
   drain_all_channels(a.fifo, a.waves_done, (unsigned)a.src, lane_id());
 }
 
-int launch_ht_ring(const HtRingArgs &a, void *stream) {
-  int threads = env_int("EP_HT_THREADS", 1024);
+int launch_ht_ring(const HtRingArgs &a, const Tunables &tune, void *stream) {
+  int threads = tune.ht_threads;
   if (threads < 64 || threads > 1024 || (threads & 63)) threads = 1024;
   hipLaunchKernelGGL(ht_ring_kernel, dim3((unsigned)a.slices), dim3((unsigned)threads), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();

@@ -341,9 +341,9 @@ static size_t small_layout_lds(const LayoutArgs &a) {
   return bytes <= 64 * 1024 ? bytes : 0;
 }
 
-int launch_layout(const LayoutArgs &a, void *stream, const LaunchTiming *timing) {
+int launch_layout(const LayoutArgs &a, const Tunables &tune, void *stream, const LaunchTiming *timing) {
   hipStream_t st = (hipStream_t)stream;
-  if (const size_t lds = env_int("EP_LAYOUT_SMALL", 1) ? small_layout_lds(a) : 0) {
+  if (const size_t lds = tune.layout_small ? small_layout_lds(a) : 0) {
     launch_kernel(layout_small_kernel, dim3(1), dim3(1024), lds, st, timing ? timing->start : nullptr,
                   timing ? timing->stop : nullptr, a);
     return (int)hipGetLastError();
@@ -351,7 +351,7 @@ int launch_layout(const LayoutArgs &a, void *stream, const LaunchTiming *timing)
   // Workgroups are 1024 threads so that the last one has many hands for the scan, but only a few
   // wavefronts of each own a tile: the LDS atomics of one tile then compete with few others.
   const int kBlock = 1024;
-  int W = env_int("EP_LAYOUT_TPB", 4);
+  int W = tune.layout_tpb;
   if (W != 1 && W != 2 && W != 4 && W != 8 && W != 16) W = 4;
   while (W > 1 && (size_t)W * a.E * sizeof(unsigned long long) > 65536 - 12288) W >>= 1;
   LayoutArgs b = a;

@@ -8,13 +8,10 @@
 #include <thread>
 #include <vector>
 namespace ep {
-int launch_layout(const LayoutArgs&, void*, const LaunchTiming*) { return 0; }
-int launch_dispatch(const DispatchArgs&, int, void*, const LaunchTiming*) { return 0; }
-int launch_combine(const CombineArgs&, void*, const LaunchTiming*) { return 0; }
+int launch_layout(const LayoutArgs&, const Tunables&, void*, const LaunchTiming*) { return 0; }
+int launch_dispatch(const DispatchArgs&, int, const Tunables&, void*, const LaunchTiming*) { return 0; }
+int launch_combine(const CombineArgs&, const Tunables&, void*, const LaunchTiming*) { return 0; }
 int launch_fill_u32(uint32_t*, uint32_t, long long, void*) { return 0; }
-int tuned_dispatch_vpl(int, int) { return 1; }
-int tuned_combine_vpl(int) { return 1; }
-int combine_fresh_mb() { return 0; }
 bool dispatch_alternates() { return false; }
 int launch_recv_wait(const RecvWaitArgs&, void*) { return 0; }
 int launch_barrier(const RingDev&, void*) { return 0; }
@@ -23,7 +20,7 @@ int launch_gather_index(const GatherIndexArgs&, void*) { return 0; }
 int launch_combine_partial(const CombinePartialArgs&, void*) { return 0; }
 int launch_bw_probe(int, const void*, void*, long long, void*) { return 0; }
 int launch_copy_batch(const CopyBatchArgs&, void*) { return 0; }
-int launch_ht_ring(const HtRingArgs&, void*) { return 0; }
+int launch_ht_ring(const HtRingArgs&, const Tunables&, void*) { return 0; }
 int launch_fifo_stress(const RingDev&, int, int, unsigned long long*, unsigned long long*, void*) { return 0; }
 }
 static uint32_t w0(uint32_t op, uint32_t src, uint32_t dr, uint32_t le) { return (op << 28) | (src << 20) | (dr << 12) | le; }

@@ -20,7 +20,7 @@ def test_header_is_strict_c99(tmp_path):
     if not shutil.which("gcc"):
         pytest.skip("no gcc")
     src = tmp_path / "only_header.c"
-    src.write_text('#include "ep.h"\nint main(void) { return sizeof(ep_config) > 0 ? 0 : 1; }\n')
+    src.write_text('#include "ep.h"\n#include "ep_diag.h"\nint main(void) { return sizeof(ep_config) > 0 ? 0 : 1; }\n')
     subprocess.run(["gcc", "-std=c99", "-pedantic-errors", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
                     "-I", os.path.join(ROOT, "include"), str(src)], check=True)
 

@@ -522,9 +522,10 @@ def test_combine_parity(epmod, oracle, cid, T, mask):
 
 @pytest.mark.parametrize("fresh_mb", [0, 1, 4096])
 def test_combine_directly_after_dispatch_reads_the_fresh_rows_first(epmod, oracle, fresh_mb, monkeypatch):
-    """A combine that follows a bf16 dispatch into the same buffer walks the tokens backwards and reads the rows
-    of the last tokens with cached loads (none, some, or all of them, by the byte budget); a second combine of
-    the same inputs takes the plain order.  Both equal the oracle's sum, bit for bit."""
+    """On a handle made with EP_FLAG_CACHE_HINTS a combine that follows a bf16 dispatch into the same buffer walks
+    the tokens backwards and reads the rows of the last tokens with cached loads (none, some, or all of them, by
+    the byte budget); a second combine of the same inputs takes the plain order.  Both equal the oracle's sum,
+    bit for bit."""
     from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
     monkeypatch.setenv("EP_COMBINE_FRESH_MB", str(fresh_mb))
     cfg = g.config(5, S=1)
@@ -535,7 +536,7 @@ def test_combine_directly_after_dispatch_reads_the_fresh_rows_first(epmod, oracl
     rows = int((idx >= 0).sum()) + 1
     x = g.activations(cfg, 0, T=T)
     want_recv, _ = oracle.dispatch_bf16(x, idx[0], lay_want["dst_row"][0], cfg.E_loc, rows, -1, fill=0)
-    with _runner(epmod, cfg, T) as r:
+    with _runner(epmod, cfg, T, flags=epmod.EP_FLAG_CACHE_HINTS) as r:
         d_idx = _dev(idx)
         lay = r.layout(d_idx)
         recv = torch.zeros((rows, cfg.H), dtype=torch.bfloat16, device="cuda")

@@ -22,7 +22,7 @@ def ep():
 
 
 def test_library_exports_every_declared_symbol(ep):
-    hdr = open(os.path.join(ROOT, "include", "ep.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", f)).read() for f in ("ep.h", "ep_diag.h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(ep_[a-z_]+)\s*\(", hdr))
     assert {"ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine"} <= names
