@@ -3,8 +3,9 @@
 
 One step = one pass of the whole path over one batch of synthetic input:
 ep_layout -> ep_dispatch (payload placement + transfer commands through the
-FIFO channels to the CPU proxy) -> identity expert -> ep_combine -> ep_wait
-(the proxy has posted every completion counter of the step).
+FIFO channels to the CPU proxy) -> ep_combine over the experts' outputs, which
+sit in a buffer of their own (as they do behind real experts) -> ep_wait (the
+proxy has posted every completion counter of the step).
 
 Workload: the 4096-token x hidden-7168 x 256-expert top-8 prefill share
 (16 simulated ranks, Zipf-skewed routing), inputs resident in HBM before the
@@ -346,10 +347,13 @@ def main() -> int:
     ap.add_argument("--proxy-threads", type=int, default=4)
     ap.add_argument("--channels", type=int, default=8)
     ap.add_argument("--ring-entries", type=int, default=4096)
-    ap.add_argument("--event-every", type=int, default=8,
-                    help="time the kernels of every Nth timed step with HIP events that receive the kernels' own "
-                         "begin/end timestamps (ep_profile); a timed launch costs the stream ~4 us, so timing "
-                         "every step would slow the path being measured by 8 %%")
+    ap.add_argument("--timed-launches", type=int, default=8,
+                    help="how many launches of each of ep_layout, ep_dispatch and ep_combine inside the timed "
+                         "region carry HIP events that receive the kernel's own begin/end timestamps (ep_profile), "
+                         "spread evenly over the steps; a timed launch costs the stream ~3 us, so timing every "
+                         "call would slow the path being measured by 5 %%")
+    ap.add_argument("--no-in-place", action="store_true",
+                    help="skip the second, labelled measurement (identity expert in place, EP_FLAG_CACHE_HINTS)")
     ap.add_argument("--gpu-wait", action="store_true",
                     help="put ep_recv_wait between dispatch and combine: the combine kernel starts only after the "
                          "proxy's completion counters reached the GPU (the GPU->CPU->GPU loop of the paper)")
@@ -397,7 +401,10 @@ def main() -> int:
     if payload == "bf16":
         recv = torch.zeros((rows, H), dtype=torch.bfloat16, device="cuda")
         scale = None
-        y = recv                                   # identity expert: combine reads the received rows
+        # the experts' outputs live in a buffer of their own (filled below, before anything is timed, with what
+        # identity experts would write: a copy of the received rows), so the combine reads rows that no kernel
+        # of the step has touched - nothing it reads can still be in a cache
+        y = torch.empty_like(recv)
     else:
         recv = torch.zeros((rows, H), dtype=torch.uint8, device="cuda")
         scale = torch.zeros((rows, H // 128), dtype=torch.float32, device="cuda")
@@ -405,20 +412,25 @@ def main() -> int:
     out = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
     pl = ep.PAYLOADS[payload]
 
-    def step(timed=False):
-        # a timed step launches its kernels with events that receive the kernels' own begin and end
-        # timestamps (ep_profile); nothing else goes onto the stream
-        if timed:
-            ep.ep_profile(r.h, True)
-        lay = r.layout(d_idx)
-        r.dispatch(d_x, d_idx[0], lay, recv, scale, payload=pl, cmd_mode=cmd_mode)
+    def step(run=None, y_buf=None, timed=()):
+        # `timed` names the calls of this step (0 layout, 1 dispatch, 2 combine) that are launched with
+        # events that receive their kernels' own begin and end timestamps (ep_profile); nothing else goes
+        # onto the stream
+        run = run or r
+        prof = lambda call, on: ep.ep_profile(run.h, on) if call in timed else None
+        prof(0, True)
+        lay = run.layout(d_idx)
+        prof(0, False)
+        prof(1, True)
+        run.dispatch(d_x, d_idx[0], lay, recv, scale, payload=pl, cmd_mode=cmd_mode)
+        prof(1, False)
         if args.gpu_wait and cmd_mode != ep.EP_CMD_NONE:
-            r.recv_wait(None)
-        r.combine(y, d_w, lay.dst_row[0], out)
-        if timed:
-            ep.ep_profile(r.h, False)
+            run.recv_wait(None)
+        prof(2, True)
+        run.combine(y if y_buf is None else y_buf, d_w, lay.dst_row[0], out)
+        prof(2, False)
         if cmd_mode != ep.EP_CMD_NONE:
-            r.wait()
+            run.wait()
         return lay
 
     # measured ceilings of this device with plain streaming kernels over a buffer of the receive
@@ -446,30 +458,44 @@ def main() -> int:
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
+    if payload == "bf16":
+        step(y_buf=recv)                           # fills recv ...
+        torch.cuda.synchronize()
+        y.copy_(recv)                              # ... and the identity experts' outputs, once, untimed
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     if cmd_mode != ep.EP_CMD_NONE:
         ep.ep_reset_stats(r.h)
-    every = max(1, args.event_every)
-    ep.ep_profile(r.h, 3 * ((args.steps + every - 1) // every))  # the timed launches' events, made ahead
+    # Which calls of which steps are timed: --timed-launches launches of every kernel, spread evenly over the
+    # steps; layout and combine of one step (they are not neighbours on the stream), dispatch of the next.
+    n_t = min(args.timed_launches, max(1, args.steps // 2))
+    plan = {}
+    for i in sorted({int(j * args.steps / n_t) for j in range(n_t)}):
+        plan[i] = plan.get(i, ()) + (0, 2)
+        plan[(i + 1) % args.steps] = plan.get((i + 1) % args.steps, ()) + (1,)
+    ep.ep_profile(r.h, 3 * n_t)  # the timed launches' events, made ahead
     ep.ep_profile(r.h, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        lay = step(timed=(i % every == 0))
+        lay = step(timed=plan.get(i, ()))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     st = r.stats()
 
-    (lay_sum, n_timed), (disp_sum, _), (comb_sum, _) = (ep.ep_profile_read(r.h, c) for c in (0, 1, 2))
-    lay_ms, disp_ms, comb_ms = lay_sum / n_timed, disp_sum / n_timed, comb_sum / n_timed
+    (lay_sum, n_lay), (disp_sum, n_disp), (comb_sum, n_comb) = (ep.ep_profile_read(r.h, c) for c in (0, 1, 2))
+    nan = float("nan")
+    lay_ms = lay_sum / n_lay if n_lay else nan
+    disp_ms = disp_sum / n_disp if n_disp else nan
+    comb_ms = comb_sum / n_comb if n_comb else nan
     total_bytes = disp_bytes + comb_bytes
     value = total_bytes / (ms_per_step * 1e-3) / 1e9
 
-    dom = "dispatch" if disp_ms >= comb_ms else "combine"
+    dom = "dispatch" if (n_disp and not n_comb) or disp_ms >= comb_ms else "combine"
     dom_ms, dom_bytes = (disp_ms, disp_bytes) if dom == "dispatch" else (comb_ms, comb_bytes)
+    n_timed = n_disp if dom == "dispatch" else n_comb
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"kernel": f"{dom}_{payload if dom == 'dispatch' else 'bf16'}", "bound": "hbm",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -517,12 +543,32 @@ def main() -> int:
             got = lay.numpy()
             ok = all(np.array_equal(got[k], v) for k, v in res["olay"].items())
             if payload == "bf16":
-                ok = ok and np.array_equal(bf16_to_bits(recv), oy)
+                ok = ok and np.array_equal(bf16_to_bits(recv), oy) and np.array_equal(bf16_to_bits(y), oy)
             else:
                 ok = ok and np.array_equal(recv.cpu().numpy(), oq) and np.array_equal(scale.cpu().numpy(), os_)
             ok = ok and int(oracle.bf16_ulp_distance(bf16_to_bits(out), res["oout"]).max()) <= 1
             verified = bool(ok)
 
+    # Second, labelled measurement: the identity expert IN PLACE - the combine reads the receive buffer the
+    # dispatch has just written, on a handle that was told so (EP_FLAG_CACHE_HINTS): part of what it reads is
+    # then served by the 256 MB memory-side cache.  Not the headline: real experts sit between the two calls.
+    in_place = None
+    if payload == "bf16" and not args.no_in_place:
+        r2 = EPRunner(R, E, K, H, T, S=1, num_channels=args.channels, ring_entries=args.ring_entries,
+                      num_proxy_threads=max(threads, 0), spin_timeout_ms=10000, flags=ep.EP_FLAG_CACHE_HINTS)
+        for _ in range(args.warmup):
+            step(run=r2, y_buf=recv)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(run=r2, y_buf=recv)
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - c0) * 1e3 / args.steps
+        r2.close()
+        in_place = {"what": "same step, but the combine reads the receive buffer itself (identity expert in place) "
+                            "on a handle made with EP_FLAG_CACHE_HINTS",
+                    "ms_per_step": round(ms2, 4), "value": round(total_bytes / (ms2 * 1e-3) / 1e9, 1),
+                    "frac_hbm_peak": round(total_bytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     r.close()
     line = {
         "metric": "dispatch+combine GB/s and tokens/s on 1 GPU; % of HBM peak",
@@ -536,7 +582,8 @@ def main() -> int:
                                f"{cfg.routing} routing, payload {payload}, commands {cmd_mode_name}",
                    "rows": rows, "proxy_threads": threads, "channels": args.channels, "gpu_wait": args.gpu_wait,
                    "ring_entries": args.ring_entries,
-                   "combine_fresh_mb": int(os.environ.get("EP_COMBINE_FRESH_MB", "224"))},
+                   "expert_outputs": "own buffer (copy of the received rows, written before the timed region)"
+                                     if payload == "bf16" else "own buffer (seeded bf16 rows)"},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "kernels_ms": {"layout": round(lay_ms, 4), "dispatch": round(disp_ms, 4), "combine": round(comb_ms, 4)},
@@ -557,6 +604,8 @@ def main() -> int:
                                 "16 x EFA 200G) (Section 5.2)",
             "ht_vs_deepep": "within 5 % of DeepEP on 4 x (8 x H100, 8 x ConnectX-7 400G) (Section 5.2)",
             "proxy_threads": "one proxy thread is the bottleneck, four are used everywhere (Section 5.3)"},
+        "identity_expert_in_place": in_place,
+        "kernels_timed_launches": {"layout": n_lay, "dispatch": n_disp, "combine": n_comb},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "verified_vs_oracle": verified,
     }
     print(json.dumps(line))

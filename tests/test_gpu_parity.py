@@ -846,7 +846,8 @@ def test_device_side_bounds_check_reports_instead_of_faulting(epmod, oracle):
 # ------------------------------------------- full sizes, bench launch configuration
 @pytest.mark.parametrize("cid,payload,mode,threads", [(4, "bf16", "chunk32", 4), (4, "bf16", "per_token", 4),
                                                       (5, "bf16", "chunk32", 4), (5, "fp8", "chunk32", 1),
-                                                      (5, "fp8", "per_token", 4)])
+                                                      (5, "fp8", "per_token", 4), (4, "fp8", "chunk32", 4),
+                                                      (4, "bf16", "chunk32_ordered", 4)])
 def test_full_size_round_trip(epmod, oracle, cid, payload, mode, threads):
     """The whole path at the workload's full size, element by element, with the
     launch configuration bench.py times (8 channels x 4096 slots)."""
@@ -891,12 +892,57 @@ def test_full_size_round_trip(epmod, oracle, cid, payload, mode, threads):
             assert np.array_equal(bf16_to_bits(out), wout)
             st = r.stats()
             assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
-            assert st["atomics_applied"] == cfg.E and st["write_rows"] == rows
-            assert np.array_equal(r.counters()[0], want["count"][0])
+            assert st["write_rows"] == rows
             nchunks = int(np.ceil(want["count"][0] / 32).sum())
             assert st["writes"] == (rows if mode == "per_token" else nchunks)
+            if mode == "chunk32_ordered":                      # tail counters instead of per-expert count atomics
+                assert np.array_equal(epmod.ep_tail_counters(r.h, 1, cfg.R)[0], want["rank_total"])
+            else:
+                assert st["atomics_applied"] == cfg.E
+                assert np.array_equal(r.counters()[0], want["count"][0])
     finally:
         oracle.set_threads(1)
+
+
+@pytest.mark.parametrize("cid,mode", [(4, "per_token"), (4, "chunk32"), (4, "chunk32_ordered"), (5, "per_token")])
+def test_full_size_proxy_performed_writes(epmod, oracle, cid, mode):
+    """Registered heaps at the workload's full size, in the shape the timing suite launches (4 proxy threads,
+    8 channels x 4096 slots, no logs): the kernel only pushes commands (per token, straight out of x) or packs a
+    send heap (chunks), the proxy threads move every row; the receive heap equals the oracle's element by element."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    cfg = g.config(cid, S=1)
+    idx, _ = g.routing_all(cfg)
+    x = g.activations(cfg)
+    rows = idx.size
+    oracle.set_threads(min(16, oracle.max_threads()))
+    try:
+        want = oracle.layout(idx, cfg.E, cfg.R)
+        wrecv, _ = oracle.dispatch_bf16(x, idx[0], want["dst_row"][0], cfg.E_loc, rows)
+    finally:
+        oracle.set_threads(1)
+    with EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, cfg.T, num_proxy_threads=4, spin_timeout_ms=10000) as r:
+        d_idx, d_x = _dev(idx), bits_to_bf16(x)
+        lay = r.layout(d_idx)
+        recv = torch.full((rows, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")
+        if mode == "per_token":
+            r.register_heaps(d_x, recv)
+            target, cm = recv, epmod.EP_CMD_PER_TOKEN | epmod.EP_CMD_NO_PLACEMENT
+        else:
+            target = torch.full((rows, cfg.H), 2.5, dtype=torch.bfloat16, device="cuda")
+            r.register_heaps(target, recv)
+            cm = epmod.CMD_MODES[mode]
+        for rep in range(2):                                   # the second dispatch overwrites the sentinel again
+            recv.fill_(-1.5)
+            r.dispatch(d_x, d_idx[0], lay, target, cmd_mode=cm)
+            r.wait()
+            torch.cuda.synchronize()
+            assert np.array_equal(bf16_to_bits(recv), wrecv), rep
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        assert st["copied_bytes"] == st["write_bytes"] == 2 * rows * cfg.H * 2 and st["write_rows"] == 2 * rows
+        if mode != "chunk32_ordered":
+            assert np.array_equal(r.counters()[0], want["count"][0])
+        r.register_heaps(None, None)
 
 
 def test_full_size_decode_share_32_sources(epmod, oracle):
@@ -1386,6 +1432,40 @@ def test_ht_ring_dispatch_full_size(epmod, oracle, cid, slices, W):
         r.wait()
         torch.cuda.synchronize()
         assert np.array_equal(bf16_to_bits(recv), want)
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        assert st["write_rows"] == rows and st["writes"] == int((-(-per_channel // 32)).sum())
+        tail, head = epmod.ep_ring_counters(r.h, 1, slices, cfg.R)
+        assert np.array_equal(tail[0], per_channel) and np.array_equal(head[0], per_channel)
+
+
+def test_ht_ring_dispatch_full_size_fp8(epmod, oracle):
+    """The 8192-token workload with FP8 rows through the rings, in the shape the timing suite launches (128
+    slices, rings of 2 slots): codes and scales equal the oracle's quantiser bit for bit at every row."""
+    cfg = g.config(5, S=1)
+    idx, _ = g.routing_all(cfg)
+    x = g.activations(cfg)
+    rows = idx.size
+    slices, W = 128, 2
+    from paper_2512_19849_amd.runner import bits_to_bf16
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    oracle.set_threads(oracle.max_threads())
+    try:
+        wq, ws, _ = oracle.dispatch_fp8(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+    finally:
+        oracle.set_threads(1)
+    per_channel = oracle.ring_channel_rows(idx[0], cfg.E_loc, cfg.R, slices)
+    with _runner(epmod, cfg, ht_slices=slices, ht_ring_slots=W, spin_timeout_ms=10000) as r:
+        d_idx = _dev(idx)
+        lay = r.layout(d_idx)
+        ring = torch.zeros(r.ht_ring_bytes(), dtype=torch.uint8, device="cuda")
+        rq = torch.full((rows, cfg.H), 0xA5, dtype=torch.uint8, device="cuda")
+        rs = torch.full((rows, cfg.H // 128), -1.0, dtype=torch.float32, device="cuda")
+        r.ht_dispatch(bits_to_bf16(x), d_idx[0], lay, ring, rq, recv_scale=rs)
+        r.wait()
+        torch.cuda.synchronize()
+        assert np.array_equal(rs.cpu().numpy().view(np.uint32), ws.view(np.uint32)), "scales differ"
+        assert np.array_equal(rq.cpu().numpy(), wq), "codes differ"
         st = r.stats()
         assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
         assert st["write_rows"] == rows and st["writes"] == int((-(-per_channel // 32)).sum())
