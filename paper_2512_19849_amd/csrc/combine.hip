@@ -24,6 +24,34 @@ EP_DEV void fma8(float (&acc)[8], float w, const u32x4 &v) {
   }
 }
 
+// The slices of one wave, one after the other: K loads in flight, the chain in ascending k, the packed
+// result kept in registers; the stores of all slices leave together at the end, so that a wave's writes
+// do not trickle into its reads.  STREAM: non-temporal loads (rows that no cache is expected to hold).
+template <int VPL, int KT, bool STREAM>
+EP_DEV void combine_slices(const u32x4 *y, u32x4 *out, const int (&rows)[KT], const float (&ws)[KT], int safe, int nvec,
+                           int v0) {
+  u32x4 res[VPL];
+#pragma unroll
+  for (int i = 0; i < VPL; ++i)
+    if (v0 + i * 64 < nvec) {
+      u32x4 ld[KT];
+#pragma unroll
+      for (int k = 0; k < KT; ++k) {
+        const u32x4 *p = y + (size_t)(rows[k] >= 0 ? rows[k] : safe) * nvec + v0 + i * 64;
+        ld[k] = STREAM ? __builtin_nontemporal_load(p) : *p;
+      }
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < KT; ++k)
+        if (rows[k] >= 0) fma8(acc, ws[k], ld[k]);
+      res[i] = u32x4{pack_bf16_rne(acc[0], acc[1]), pack_bf16_rne(acc[2], acc[3]), pack_bf16_rne(acc[4], acc[5]),
+                     pack_bf16_rne(acc[6], acc[7])};
+    }
+#pragma unroll
+  for (int i = 0; i < VPL; ++i)
+    if (v0 + i * 64 < nvec) __builtin_nontemporal_store(res[i], out + v0 + i * 64);
+}
+
 template <int VPL, int KT>
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   const int wave = threadIdx.x >> 6, lane = lane_id();
@@ -68,36 +96,14 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
       rows[k] = __builtin_amdgcn_readlane(row, k);
       ws[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wt), k));
     }
-    u32x4 ld[VPL][KT];
-    if (fresh) {  // (wave-uniform; two loops so that each keeps its own kind of load)
-#pragma unroll
-      for (int i = 0; i < VPL; ++i)
-        if (v0 + i * 64 < nvec) {
-#pragma unroll
-          for (int k = 0; k < KT; ++k) ld[i][k] = y[(size_t)(rows[k] >= 0 ? rows[k] : safe) * nvec + v0 + i * 64];
-        }
-      // (keeps the optimiser from folding the two loops into one, which drops the streaming hint of the other)
+    // (wave-uniform; two instances so that each keeps its own kind of load)
+    if (fresh) {
+      combine_slices<VPL, KT, false>(y, out, rows, ws, safe, nvec, v0);
+      // (keeps the optimiser from folding the two instances into one, which drops the streaming hint of the other)
       asm volatile("" ::: "memory");
     } else {
-#pragma unroll
-      for (int i = 0; i < VPL; ++i)
-        if (v0 + i * 64 < nvec) {
-#pragma unroll
-          for (int k = 0; k < KT; ++k)
-            ld[i][k] = __builtin_nontemporal_load(y + (size_t)(rows[k] >= 0 ? rows[k] : safe) * nvec + v0 + i * 64);
-        }
+      combine_slices<VPL, KT, true>(y, out, rows, ws, safe, nvec, v0);
     }
-#pragma unroll
-    for (int i = 0; i < VPL; ++i)
-      if (v0 + i * 64 < nvec) {
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int k = 0; k < KT; ++k)
-          if (rows[k] >= 0) fma8(acc, ws[k], ld[i][k]);
-        u32x4 o = {pack_bf16_rne(acc[0], acc[1]), pack_bf16_rne(acc[2], acc[3]),
-                   pack_bf16_rne(acc[4], acc[5]), pack_bf16_rne(acc[6], acc[7])};
-        __builtin_nontemporal_store(o, out + v0 + i * 64);
-      }
   } else {
 #pragma unroll
     for (int i = 0; i < VPL; ++i)
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
 }
 
 static int tuned_combine_vpl(int forced) {
-  static const int c[] = {1, 2, 4};
+  static const int c[] = {1, 2, 4, 7, 14};
   for (int v : c)
     if (v == forced) return v;
   return 1;  // one 16-byte column slice per lane: fewest registers, most waves in flight (measured best)
@@ -146,6 +152,8 @@ int launch_combine(const CombineArgs &a, const Tunables &tune, void *stream, con
   switch (tuned_combine_vpl(tune.combine_vpl)) {
     case 2: launch_combine_t<2>(a, st, timing); break;
     case 4: launch_combine_t<4>(a, st, timing); break;
+    case 7: launch_combine_t<7>(a, st, timing); break;
+    case 14: launch_combine_t<14>(a, st, timing); break;
     default: launch_combine_t<1>(a, st, timing); break;
   }
   return (int)hipGetLastError();
