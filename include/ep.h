@@ -182,6 +182,28 @@ int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T,
               int32_t *d_base, int32_t *d_expert_offset, int32_t *d_rank_offset,
               int32_t *d_slot, int32_t *d_dst_row, void *stream);
 
+/* ep_layout_static - ep_layout for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It
+ * needs no handle (ep_proxy_start allocates) and calls no hipMalloc, hipFree or any
+ * other allocating routine: the scratch that ep_layout keeps in its handle (tile
+ * histograms, tile prefixes, a ticket) lives in a device array that is part of the
+ * library's code object, 2 MiB + 512 bytes per GPU, held until the process ends.
+ * Same kernels, same outputs, bit for bit, as ep_layout with num_src = S, top_k = K,
+ * num_experts = E, num_ranks = R (limits as in ep_config; 0 <= T < 2^19).
+ *   Limit: (S * ceil(T/64) + 1) * E <= 262144 scratch entries (the 4096-token,
+ *   256-expert table needs 16640); beyond that EP_EINVAL, with the figures in
+ *   ep_last_error.
+ *   d_status: device int32, may be NULL; receives EP_EBOUNDS when an expert id outside
+ *   [-1, E) is met (that entry gets slot = dst_row = -1); never cleared by the call.
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on the
+ * same GPU (two streams, two threads) race; order them on one stream.  The first call
+ * on a device looks the array's address up (not while the stream is being captured,
+ * unless ep_proxy_start has run on that device before: it does the look-up too). */
+int ep_layout_static(const int32_t *d_topk_idx, int32_t S, int32_t T, int32_t K, int32_t E, int32_t R,
+                     int32_t *d_count, int32_t *d_expert_total, int32_t *d_rank_total,
+                     int32_t *d_base, int32_t *d_expert_offset, int32_t *d_rank_offset,
+                     int32_t *d_slot, int32_t *d_dst_row, int32_t *d_status, void *stream);
+
 /* ep_dispatch - the dispatch phase (Section 2.1) for the T tokens of source
  * rank src_rank: every valid (t,k) whose expert lives on dst_rank_filter (or on
  * any rank if -1) gets x[t,:] written to receive row dst_row[t,k]:

@@ -64,7 +64,7 @@ class ep_stats_t(C.Structure):
         return d
 
 
-EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
+EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_layout_static", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
@@ -97,6 +97,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_proxy_start.argtypes = [C.POINTER(ep_config), C.POINTER(vp)]
     L.ep_proxy_stop.argtypes = [vp]
     L.ep_layout.argtypes = [vp, vp, i32] + [vp] * 8 + [vp]
+    L.ep_layout_static.argtypes = [vp, i32, i32, i32, i32, i32] + [vp] * 8 + [vp, vp]
     L.ep_dispatch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp]
     L.ep_combine.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
     L.ep_wait.argtypes = [vp]
@@ -179,6 +180,14 @@ def ep_layout(h: int, topk_idx, T: int, count, expert_total, rank_total, base, e
     _check("ep_layout", load_library().ep_layout(h, _ptr(topk_idx), T, _ptr(count), _ptr(expert_total),
                                                  _ptr(rank_total), _ptr(base), _ptr(expert_offset),
                                                  _ptr(rank_offset), _ptr(slot), _ptr(dst_row), _stream(stream)))
+
+
+def ep_layout_static(topk_idx, S: int, T: int, K: int, E: int, R: int, count, expert_total, rank_total, base,
+                     expert_offset, rank_offset, slot, dst_row, status=None, stream=None) -> None:
+    """ep_layout without a handle and without any allocation (scratch in a static device array)."""
+    _check("ep_layout_static", load_library().ep_layout_static(
+        _ptr(topk_idx), S, T, K, E, R, _ptr(count), _ptr(expert_total), _ptr(rank_total), _ptr(base),
+        _ptr(expert_offset), _ptr(rank_offset), _ptr(slot), _ptr(dst_row), _ptr(status), _stream(stream)))
 
 
 def ep_dispatch(h: int, x, topk_idx, dst_row, count, base, T: int, src_rank: int, dst_rank_filter: int,

@@ -271,6 +271,8 @@ int ep_proxy_start(const ep_config *cfg, ep_handle **out) {
     h->ring.log2_entries = h->log2_entries;
     h->ring.channels = (unsigned)C;
     h->ring.timeout_ticks = (unsigned long long)ms * 100000ull;  // wall_clock64 runs at 100 MHz
+    // (set-up is also where the static scratch of ep_layout_static gets its address looked up on this device)
+    if (!rc && !HIP_OK((hipError_t)static_layout_scratch(nullptr))) rc = EP_EHIP;
     if (!rc && !HIP_OK(hipDeviceSynchronize())) rc = EP_EHIP;
   }
   if (rc) {
@@ -423,6 +425,47 @@ int ep_layout(ep_handle *h, const int32_t *d_topk_idx, int32_t T, int32_t *d_cou
   LaunchTiming tm{nullptr, nullptr};
   const bool timed = T > 0 && timing_for(h, 0, stream, &tm);
   return HIP_OK((hipError_t)launch_layout(a, h->tune, stream, timed ? &tm : nullptr)) ? EP_OK : EP_EHIP;
+}
+
+int ep_layout_static(const int32_t *d_topk_idx, int32_t S, int32_t T, int32_t K, int32_t E, int32_t R,
+                     int32_t *d_count, int32_t *d_expert_total, int32_t *d_rank_total, int32_t *d_base,
+                     int32_t *d_expert_offset, int32_t *d_rank_offset, int32_t *d_slot, int32_t *d_dst_row,
+                     int32_t *d_status, void *stream) {
+  if (R < 1 || R > 256 || E < 1 || E > kMaxExperts || E % R || K < 1 || K > 64 || S < 1 || S > 256) return EP_EINVAL;
+  if (T < 0 || T >= (1 << 19)) return EP_EINVAL;
+  if (!d_count || !d_expert_total || !d_rank_total || !d_base || !d_expert_offset || !d_rank_offset) return EP_EINVAL;
+  if (T > 0 && (!d_topk_idx || !d_slot || !d_dst_row)) return EP_EINVAL;
+  const int ntiles = (T + kLayoutTile - 1) / kLayoutTile;
+  const long long entries = ((long long)S * ntiles + 1) * E;
+  if (entries > kStaticLayoutEntries) {
+    snprintf(g_last_error, sizeof(g_last_error),
+             "ep_layout_static: (S * ceil(T/64) + 1) * E = %lld scratch entries, the static buffer holds %lld",
+             entries, kStaticLayoutEntries);
+    return EP_EINVAL;
+  }
+  LayoutArgs a{};
+  a.idx = d_topk_idx;
+  a.S = S;
+  a.T = T;
+  a.K = K;
+  a.E = E;
+  a.R = R;
+  a.E_loc = E / R;
+  a.ntiles = ntiles;
+  a.count = d_count;
+  a.expert_total = d_expert_total;
+  a.rank_total = d_rank_total;
+  a.base = d_base;
+  a.expert_offset = d_expert_offset;
+  a.rank_offset = d_rank_offset;
+  a.slot = d_slot;
+  a.dst_row = d_dst_row;
+  a.error = d_status;  // null: errors go to a sink inside the static array
+  if (!HIP_OK((hipError_t)static_layout_scratch(&a))) return EP_EHIP;
+  // the array keeps what the last call left: the ticket has to start at zero (a fill kernel, not a memset
+  // node, so that the call can be captured into a graph)
+  if (!HIP_OK((hipError_t)launch_fill_u32(a.ticket, 0u, 1, stream))) return EP_EHIP;
+  return HIP_OK((hipError_t)launch_layout(a, Tunables{}, stream, nullptr)) ? EP_OK : EP_EHIP;
 }
 
 static uint32_t row_bytes_of(int H, int payload) {

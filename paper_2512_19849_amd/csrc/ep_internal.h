@@ -199,6 +199,11 @@ int launch_layout(const LayoutArgs &a, const Tunables &tune, void *stream, const
 int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, void *stream,
                     const LaunchTiming *timing = nullptr);
 int launch_combine(const CombineArgs &a, const Tunables &tune, void *stream, const LaunchTiming *timing = nullptr);
+// ep_layout_static: points a's scratch (tile_hist, tile_base, ticket, and error when it is null) into the
+// file-scope device array of layout.hip, looking its address up on the current device the first time.
+// a == nullptr only does the look-up.  Holds (S * ntiles + 1) * E entries up to kStaticLayoutEntries.
+constexpr long long kStaticLayoutEntries = 262144;
+int static_layout_scratch(LayoutArgs *a);
 int launch_recv_wait(const RecvWaitArgs &a, void *stream);
 int launch_barrier(const RingDev &ring, void *stream);
 int launch_fifo_stress(const RingDev &ring, int pushers, int per_pusher, unsigned long long *lat_sum,

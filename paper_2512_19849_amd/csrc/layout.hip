@@ -2,6 +2,8 @@
 // exclusive scans and slot indices as an integer counting sort built from LDS bit masks and popcounts.
 #include "ep_device.h"
 
+#include <mutex>
+
 namespace ep {
 
 // ------------------------------------------------------------------ layout
@@ -339,6 +341,50 @@ static size_t small_layout_lds(const LayoutArgs &a) {
   if (a.T <= 0 || a.K > 8 || F <= 0 || F > 12) return 0;
   const size_t bytes = (size_t)kSmallTiles * a.E * (8 + 2) + (size_t)(2 * a.E + 1) * 4;
   return bytes <= 64 * 1024 ? bytes : 0;
+}
+
+// ------------------------------------------------- scratch that nobody allocates
+// For callers that cannot allocate (ep_layout_static): the tile histograms, the tile prefixes, the ticket
+// and an error sink live in a file-scope device array.  Every GPU holds its own copy at its own address
+// until the process ends, so the address is looked up once per device, with that device current, and
+// host code only ever uses the looked-up pointer (the array's name is a host-side stand-in, not a
+// device address).
+struct StaticLayoutScratch {
+  unsigned ticket[64];  // one word used; a 256-byte line of its own
+  int error_sink[64];   // where device-side errors go when the caller passes no status word
+  int32_t hist[kStaticLayoutEntries];
+  int32_t base[kStaticLayoutEntries];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticLayoutScratch)];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_layout_scratch(LayoutArgs *a) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return (int)err;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  void *p = nullptr;
+  {
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (err != hipSuccess) return (int)err;
+      if (!p) return (int)hipErrorInvalidSymbol;
+      g_scratch_ptr[dev] = p;
+    }
+    p = g_scratch_ptr[dev];
+  }
+  if (a) {
+    StaticLayoutScratch *sc = (StaticLayoutScratch *)p;
+    a->ticket = sc->ticket;
+    a->tile_hist = sc->hist;
+    a->tile_base = sc->base;
+    if (!a->error) a->error = sc->error_sink;
+  }
+  return 0;
 }
 
 int launch_layout(const LayoutArgs &a, const Tunables &tune, void *stream, const LaunchTiming *timing) {
