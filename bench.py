@@ -51,6 +51,95 @@ def read_traffic(kernel_key: str):
     return float(m.group(1)) if m else None
 
 
+def source_stamp() -> str:
+    """Identifies the code that produced a table: the git revision when the tree has one (the GPU machine gets a
+    copy without .git), and always a hash over the library's sources and this file, which anyone can recompute:
+    cat include/*.h paper_2512_19849_amd/csrc/*.{h,hip,cpp} bench.py (sorted by path) | sha256sum."""
+    import glob
+    import hashlib
+    import subprocess
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")) +
+                   [f for pat in ("*.h", "*.hip", "*.cpp")
+                    for f in glob.glob(os.path.join(ROOT, "paper_2512_19849_amd", "csrc", pat))] +
+                   [os.path.join(ROOT, "bench.py")])
+    for f in files:
+        h.update(open(f, "rb").read())
+    rev = "n/a (no .git in this copy)"
+    try:
+        p = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True, text=True, timeout=10)
+        if p.returncode == 0 and p.stdout.strip():
+            dirty = subprocess.run(["git", "-C", ROOT, "status", "--porcelain", "--untracked-files=no"],
+                                   capture_output=True, text=True, timeout=10).stdout.strip()
+            rev = p.stdout.strip() + (" + uncommitted changes" if dirty else "")
+    except Exception:
+        pass
+    return f"git {rev}; sources sha256 {h.hexdigest()[:16]}"
+
+
+SUITE_LEGEND = """Per-call timings of all five workloads, MI355X (HIP-event medians of 20 calls, microseconds).
+
+command:  python3 bench.py --suite      (this file is written by that command, nothing is edited by hand)
+code:     {stamp}
+Every handle is made WITHOUT EP_FLAG_CACHE_HINTS: each call walks the tokens in ascending order and streams
+its rows, whatever ran before it.
+"warm": calls queued back to back.  Small workloads are launch-latency bound there (the host cannot
+queue them faster than ~15 us apart); "cold": a 512 MiB fill runs before every call, which also keeps the
+queue busy, so those figures are the kernel itself with cold caches.
+"*_kernel_us": the kernels' own duration from their begin / end timestamps (ep_profile), mean of 16 warm launches.
+"launch->last counter": host clock from the ep_dispatch call to ep_wait returning (all completion counters
+posted by the proxy).  "proxy rate": commands / (last atomic applied - first command polled), proxy-side clocks.
+GB/s = algorithmic bytes of that call / time.
+"ll_step_*": one whole low-latency step (layout, per-token dispatch with commands through the proxy, GPU-side
+wait for the posted counters, combine), host clock over 30 steps queued back to back: launched call by call
+(four launches per step through Python) and replayed from a HIP graph (ep_captured / ep_expect).
+"proxy_writes_*": heaps registered (ep_register_heaps), the proxy threads move the rows with batched copy
+kernels on the proxy's stream and release arrival notices when a batch has completed; same host clock.
+"inbound_share_*" (the 32-source decode workload): the rows the other 31 source ranks send into this rank's
+partition, 31 ep_dispatch calls with a rank filter queued back to back, event to event; "send_share" is this
+rank's own dispatch to all 32 ranks.
+"ht_step_*": the whole high-throughput step - dedup, group layout, group dispatch with chunk commands,
+gather index, partial reduce per group, final reduce, wait - host clock over 20 steps queued back to back.
+"""
+
+
+def format_suite(out: dict) -> str:
+    L = [SUITE_LEGEND.format(stamp=source_stamp())]
+    for name, v in out.items():
+        L.append(f"== {name}: T={v['T']} H={v['H']} E={v['E']} K={v['K']} R={v['R']} S={v['S']}  algorithmic bytes "
+                 f"dispatch={v['dispatch_bytes']:,} combine={v['combine_bytes']:,}")
+        for key in [k for k in v if k.startswith("threads")]:
+            L.append(f"  [{key}]")
+            for a, b in v[key].items():
+                extra = ""
+                if a.endswith("_us") and "dispatch_bf16" in a and "cold" not in a:
+                    extra = f"   ({v['dispatch_bytes'] / b / 1e3:.0f} GB/s)"
+                if a.endswith("_us") and "dispatch_fp8" in a and "cold" not in a:
+                    extra = f"   ({v['dispatch_fp8_bytes'] / b / 1e3:.0f} GB/s)"
+                if a in ("combine_us", "combine_kernel_us"):
+                    extra = f"   ({v['combine_bytes'] / b / 1e3:.0f} GB/s)"
+                L.append(f"    {a:50s} {b}{extra}")
+        if "fifo_stress" in v:
+            L.append("  [fifo_stress]  closed loop: each pusher (one wavefront) pushes a command, waits until the proxy "
+                     "has popped it, pushes the next; 8 channels")
+            for a, b in v["fifo_stress"].items():
+                L.append(f"    {a:28s} {b['Mcmd_per_s']:8.2f} Mcmd/s   push->popped mean {b['mean_latency_us']:8.2f} us"
+                         f"  max {b['max_latency_us']:8.1f} us")
+        for key in [k for k in v if k.startswith("per_token_")]:
+            L.append(f"  [{key}]  per-token dispatch with an option of the proxy (packing, pacing, where the fence sits)")
+            for a, b in v[key].items():
+                L.append(f"    {a:50s} {b}")
+        for key in [k for k in v if k.startswith("ht_")]:
+            what = ("ring-buffer channels: sending step -> ring slot -> receiving step -> packed buffer (one workgroup "
+                    "per slice plays both ends in turns); Write / tail / head messages through the proxy; host clock "
+                    "from the ep_ht_dispatch call to ep_wait (Drains popped)" if key.startswith("ht_ring")
+                    else "high-throughput mode: one copy per (token, group of ranks), two-level reduce")
+            L.append(f"  [{key}]  {what}")
+            for a, b in v[key].items():
+                L.append(f"    {a:50s} {b}")
+    return "\n".join(L) + "\n"
+
+
 def run_suite(args) -> int:
     """Per-call timings of all five workloads : layout, dispatch
     with the ring off / per-token / chunk32, FP8 where the workload names it, combine, the command
@@ -105,7 +194,8 @@ def run_suite(args) -> int:
         o = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
         db, cb = algorithmic_bytes(T, H, K, my_rows, "bf16")
         fb, _ = algorithmic_bytes(T, H, K, my_rows, "fp8")
-        res = {"T": T, "H": H, "E": E, "K": K, "R": R, "S": S, "dispatch_bytes": db, "combine_bytes": cb}
+        res = {"T": T, "H": H, "E": E, "K": K, "R": R, "S": S, "dispatch_bytes": db, "combine_bytes": cb,
+               "dispatch_fp8_bytes": fb}
         small = rows * H * 2 < (128 << 20)
         for threads, chans in (((1, 8), (4, 8), (4, 64)) if cid in (4, 5) else ((4, 8),)):
             with EPRunner(R, E, K, H, T, S=S, num_proxy_threads=threads, num_channels=chans,
@@ -134,7 +224,7 @@ def run_suite(args) -> int:
                         rr["dispatch_bf16_ring_off_cold_us"] = timed(
                             lambda: r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=ep.EP_CMD_NONE), cold=True)
                         rr["combine_cold_us"] = timed(lambda: r.combine(recv, d_w, lay.dst_row[0], o), cold=True)
-                    if cid in (3, 5):
+                    if cid in (3, 4, 5):
                         rr["dispatch_fp8_ring_off_us"] = timed(
                             lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3,
                                                cmd_mode=ep.EP_CMD_NONE))
@@ -160,10 +250,27 @@ def run_suite(args) -> int:
                     rr[f"{mode}_cmds"] = st["cmds"]
                     rr[f"{mode}_launch_to_last_counter_us"] = round(e2e[len(e2e) // 2], 1)
                     rr[f"{mode}_proxy_Mcmd_per_s"] = round(rate[len(rate) // 2], 2)
-                    if cid in (3, 5):
+                    if cid in (3, 4, 5):
                         rr[f"dispatch_fp8_{mode}_us"] = timed(
                             lambda: r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=ep.EP_FP8_E4M3, cmd_mode=cm),
                             after=r.wait)
+                if S > 1 and threads == 4 and chans == 8:
+                    # the decode workload's inbound share: what the other S - 1 source ranks send into this rank's
+                    # partition (rank filter = 0), one ep_dispatch per source, queued back to back
+                    xs = [bits_to_bf16(g.activations(cfg, s_)) for s_ in range(1, S)]
+                    inbound_rows = int((idx[1:] // cfg.E_loc == 0).sum())
+                    for mode in ("none", "per_token"):
+                        cm = ep.CMD_MODES[mode]
+
+                        def inbound():
+                            for s_ in range(1, S):
+                                r.dispatch(xs[s_ - 1], d_idx[s_], lay, recv, src=s_, rank_filter=0, cmd_mode=cm)
+
+                        rr[f"inbound_share_{S - 1}_sources_{mode}_us"] = timed(
+                            inbound, n=10, after=(r.wait if cm != ep.EP_CMD_NONE else None))
+                    rr["inbound_share_rows"] = inbound_rows
+                    rr["send_share_per_token_us"] = rr["dispatch_bf16_per_token_us"]
+                    del xs
                 if threads == 4 and chans == 8 and T <= 512:
                     # one whole low-latency step - layout, per-token dispatch with commands through the proxy,
                     # GPU-side wait for the posted counters, combine - launched call by call and replayed
@@ -252,6 +359,28 @@ def run_suite(args) -> int:
                         lambda: ep.ep_combine_partial(r1.h, recv, d_w, L.dst_row[0], fk[0], Lg.dst_row[0], T, rows,
                                                       rows_g, partial))
                     hh["combine_final_us"] = timed(lambda: rg.combine(partial, ones, Lg.dst_row[0], o))
+
+                    # the whole high-throughput step, host clock over 20 steps queued back to back; the experts'
+                    # outputs y sit in a buffer of their own (here: the flat receive buffer of the plain path)
+                    def ht_step():
+                        ep.ep_dedup(r1.h, d_idx, T, G, gi, fk)
+                        L2 = r1.layout(d_idx)
+                        Lg2 = rg.layout(gi)
+                        rg.dispatch(d_x, gi[0], Lg2, recv_g, cmd_mode=ep.EP_CMD_CHUNK32)
+                        ep.ep_gather_index(r1.h, L2.dst_row[0], Lg2.dst_row[0], fk[0], T, rows, index)
+                        ep.ep_combine_partial(r1.h, recv, d_w, L2.dst_row[0], fk[0], Lg2.dst_row[0], T, rows, rows_g,
+                                              partial)
+                        rg.combine(partial, ones, Lg2.dst_row[0], o)
+                        rg.wait()
+
+                    for _ in range(3):
+                        ht_step()
+                    torch.cuda.synchronize()
+                    c0 = time.perf_counter()
+                    for _ in range(20):
+                        ht_step()
+                    torch.cuda.synchronize()
+                    hh["ht_step_us"] = round((time.perf_counter() - c0) / 20 * 1e6, 1)
                     res[f"ht_ranks_per_group{G}"] = hh
                     del recv_g, partial
             # sender-side policies of the proxy on the per-token stream: best-effort packing, pacing
@@ -332,7 +461,11 @@ def run_suite(args) -> int:
         out[cfg.name] = res
         del recv, rq, rs, d_x, o
         torch.cuda.empty_cache()
-    print(json.dumps({"suite": out}))
+    table = format_suite(out)
+    os.makedirs(os.path.dirname(os.path.abspath(args.suite_out)), exist_ok=True)
+    with open(args.suite_out, "w") as f:
+        f.write(table)
+    print(json.dumps({"suite": out, "table": args.suite_out}))
     return 0
 
 
@@ -362,6 +495,8 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also launch N plain device copies of 1 GiB (counter calibration for rocprofv3 --pmc)")
     ap.add_argument("--suite", action="store_true", help="per-call timings of all five workloads instead")
+    ap.add_argument("--suite-out", default=os.path.join(ROOT, "gpurun_out", "per_call_timings_all_workloads.txt"),
+                    help="where --suite writes its formatted table (copy it to profiles/ to commit it)")
     args = ap.parse_args()
     if args.suite and args.gpus == 1:
         return run_suite(args)
@@ -451,6 +586,23 @@ def main() -> int:
         ceilings[name + "_GBs"] = round(probe_a.numel() * (2 if kind == 2 else 1) / best / 1e6, 1)
     del probe_a, probe_b
     torch.cuda.empty_cache()
+    # ... and of the two access patterns themselves, on this workload's own destination rows: the dispatch's
+    # stores without its loads, the combine's loads without its stores (plain write and read streams are the
+    # only traffic that reaches the figures above; rows scattered over expert regions do not)
+    if payload == "bf16":
+        lay0 = r.layout(d_idx)
+        sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+        for kind, name, buf in ((0, "row_scatter_write", recv), (1, "row_gather_read", y)):
+            best = 1e9
+            for i in range(13):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ep.ep_row_probe(kind, lay0.dst_row[0], K, T, 2 * H, buf, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                if i >= 3:
+                    best = min(best, e0.elapsed_time(e1))
+            ceilings[name + "_GBs"] = round(rows * 2 * H / best / 1e6, 1)
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)

@@ -50,6 +50,16 @@ int ep_fifo_stress(ep_handle *h, int32_t pushers, int32_t cmds_per_pusher, uint6
  * 16; buffers are caller-owned device memory.  Needs no handle. */
 int ep_bw_probe(int32_t kind, const void *d_src, void *d_dst, int64_t bytes, void *stream);
 
+/* ep_row_probe - the memory access pattern of the path's two big kernels without the other half of their
+ * traffic, to tell what the pattern itself can reach on this device (no part of the method): every item i
+ * (a token) names k rows, d_rowmap[i*k .. i*k+k) (int32, device; entries < 0 or >= buf_rows are skipped), of
+ * row_bytes bytes each in d_buf.  kind 0 stores a constant to every such row with the dispatch's kind of store
+ * and wave shape (nothing is read); kind 1 reads every such row with the combine's kind of load and wave shape
+ * (nothing is written; d_sink, 16 bytes of device memory, only keeps the loads alive).  row_bytes a multiple of
+ * 16.  Needs no handle. */
+int ep_row_probe(int32_t kind, const int32_t *d_rowmap, int32_t k, int64_t items, int32_t row_bytes, int64_t buf_rows,
+                 void *d_buf, void *d_sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -68,7 +68,8 @@ EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_layout_static", "
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
-           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters", "ep_fifo_stress", "ep_captured", "ep_expect", "ep_profile", "ep_profile_read"]
+           "ep_register_heaps", "ep_ht_dispatch", "ep_ring_counters", "ep_fifo_stress", "ep_captured", "ep_expect", "ep_profile", "ep_profile_read",
+           "ep_row_probe"]
 
 _lib = None
 
@@ -116,6 +117,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_host_check_completion.argtypes = [vp, i32, u64]
     L.ep_host_expect_atomics.argtypes = [vp, i32]
     L.ep_bw_probe.argtypes = [i32, vp, vp, i64, vp]
+    L.ep_row_probe.argtypes = [i32, vp, i32, i64, i32, i64, vp, vp, vp]
     L.ep_register_heaps.argtypes = [vp, vp, i64, vp, i64]
     L.ep_ht_dispatch.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp]
     L.ep_ring_counters.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
@@ -322,6 +324,12 @@ def ep_host_check_completion(h: int, channel: int, idx: int) -> bool:
 def ep_bw_probe(kind: int, src, dst, nbytes: int, stream=None) -> None:
     """kind 0 read src, 1 write dst, 2 copy src -> dst (plain streaming kernels, for ceilings)."""
     _check("ep_bw_probe", load_library().ep_bw_probe(kind, _ptr(src), _ptr(dst), nbytes, _stream(stream)))
+
+
+def ep_row_probe(kind: int, rowmap, k: int, items: int, row_bytes: int, buf, sink, stream=None) -> None:
+    """kind 0: the dispatch's stores without its loads; 1: the combine's loads without its stores (see ep_diag.h)."""
+    _check("ep_row_probe", load_library().ep_row_probe(kind, _ptr(rowmap), k, items, row_bytes, buf.shape[0], _ptr(buf),
+                                                       _ptr(sink), _stream(stream)))
 
 
 def ep_last_error() -> str:

@@ -944,6 +944,18 @@ int ep_bw_probe(int32_t kind, const void *d_src, void *d_dst, int64_t bytes, voi
   return HIP_OK((hipError_t)launch_bw_probe(kind, d_src, d_dst, bytes, stream)) ? EP_OK : EP_EHIP;
 }
 
+int ep_row_probe(int32_t kind, const int32_t *d_rowmap, int32_t k, int64_t items, int32_t row_bytes, int64_t buf_rows,
+                 void *d_buf, void *d_sink, void *stream) {
+  if (kind < 0 || kind > 1 || !d_rowmap || !d_buf || !d_sink) return EP_EINVAL;
+  if (k < 1 || k > 64 || items < 0 || items >= (1ll << 31) || buf_rows < 0) return EP_EINVAL;
+  if (row_bytes < 16 || (row_bytes & 15) || row_bytes > (1 << 20)) return EP_EINVAL;
+  if (((uintptr_t)d_buf | (uintptr_t)d_sink) & 15) return EP_EINVAL;
+  if (items * (((int64_t)row_bytes / 16 + 63) / 64) >= (1ll << 33)) return EP_EINVAL;  // grid index range
+  return HIP_OK((hipError_t)launch_row_probe(kind, d_rowmap, k, items, row_bytes, buf_rows, d_buf, d_sink, stream))
+             ? EP_OK
+             : EP_EHIP;
+}
+
 int ep_profile(ep_handle *h, int32_t on) {
   if (!h) return EP_EINVAL;
   if (h->host_only) return EP_ESTATE;

@@ -215,5 +215,7 @@ int launch_gather_index(const GatherIndexArgs &a, void *stream);
 int launch_combine_partial(const CombinePartialArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
 int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void *stream);
+int launch_row_probe(int kind, const int32_t *rowmap, int k, long long items, int row_bytes, long long buf_rows,
+                     void *buf, void *sink, void *stream);
 
 }  // namespace ep

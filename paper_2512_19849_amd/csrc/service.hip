@@ -162,6 +162,50 @@ int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void 
   return (int)hipGetLastError();
 }
 
+// Row-pattern probes: the dispatch's stores without its loads (every item stores a constant to the slices of
+// its k rows, write-through as the dispatch does), and the combine's loads without its stores (k streaming
+// loads per lane, nothing written).  One wave per (item, 64-vector slice); rows outside the buffer are skipped.
+template <bool WRITE>
+__global__ __launch_bounds__(256) void row_probe_kernel(const int32_t *rowmap, int k, long long items, int nvec,
+                                                        long long buf_rows, u32x4 *buf, u32x4 *sink) {
+  const int lane = lane_id();
+  const int parts = (nvec + 63) / 64;
+  const long long w = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long item = w / parts;
+  const int v = (int)(w % parts) * 64 + lane;
+  if (item >= items) return;
+  int row = lane < k ? rowmap[item * k + lane] : -1;
+  if (row >= buf_rows) row = -1;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int j = 0; j < k; ++j) {
+    const int r = __builtin_amdgcn_readlane(row, j);
+    if (r < 0 || v >= nvec) continue;
+    u32x4 *p = buf + (size_t)r * nvec + v;
+    if (WRITE) {
+      store_payload(p, u32x4{1u, 2u, 3u, (unsigned)item});
+    } else {
+      const u32x4 x = __builtin_nontemporal_load(p);
+      acc[0] ^= x[0], acc[1] ^= x[1], acc[2] ^= x[2], acc[3] ^= x[3];
+    }
+  }
+  if (!WRITE && acc[0] == 0x9E3779B9u && acc[1] == 0x7F4A7C15u && acc[2] == 0xBF58476Du && acc[3] == 0x1CE4E5B9u) *sink = acc;
+}
+
+int launch_row_probe(int kind, const int32_t *rowmap, int k, long long items, int row_bytes, long long buf_rows,
+                     void *buf, void *sink, void *stream) {
+  const int nvec = row_bytes / 16;
+  const long long waves = items * ((nvec + 63) / 64);
+  if (waves <= 0) return 0;
+  const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+  if (kind == 0)
+    hipLaunchKernelGGL(row_probe_kernel<true>, grid, block, 0, (hipStream_t)stream, rowmap, k, items, nvec, buf_rows,
+                       (u32x4 *)buf, (u32x4 *)sink);
+  else
+    hipLaunchKernelGGL(row_probe_kernel<false>, grid, block, 0, (hipStream_t)stream, rowmap, k, items, nvec, buf_rows,
+                       (u32x4 *)buf, (u32x4 *)sink);
+  return (int)hipGetLastError();
+}
+
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream) {
   if (n <= 0) return 0;
   hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, p, v, n);

@@ -20,6 +20,7 @@ int launch_gather_index(const GatherIndexArgs&, void*) { return 0; }
 int launch_combine_partial(const CombinePartialArgs&, void*) { return 0; }
 int launch_bw_probe(int, const void*, void*, long long, void*) { return 0; }
 int launch_copy_batch(const CopyBatchArgs&, void*) { return 0; }
+int launch_row_probe(int, const int32_t*, int, long long, int, long long, void*, void*, void*) { return 0; }
 int launch_ht_ring(const HtRingArgs&, const Tunables&, void*) { return 0; }
 int launch_fifo_stress(const RingDev&, int, int, unsigned long long*, unsigned long long*, void*) { return 0; }
 }
