@@ -76,9 +76,11 @@ enum ep_cmd_mode {
   EP_CMD_MODE_MASK = 0xFF,
   EP_CMD_ATOMICS_FIRST = 0x100, /* push every count Atomic before any Write (forces the fence path) */
   EP_CMD_DRAIN = 0x200,         /* last wave pushes Drain on every channel and blocks on Check-completion */
-  EP_CMD_NO_PLACEMENT = 0x400   /* EP_CMD_PER_TOKEN + EP_BF16 only: the kernel stores no payload, it only pushes
-                                   the commands; the proxy moves the rows (needs ep_register_heaps with the
-                                   source heap = d_x).  The low-latency mode as the paper runs it. */
+  EP_CMD_NO_PLACEMENT = 0x400   /* EP_CMD_PER_TOKEN with registered heaps (ep_register_heaps): the kernel places no
+                                   row at its destination, it only pushes the commands; the proxy moves the rows.
+                                   The low-latency mode as the paper runs it.  EP_BF16: nothing is stored at all,
+                                   the source heap is d_x.  EP_FP8_E4M3: the kernel quantises every token once
+                                   and stores it as ONE message (see ep_dispatch) at row t of the source heap. */
 };
 
 enum ep_flags {
@@ -218,7 +220,13 @@ int ep_layout_static(const int32_t *d_topk_idx, int32_t S, int32_t T, int32_t K,
  * destination expert mod C): Writes at the granularity cmd_mode selects, after
  * the rows they describe are stored, and per destination expert one Atomic
  * carrying count[e] (also when 0).  A full channel blocks the pushing wave
- * until the proxy pops (bounded by spin_timeout_ms). */
+ * until the proxy pops (bounded by spin_timeout_ms).
+ * FP8 rows that the proxy moves (heaps registered, commands on; Section 2.1: the ~7 KB FP8 token is ONE
+ * message): a row is then H codes followed by its H/128 fp32 scales, padded to a multiple of 16 bytes
+ * (7392 bytes at H = 7168), d_recv_scale must be NULL, and d_recv is the source heap: [recv_rows] message
+ * rows laid out like the receive heap for the chunk modes, [T] message rows (row t = token t) for
+ * EP_CMD_PER_TOKEN | EP_CMD_NO_PLACEMENT.  The destination heap receives [recv_rows] message rows;
+ * ep_fp8_unpack splits them into codes and scales. */
 int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
                 const int32_t *d_dst_row, const int32_t *d_count, const int32_t *d_base,
                 int32_t T, int32_t src_rank, int32_t dst_rank_filter,
@@ -236,6 +244,12 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx,
 int ep_combine(ep_handle *h, const void *d_y, const float *d_topk_w,
                const int32_t *d_dst_row, int32_t T, int64_t y_rows,
                void *d_out, void *stream);
+
+/* ep_fp8_unpack - receiver side of FP8 rows that travelled as messages (Section 2.1: a token is one ~7 KB FP8
+ * message; Section 3.2: the proxy moves it between registered heaps): splits `rows` message rows of d_msgs
+ * (each H codes + H/128 fp32 scales, padded to 16 bytes) into d_recv (uint8 [rows, H]) and d_recv_scale
+ * (fp32 [rows, H/128]).  Call it once the rows have arrived (after ep_wait, or after ep_recv_wait on `stream`). */
+int ep_fp8_unpack(ep_handle *h, const void *d_msgs, int64_t rows, void *d_recv, float *d_recv_scale, void *stream);
 
 /* ep_wait - the host-side view of completion (Section 3.3: an Atomic is applied
  * only when the Writes it vouches for have arrived; Section 4.1: completion is a
@@ -290,7 +304,10 @@ int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, con
  * so they regularly overtake their data and wait in the control buffer.
  *   chunk modes : ep_dispatch packs rows into the source heap (pass it as
  *                 d_recv); a chunk's source offset equals its destination offset.
- *   per-token   : with EP_CMD_NO_PLACEMENT the source heap is d_x itself.
+ *   per-token   : with EP_CMD_NO_PLACEMENT the source heap is d_x itself (bf16), or
+ *                 the [T] message rows the kernel quantises the tokens into (FP8;
+ *                 pass them as d_recv).
+ * FP8 rows travel as one message each: see ep_dispatch and ep_fp8_unpack.
  * Call it only while no dispatch is in flight; NULL bases unregister. */
 int ep_register_heaps(ep_handle *h, const void *d_src_base, int64_t src_bytes, void *d_dst_base, int64_t dst_bytes);
 

@@ -310,6 +310,27 @@ def row_bytes(H: int, payload: str) -> int:
     return (H + H // 32 + 15) // 16 * 16
 
 
+def fp8_message_rows(q: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """FP8 rows as they travel when the proxy moves them (Section 2.1: a token is ONE ~7 KB FP8 message):
+    per row the H codes, then the H/128 fp32 scales as stored (little-endian), then zero bytes up to the
+    16-byte offset granule.  uint8 [rows, row_bytes(H, "fp8")]."""
+    rows, H = q.shape
+    assert scale.shape == (rows, H // 128) and q.dtype == np.uint8 and scale.dtype == np.float32
+    out = np.zeros((rows, row_bytes(H, "fp8")), np.uint8)
+    out[:, :H] = q
+    out[:, H:H + H // 32] = np.ascontiguousarray(scale).view(np.uint8).reshape(rows, H // 32)
+    return out
+
+
+def fp8_split_messages(msgs: np.ndarray, H: int):
+    """Inverse of fp8_message_rows: (codes uint8 [rows, H], scales fp32 [rows, H/128])."""
+    rows = msgs.shape[0]
+    assert msgs.shape[1] == row_bytes(H, "fp8")
+    q = np.ascontiguousarray(msgs[:, :H])
+    scale = np.ascontiguousarray(msgs[:, H:H + H // 32]).view(np.float32).reshape(rows, H // 128)
+    return q, scale
+
+
 def decode_cmd(words: Iterable[int]) -> Dict[str, int]:
     w0, w1, w2, w3 = (int(v) & 0xFFFFFFFF for v in words)
     return dict(gen=w0 >> 31, gen_hi=w3 >> 31, op=(w0 >> 28) & 7, src=(w0 >> 20) & 0xFF,

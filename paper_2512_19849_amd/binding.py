@@ -64,7 +64,7 @@ class ep_stats_t(C.Structure):
         return d
 
 
-EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_layout_static", "ep_dispatch", "ep_combine", "ep_recv_wait", "ep_wait",
+EXPORTS = ["ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_layout_static", "ep_dispatch", "ep_combine", "ep_fp8_unpack", "ep_recv_wait", "ep_wait",
            "ep_counters", "ep_tail_counters", "ep_barrier", "ep_dedup", "ep_gather_index", "ep_combine_partial",
            "ep_stats", "ep_reset_stats", "ep_cmd_log", "ep_event_log", "ep_host_push",
            "ep_host_check_completion", "ep_host_expect_atomics", "ep_last_error", "ep_bw_probe",
@@ -101,6 +101,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     L.ep_layout_static.argtypes = [vp, i32, i32, i32, i32, i32] + [vp] * 8 + [vp, vp]
     L.ep_dispatch.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp]
     L.ep_combine.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
+    L.ep_fp8_unpack.argtypes = [vp, vp, i64, vp, vp, vp]
     L.ep_wait.argtypes = [vp]
     L.ep_barrier.argtypes = [vp, vp]
     L.ep_dedup.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -202,6 +203,11 @@ def ep_dispatch(h: int, x, topk_idx, dst_row, count, base, T: int, src_rank: int
 def ep_combine(h: int, y, topk_w, dst_row, T: int, y_rows: int, out, stream=None) -> None:
     _check("ep_combine", load_library().ep_combine(h, _ptr(y), _ptr(topk_w), _ptr(dst_row), T, y_rows, _ptr(out),
                                                    _stream(stream)))
+
+
+def ep_fp8_unpack(h: int, msgs, rows: int, recv, recv_scale, stream=None) -> None:
+    _check("ep_fp8_unpack", load_library().ep_fp8_unpack(h, _ptr(msgs), rows, _ptr(recv), _ptr(recv_scale),
+                                                         _stream(stream)))
 
 
 def ep_dedup(h: int, topk_idx, T: int, ranks_per_group: int, group_idx, first_k, stream=None) -> None:

@@ -490,23 +490,32 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
     cmd_mode |= EP_CMD_DRAIN;
   }
   if (cmd_mode & ~(EP_CMD_MODE_MASK | EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN | EP_CMD_NO_PLACEMENT)) return EP_EINVAL;
-  if (const char *dbase = h->dst_base.load(std::memory_order_acquire)) {
-    // the proxy performs the writes: rows travel as 16-bit words only, and the offsets the kernel
-    // is about to put into its commands must be relative to the registered source heap
-    if (mode != EP_CMD_NONE) {
-      if (payload != EP_BF16) return EP_EINVAL;
-      const bool chunked = mode != EP_CMD_PER_TOKEN;
-      if (chunked && ((cmd_mode & EP_CMD_NO_PLACEMENT) || d_recv != (const void *)h->src_base.load())) return EP_EINVAL;
-      if (!chunked && (!(cmd_mode & EP_CMD_NO_PLACEMENT) || d_x != (const void *)h->src_base.load())) return EP_EINVAL;
-      if (!chunked && (uint64_t)recv_rows * 2u * (uint64_t)c.hidden > h->dst_bytes) return EP_EINVAL;
+  // With registered heaps and commands on, the proxy moves the rows.  FP8 rows then travel as one message
+  // each (codes, scales, padding), so there is no separate scale array on the sending side.
+  const char *const dbase = h->dst_base.load(std::memory_order_acquire);
+  const bool proxy_moves = dbase != nullptr && mode != EP_CMD_NONE;
+  const bool msg_rows = proxy_moves && payload == EP_FP8_E4M3;
+  if (proxy_moves) {
+    // the offsets the kernel is about to put into its commands must be relative to the registered heaps
+    const uint64_t rb = row_bytes_of(c.hidden, payload);
+    const void *sbase = (const void *)h->src_base.load();
+    const bool chunked = mode != EP_CMD_PER_TOKEN;
+    if (chunked) {  // the kernel packs a send heap laid out like the receive heap; chunks are forwarded
+      if ((cmd_mode & EP_CMD_NO_PLACEMENT) || d_recv != sbase) return EP_EINVAL;
+      if ((uint64_t)recv_rows * rb > h->src_bytes || (uint64_t)recv_rows * rb > h->dst_bytes) return EP_EINVAL;
+    } else {        // every row is forwarded on its own, out of x (bf16) or out of one message per token (FP8)
+      if (!(cmd_mode & EP_CMD_NO_PLACEMENT)) return EP_EINVAL;
+      if (payload == EP_BF16 && d_x != sbase) return EP_EINVAL;
+      if (payload == EP_FP8_E4M3 && (d_recv != sbase || (uint64_t)T * rb > h->src_bytes)) return EP_EINVAL;
+      if ((uint64_t)recv_rows * rb > h->dst_bytes) return EP_EINVAL;
     }
-    (void)dbase;
+    if (msg_rows && d_recv_scale) return EP_EINVAL;
   } else if (cmd_mode & EP_CMD_NO_PLACEMENT) {
     return EP_EINVAL;
   }
   if (recv_rows < 0 || recv_rows > c.heap_rows) return EP_EINVAL;
   if (T > 0 && (!d_x || !d_topk_idx || !d_dst_row || !d_recv)) return EP_EINVAL;
-  if ((payload == EP_FP8_E4M3) != (d_recv_scale != nullptr)) return EP_EINVAL;
+  if (!msg_rows && (payload == EP_FP8_E4M3) != (d_recv_scale != nullptr)) return EP_EINVAL;
   if (mode != EP_CMD_NONE) {
     if (h->nthreads < 1 || !d_count || !d_base) return EP_EINVAL;
     if (mode == EP_CMD_NONE && (cmd_mode & (EP_CMD_ATOMICS_FIRST | EP_CMD_DRAIN))) return EP_EINVAL;
@@ -534,6 +543,7 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
   a.filter = dst_rank_filter;
   a.cmd_mode = cmd_mode;
   a.row_bytes = row_bytes_of(c.hidden, payload);
+  a.msg_rows = msg_rows ? (mode == EP_CMD_PER_TOKEN ? 2 : 1) : 0;
   a.chunks_per_expert = h->chunks_per_expert;
   a.chunk_cnt = h->chunk_cnt;
   a.expert_done = h->expert_done;
@@ -670,6 +680,19 @@ int ep_combine_partial(ep_handle *h, const void *d_y, const float *d_topk_w, con
   a.error = h->ring.error;
   h->fresh_buf.store(nullptr, std::memory_order_relaxed);
   return HIP_OK((hipError_t)launch_combine_partial(a, stream)) ? EP_OK : EP_EHIP;
+}
+
+int ep_fp8_unpack(ep_handle *h, const void *d_msgs, int64_t rows, void *d_recv, float *d_recv_scale, void *stream) {
+  if (!h) return EP_EINVAL;
+  if (h->host_only) return EP_ESTATE;
+  if (rows < 0 || rows > h->cfg.heap_rows) return EP_EINVAL;
+  if (rows == 0) return EP_OK;
+  if (!d_msgs || !d_recv || !d_recv_scale) return EP_EINVAL;
+  if (((uintptr_t)d_msgs | (uintptr_t)d_recv) & 15) return EP_EINVAL;
+  return HIP_OK((hipError_t)launch_fp8_unpack(d_msgs, rows, h->cfg.hidden, row_bytes_of(h->cfg.hidden, EP_FP8_E4M3),
+                                              d_recv, d_recv_scale, stream))
+             ? EP_OK
+             : EP_EHIP;
 }
 
 int ep_barrier(ep_handle *h, void *stream) {

@@ -222,13 +222,25 @@ __global__ void dispatch_fp8_kernel(DispatchArgs a) {
       }
 #pragma unroll
     for (int i = 0; i < VPL; ++i) quant16(lo[i], hi[i], q[i], sc[i]);
-    unsigned long long mm = vmask;
+    // Where a row goes: into the two receive arrays (codes, scales), or - when the proxy moves the rows -
+    // as ONE message of row_bytes bytes (the H codes, then the H/128 fp32 scales, padded to 16 bytes:
+    // the ~7 KB token of Section 2.1) into the send heap: at its destination row for chunk commands
+    // (the heap mirrors the receive heap), or once, at the token's own row, for per-token commands.
+    unsigned long long mm = a.msg_rows == 2 ? 1ull : vmask;
     while (mm) {
       const int k = __builtin_ctzll(mm);
       mm &= mm - 1;
-      const int row = __builtin_amdgcn_readlane(m.row, k);
-      u32x4 *dq = (u32x4 *)a.recv + (size_t)row * npair;
-      float *ds = a.recv_scale + (size_t)row * nblk;
+      const int row = a.msg_rows == 2 ? t : __builtin_amdgcn_readlane(m.row, k);
+      u32x4 *dq;
+      float *ds;
+      if (a.msg_rows) {
+        char *msg = (char *)a.recv + (size_t)row * a.row_bytes;
+        dq = (u32x4 *)msg;
+        ds = (float *)(msg + a.H);
+      } else {
+        dq = (u32x4 *)a.recv + (size_t)row * npair;
+        ds = a.recv_scale + (size_t)row * nblk;
+      }
 #pragma unroll
       for (int i = 0; i < VPL; ++i)
         if (p0 + i * 64 < npair) {

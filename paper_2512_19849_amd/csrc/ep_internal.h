@@ -71,6 +71,9 @@ struct DispatchArgs {
   int32_t tokens_per_block;
   int32_t block_cmds;      // the workgroup's first wave pushes the commands of all its tokens
   int32_t reverse;         // workgroups take the tokens from the last one down (see ep_dispatch)
+  int32_t msg_rows;        // FP8 only: 0 = codes and scales go to the two receive arrays; 1 = every row is one message
+                           // (codes, scales, padding: row_bytes) at its destination row of `recv`; 2 = one message
+                           // per token at row t of `recv` (the proxy forwards it to every destination)
   int32_t chunks_per_expert;
   int32_t *chunk_cnt;      // scratch [E * chunks_per_expert], zero between calls
   int32_t *expert_done;    // scratch [E], zero between calls
@@ -214,6 +217,7 @@ int launch_dedup(const DedupArgs &a, void *stream);
 int launch_gather_index(const GatherIndexArgs &a, void *stream);
 int launch_combine_partial(const CombinePartialArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, uint32_t v, long long n, void *stream);
+int launch_fp8_unpack(const void *msgs, long long rows, int H, unsigned row_bytes, void *q, float *scale, void *stream);
 int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void *stream);
 int launch_row_probe(int kind, const int32_t *rowmap, int k, long long items, int row_bytes, long long buf_rows,
                      void *buf, void *sink, void *stream);

@@ -162,6 +162,32 @@ int launch_bw_probe(int kind, const void *src, void *dst, long long bytes, void 
   return (int)hipGetLastError();
 }
 
+// Receiver side of FP8 rows that travelled as messages (codes, scales, padding): split them into the code and
+// the scale array.  One wave per (row, 64 vectors of codes); the wave of a row's first slice also moves the scales.
+__global__ __launch_bounds__(256) void fp8_unpack_kernel(const char *msgs, long long rows, int H, unsigned row_bytes,
+                                                         u32x4 *q, float *scale) {
+  const int lane = lane_id();
+  const int nvec = H >> 4, parts = (nvec + 63) / 64, nblk = H >> 7;
+  const long long w = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long row = w / parts;
+  const int part = (int)(w % parts);
+  if (row >= rows) return;
+  const char *msg = msgs + (size_t)row * row_bytes;
+  const int v = part * 64 + lane;
+  if (v < nvec) q[(size_t)row * nvec + v] = __builtin_nontemporal_load((const u32x4 *)msg + v);
+  if (part == 0)
+    for (int b = lane; b < nblk; b += 64) scale[(size_t)row * nblk + b] = __builtin_nontemporal_load((const float *)(msg + H) + b);
+}
+
+int launch_fp8_unpack(const void *msgs, long long rows, int H, unsigned row_bytes, void *q, float *scale, void *stream) {
+  const long long waves = rows * (((H >> 4) + 63) / 64);
+  if (waves <= 0) return 0;
+  if (waves >= (1ll << 33)) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(fp8_unpack_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, (hipStream_t)stream,
+                     (const char *)msgs, rows, H, row_bytes, (u32x4 *)q, scale);
+  return (int)hipGetLastError();
+}
+
 // Row-pattern probes: the dispatch's stores without its loads (every item stores a constant to the slices of
 // its k rows, write-through as the dispatch does), and the combine's loads without its stores (k streaming
 // loads per lane, nothing written).  One wave per (item, 64-vector slice); rows outside the buffer are skipped.

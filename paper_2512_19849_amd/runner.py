@@ -90,10 +90,15 @@ class EPRunner:
 
     def dispatch(self, x: torch.Tensor, topk_idx_s: torch.Tensor, lay: LayoutOut, recv: torch.Tensor,
                  recv_scale: Optional[torch.Tensor] = None, src: int = 0, rank_filter: int = -1,
-                 payload: int = ep.EP_BF16, cmd_mode: int = ep.EP_CMD_NONE) -> None:
+                 payload: int = ep.EP_BF16, cmd_mode: int = ep.EP_CMD_NONE, recv_rows: Optional[int] = None) -> None:
+        """recv_rows: rows of the destination; defaults to recv's own row count (it differs when recv is the [T]
+        message rows of a per-token FP8 dispatch that the proxy forwards)."""
         T = x.shape[0]
         ep.ep_dispatch(self.h, x, topk_idx_s, lay.dst_row[src], lay.count[src], lay.base[src], T, src, rank_filter,
-                       payload, cmd_mode, recv, recv_scale, recv.shape[0])
+                       payload, cmd_mode, recv, recv_scale, recv.shape[0] if recv_rows is None else recv_rows)
+
+    def fp8_unpack(self, msgs: torch.Tensor, recv: torch.Tensor, recv_scale: torch.Tensor) -> None:
+        ep.ep_fp8_unpack(self.h, msgs, recv.shape[0], recv, recv_scale)
 
     def combine(self, y: torch.Tensor, topk_w_s: torch.Tensor, dst_row_s: torch.Tensor, out: torch.Tensor) -> None:
         ep.ep_combine(self.h, y, topk_w_s, dst_row_s, out.shape[0], y.shape[0], out)

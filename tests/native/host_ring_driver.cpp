@@ -12,6 +12,7 @@ int launch_layout(const LayoutArgs&, const Tunables&, void*, const LaunchTiming*
 int launch_dispatch(const DispatchArgs&, int, const Tunables&, void*, const LaunchTiming*) { return 0; }
 int launch_combine(const CombineArgs&, const Tunables&, void*, const LaunchTiming*) { return 0; }
 int launch_fill_u32(uint32_t*, uint32_t, long long, void*) { return 0; }
+int launch_fp8_unpack(const void*, long long, int, unsigned, void*, float*, void*) { return 0; }
 int static_layout_scratch(LayoutArgs*) { return 0; }
 int launch_recv_wait(const RecvWaitArgs&, void*) { return 0; }
 int launch_barrier(const RingDev&, void*) { return 0; }

@@ -253,6 +253,77 @@ def test_proxy_performs_chunk_writes(epmod, oracle, cid, T, mask, window, mode):
         assert out["stats"]["drains"] == 8
 
 
+@pytest.mark.parametrize("cid,T,mask,window,mode,threads", [
+    (3, None, 0.0, 0, "per_token", 4), (3, 50, 0.25, 5, "per_token", 1), (3, None, 0.2, 6, "chunk32", 2),
+    (5, 700, 0.0, 16, "per_token", 3), (5, 1000, 0.05, 0, "chunk32", 4), (4, 300, 0.0, 8, "chunk32_ordered", 4),
+    ("h128", 90, 0.1, 3, "per_token", 2), ("h128", 90, 0.0, 0, "chunk32", 2), (5, None, 0.0, 0, "per_token", 4)])
+def test_proxy_performs_fp8_writes(epmod, oracle, cid, T, mask, window, mode, threads):
+    """The low-latency token as the paper sends it: FP8, ONE message per row (codes, scales, padding), moved by the
+    proxy between registered heaps.  Per token the kernel quantises every token once into its own message row and
+    only pushes commands; in the chunk modes it packs message rows into a send heap that mirrors the receive heap.
+    After ep_fp8_unpack the codes and scales equal the oracle's quantiser bit for bit, the messages equal the
+    oracle's message rows, rows nobody addressed keep their bytes, and the command stream carries message lengths."""
+    from paper_2512_19849_amd.runner import bits_to_bf16
+    if cid == "h128":                                          # one block per row: 132 bytes padded to 144
+        cfg = g.EPConfig("h128", T=T, H=128, E=8, K=2, R=4, S=1)
+        rng = np.random.default_rng(3)
+        idx = np.stack([rng.permutation(8)[:2] for _ in range(T)]).astype(np.int32)[None]
+    else:
+        cfg = g.config(cid, S=1)
+        idx, _ = g.routing_all(cfg, T)
+    if mask:
+        idx = g.mask_random(idx, mask, seed=29)
+    T = idx.shape[1]
+    x = g.activations(cfg, 0, T=T)
+    rows = int((idx >= 0).sum()) + 2
+    rb = oracle.row_bytes(cfg.H, "fp8")
+    want_lay = oracle.layout(idx, cfg.E, cfg.R)
+    oracle.set_threads(min(16, oracle.max_threads()))
+    try:
+        wq, ws, wc = oracle.dispatch_fp8(x, idx[0], want_lay["dst_row"][0], cfg.E_loc, rows)
+    finally:
+        oracle.set_threads(1)
+    hit = wc > 0
+    log = T <= 1000
+    flags = (epmod.EP_FLAG_LOG_CMDS | epmod.EP_FLAG_LOG_EVENTS) if log else 0
+    with _runner(epmod, cfg, T, flags=flags, heap_rows=rows, reorder_window=window, reorder_seed=4,
+                 num_proxy_threads=threads, spin_timeout_ms=10000) as r:
+        d_idx, d_x = _dev(idx), bits_to_bf16(x)
+        lay = r.layout(d_idx)
+        dst = torch.full((rows, rb), 0xA5, dtype=torch.uint8, device="cuda")
+        if mode == "per_token":
+            send = torch.zeros((T, rb), dtype=torch.uint8, device="cuda")
+            cm = epmod.EP_CMD_PER_TOKEN | epmod.EP_CMD_NO_PLACEMENT
+        else:
+            send = torch.zeros((rows, rb), dtype=torch.uint8, device="cuda")
+            cm = epmod.CMD_MODES[mode]
+        r.register_heaps(send, dst)
+        rq = torch.zeros((rows, cfg.H), dtype=torch.uint8, device="cuda")
+        rs = torch.zeros((rows, cfg.H // 128), dtype=torch.float32, device="cuda")
+        for rep in range(2):
+            dst.fill_(0xA5)
+            r.dispatch(d_x, d_idx[0], lay, send, None, payload=epmod.EP_FP8_E4M3, cmd_mode=cm, recv_rows=rows)
+            r.wait()
+            r.fp8_unpack(dst, rq, rs)
+            torch.cuda.synchronize()
+            got = dst.cpu().numpy()
+            used = cfg.H + cfg.H // 32
+            assert np.array_equal(got[hit][:, :used], oracle.fp8_message_rows(wq[hit], ws[hit])[:, :used]), rep
+            assert (got[~hit] == 0xA5).all(), rep
+            assert np.array_equal(rq.cpu().numpy()[hit], wq[hit]), rep
+            assert np.array_equal(rs.cpu().numpy()[hit].view(np.uint32), ws[hit].view(np.uint32)), rep
+        st = r.stats()
+        assert st["device_error"] == 0 and st["proxy_error"] == 0 and st["rejected"] == 0
+        assert st["copied_bytes"] == st["write_bytes"] == 2 * int(hit.sum()) * rb
+        if mode != "chunk32_ordered":
+            assert np.array_equal(r.counters()[0], want_lay["count"][0])
+        if log and mode != "chunk32_ordered":
+            want_cmds = oracle.expected_cmds(idx[0], want_lay, 0, cfg.E_loc, cfg.H, "fp8", mode)
+            assert oracle.cmd_multiset(epmod.ep_cmd_log(r.h)) == want_cmds + want_cmds
+            oracle.check_fence_trace(epmod.ep_event_log(r.h), want_lay["count"])
+        r.register_heaps(None, None)
+
+
 def test_proxy_performs_writes_of_another_source_into_one_rank(epmod, oracle):
     """Config 2's inbound share: source 31's rows for rank 5 only, moved by the proxy (per token out of that
     source's x; as chunks out of a send heap), with the other ranks' partitions untouched."""
@@ -342,7 +413,7 @@ def test_registered_heaps_argument_errors(epmod):
         assert rc_of(lambda: r.dispatch(x, idx[0], lay, recv, cmd_mode=epmod.EP_CMD_PER_TOKEN)) == epmod.EP_EINVAL
         assert rc_of(lambda: r.dispatch(x.clone(), idx[0], lay, recv, cmd_mode=epmod.EP_CMD_PER_TOKEN |
                                         epmod.EP_CMD_NO_PLACEMENT)) == epmod.EP_EINVAL
-        # chunks: must be packed into the registered source heap; FP8 rows are not forwarded
+        # chunks: must be packed into the registered source heap; FP8 messages carry their scales (no scale array)
         assert rc_of(lambda: r.dispatch(x, idx[0], lay, recv, cmd_mode=epmod.EP_CMD_CHUNK32)) == epmod.EP_EINVAL
         assert rc_of(lambda: r.dispatch(x, idx[0], lay, x, recv_scale=sc, payload=epmod.EP_FP8_E4M3,
                                         cmd_mode=epmod.EP_CMD_CHUNK32)) == epmod.EP_EINVAL

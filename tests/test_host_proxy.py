@@ -24,7 +24,7 @@ def ep():
 def test_library_exports_every_declared_symbol(ep):
     hdr = "".join(open(os.path.join(ROOT, "include", f)).read() for f in ("ep.h", "ep_diag.h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(ep_[a-z_]+)\s*\(", hdr))
+    names = set(re.findall(r"\b(ep_[a-z0-9_]+)\s*\(", hdr))
     assert {"ep_proxy_start", "ep_proxy_stop", "ep_layout", "ep_dispatch", "ep_combine"} <= names
     lib = ep.load_library()
     for n in sorted(names):

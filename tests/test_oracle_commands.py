@@ -59,6 +59,24 @@ def test_expected_per_token_commands_replay_to_the_dispatch_result(oracle, paylo
     assert np.array_equal(heap[:, :want.shape[1]], want)
 
 
+def test_fp8_message_rows_are_codes_then_scales_then_padding(oracle):
+    """The message a token travels as when the proxy moves FP8 rows: built here by hand from the quantiser's
+    outputs, byte for byte, for a row length with padding (H = 128 -> 132 -> 144) and one without."""
+    rng = np.random.default_rng(5)
+    for H in (128, 1024):
+        rows = 7
+        q = rng.integers(0, 255, (rows, H), dtype=np.uint8)
+        s = rng.standard_normal((rows, H // 128)).astype(np.float32)
+        m = oracle.fp8_message_rows(q, s)
+        rb = oracle.row_bytes(H, "fp8")
+        assert m.shape == (rows, rb) and m.dtype == np.uint8
+        for r in range(rows):
+            want = bytes(q[r]) + b"".join(np.float32(v).tobytes() for v in s[r])
+            assert bytes(m[r, :len(want)]) == want and not m[r, len(want):].any()
+        q2, s2 = oracle.fp8_split_messages(m, H)
+        assert np.array_equal(q2, q) and np.array_equal(s2.view(np.uint32), s.view(np.uint32))
+
+
 def test_row_bytes(oracle):
     assert oracle.row_bytes(7168, "bf16") == 14336
     assert oracle.row_bytes(7168, "fp8") == 7168 + 224          # the paper's "7 KB" token
