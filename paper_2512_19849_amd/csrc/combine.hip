@@ -259,6 +259,8 @@ __global__ __launch_bounds__(256) void combine_partial_kernel(CombinePartialArgs
       ws[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wt), k));
       ld[k] = __builtin_nontemporal_load(y + (size_t)(rows[k] >= 0 ? rows[k] : safe) * nvec + vi);
     }
+    // every group's chain first, the packed sums kept in registers; then the stores, together
+    u32x4 res[KT];
 #pragma unroll
     for (int j = 0; j < KT; ++j) {
       if (!((leaders >> j) & 1)) continue;
@@ -266,10 +268,14 @@ __global__ __launch_bounds__(256) void combine_partial_kernel(CombinePartialArgs
 #pragma unroll
       for (int k = 0; k < KT; ++k)
         if (rows[k] >= 0 && fks[k] == j) fma8(acc, ws[k], ld[k]);
+      res[j] = u32x4{pack_bf16_rne(acc[0], acc[1]), pack_bf16_rne(acc[2], acc[3]), pack_bf16_rne(acc[4], acc[5]),
+                     pack_bf16_rne(acc[6], acc[7])};
+    }
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+      if (!((leaders >> j) & 1)) continue;
       const int pr = __builtin_amdgcn_readlane(prow, j);
-      u32x4 o = {pack_bf16_rne(acc[0], acc[1]), pack_bf16_rne(acc[2], acc[3]),
-                 pack_bf16_rne(acc[4], acc[5]), pack_bf16_rne(acc[6], acc[7])};
-      store_payload((u32x4 *)a.partial + (size_t)pr * nvec + vi, o);
+      store_payload((u32x4 *)a.partial + (size_t)pr * nvec + vi, res[j]);
     }
   } else {
     unsigned long long lm = leaders;
@@ -300,8 +306,10 @@ int launch_combine_partial(const CombinePartialArgs &a0, void *stream) {
   const unsigned grid = (unsigned)((items + 3) / 4);
   hipStream_t st = (hipStream_t)stream;
   switch (a.K) {
+    case 1: hipLaunchKernelGGL(combine_partial_kernel<1>, dim3(grid), dim3(256), 0, st, a); break;
     case 2: hipLaunchKernelGGL(combine_partial_kernel<2>, dim3(grid), dim3(256), 0, st, a); break;
     case 4: hipLaunchKernelGGL(combine_partial_kernel<4>, dim3(grid), dim3(256), 0, st, a); break;
+    case 6: hipLaunchKernelGGL(combine_partial_kernel<6>, dim3(grid), dim3(256), 0, st, a); break;
     case 8: hipLaunchKernelGGL(combine_partial_kernel<8>, dim3(grid), dim3(256), 0, st, a); break;
     default: hipLaunchKernelGGL(combine_partial_kernel<0>, dim3(grid), dim3(256), 0, st, a); break;
   }

@@ -53,6 +53,28 @@ def test_layout_parity(epmod, oracle, cid, T, mask):
         assert r.stats()["device_error"] == 0
 
 
+def test_layout_hand_over_between_workgroups_many_times(epmod, oracle):
+    """The tile histograms cross workgroups through write-through stores, a ticket and cache-bypassing loads (no
+    L2 write-back or invalidate): 300 layouts of the full 4096-token table, each compared on the device with the
+    oracle's arrays, other kernels' dirty lines in the caches in between."""
+    cfg = g.config(4)
+    idx, _ = g.routing_all(cfg)
+    want = {k: _dev(v) for k, v in oracle.layout(idx, cfg.E, cfg.R).items()}
+    noise = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    with _runner(epmod, cfg) as r:
+        d_idx = _dev(idx)
+        bad = torch.zeros((), dtype=torch.int64, device="cuda")
+        for it in range(300):
+            if it % 3 == 0:
+                noise.add_(1)                                    # leaves dirty lines in every L2
+            lay = r.layout(d_idx)
+            for name, v in want.items():
+                bad += (getattr(lay, name) != v).sum()
+        torch.cuda.synchronize()
+        assert int(bad.item()) == 0
+        assert r.stats()["device_error"] == 0
+
+
 def test_layout_special_shapes(epmod, oracle):
     rng = np.random.default_rng(0)
     for (S, T, K, E, R) in [(1, 300, 1, 1, 1), (3, 129, 4, 8, 8), (2, 64, 6, 96, 3), (1, 1000, 8, 1024, 4),
