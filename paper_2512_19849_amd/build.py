@@ -50,5 +50,20 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+PROBE_SRC = os.path.join(HERE, "probes", "mem_patterns.hip")
+PROBE_BIN = os.path.join(HERE, "probes", "mem_patterns")
+
+
+def build_probes(verbose: bool = False) -> str:
+    """The stand-alone access-pattern probe (a measuring program for rocprofv3, not part of the library)."""
+    cmd = [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", PROBE_SRC, "-o", PROBE_BIN]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return PROBE_BIN
+
+
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_probes(verbose=True))
