@@ -31,6 +31,7 @@ Tunables read_tunables() {
   t.dispatch_vpl = env_int("EP_DISPATCH_VPL", t.dispatch_vpl);
   t.dispatch_fp8_vpl = env_int("EP_DISPATCH_FP8_VPL", t.dispatch_fp8_vpl);
   t.per_token_waves = env_int("EP_PER_TOKEN_WAVES", t.per_token_waves);
+  t.dispatch_pipeline = env_int("EP_DISPATCH_PIPELINE", t.dispatch_pipeline);
   t.combine_vpl = env_int("EP_COMBINE_VPL", t.combine_vpl);
   t.layout_small = env_int("EP_LAYOUT_SMALL", t.layout_small);
   t.layout_tpb = env_int("EP_LAYOUT_TPB", t.layout_tpb);

@@ -183,7 +183,10 @@ struct RecvWaitArgs {
 struct Tunables {
   int dispatch_vpl = 0;      // EP_DISPATCH_VPL: 16-byte vectors per lane of a bf16 row
   int dispatch_fp8_vpl = 0;  // EP_DISPATCH_FP8_VPL: 16-channel groups per lane of an FP8 row
-  int per_token_waves = 16;  // EP_PER_TOKEN_WAVES: wavefronts per workgroup of a per-token dispatch
+  int per_token_waves = 0;   // EP_PER_TOKEN_WAVES: data wavefronts per workgroup of a ring-on dispatch (0 = 12);
+                             // in the plain form: wavefronts per workgroup of a per-token dispatch (0 = 16)
+  int dispatch_pipeline = 0; // EP_DISPATCH_PIPELINE: 1 = ring-on dispatches run persistent workgroups with a command
+                             // wave (measured: no faster in chunk mode, slower per token; see the kernel's comment)
   int combine_vpl = 0;       // EP_COMBINE_VPL: 16-byte column slices per lane
   int layout_small = 1;      // EP_LAYOUT_SMALL: 0 keeps small routing tables on the two-kernel form
   int layout_tpb = 4;        // EP_LAYOUT_TPB: tiles per workgroup of the count kernel

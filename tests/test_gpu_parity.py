@@ -187,19 +187,51 @@ def test_dispatch_bf16_other_source_and_rank_filter(epmod, oracle):
     _dispatch_case(epmod, oracle, cfg, 64, 0.0, epmod.EP_CMD_PER_TOKEN, rank_filter=5, src=31)
 
 
+@pytest.mark.parametrize("pipeline", ["1", "0"])
 @pytest.mark.parametrize("vpl", [1, 2, 4, 7, 8, 14, 16])
-def test_dispatch_bf16_every_row_split(epmod, oracle, vpl, monkeypatch):
+def test_dispatch_bf16_every_row_split(epmod, oracle, vpl, pipeline, monkeypatch):
+    """Every way of cutting a row into wavefronts, in the plain form and in the form with a command wave
+    (EP_DISPATCH_PIPELINE=1), with the ring off as well."""
     monkeypatch.setenv("EP_DISPATCH_VPL", str(vpl))
+    monkeypatch.setenv("EP_DISPATCH_PIPELINE", pipeline)
     _dispatch_case(epmod, oracle, g.config(4), 70, 0.05, epmod.EP_CMD_CHUNK32)
     _dispatch_case(epmod, oracle, g.config(1), 33, 0.0, epmod.EP_CMD_PER_TOKEN)
+    if pipeline == "1":
+        _dispatch_case(epmod, oracle, g.config(4), 70, 0.05, epmod.EP_CMD_NONE)
 
 
+@pytest.mark.parametrize("pipeline", ["1", "0"])
+@pytest.mark.parametrize("mode", ["per_token", "chunk32", "ordered"])
+def test_ring_on_dispatch_with_and_without_a_command_wave(epmod, oracle, mode, pipeline, monkeypatch):
+    """With EP_DISPATCH_PIPELINE=1 ring-on dispatches run persistent workgroups whose command wave lags one batch
+    of tokens behind the data waves; the default is the plain form.  Both: payload and command multiset equal the oracle's,
+    with rings of 8 slots (back-pressure reaches the command wave, then the data waves), with more batches than
+    workgroups (14 000 tokens of 128-wide rows, 12 tokens per batch: up to three batches per workgroup, so both
+    LDS slots are reused) and with a Drain at the end."""
+    monkeypatch.setenv("EP_DISPATCH_PIPELINE", pipeline)
+    cm = {"per_token": epmod.EP_CMD_PER_TOKEN, "chunk32": epmod.EP_CMD_CHUNK32,
+          "ordered": epmod.EP_CMD_CHUNK32_ORDERED}[mode]
+    wide = g.EPConfig("narrow_many", T=14000, H=128, E=16, K=3, R=4, seed=77)
+    for cfg, T, entries, extra in ((g.config(4), 900, 4096, 0), (g.config(4), 200, 8, epmod.EP_CMD_DRAIN),
+                                   (wide, None, 64, 0), (g.config(2, S=1), None, 4096, epmod.EP_CMD_DRAIN)):
+        if mode == "ordered" and extra:
+            extra = 0                                           # (the sequenced mode ends with its own Drain)
+        out = _dispatch_case(epmod, oracle, cfg, T, 0.05, cm | extra, ring_entries=entries, spin_timeout_ms=10000)
+        if mode == "ordered":
+            oracle.check_order_trace(out["events"])
+        else:
+            _check_commands(epmod, oracle, cfg, out, mode)
+
+
+@pytest.mark.parametrize("pipeline", ["1", "0"])
 @pytest.mark.parametrize("waves", [4, 8, 16])
-def test_per_token_commands_every_push_form(epmod, oracle, waves, monkeypatch):
+def test_per_token_commands_every_push_form(epmod, oracle, waves, pipeline, monkeypatch):
     """One command per row leaves through the push of the token's own wave (a workgroup that holds one token:
-    lanes of a channel share the tail atomic) or through the workgroup's first wave (several tokens: commands
-    sorted by channel); both must hand the proxy the same multiset of commands, with rings of 8 and of 4096 slots."""
+    lanes of a channel share the tail atomic), through the workgroup's first wave (several tokens: commands
+    sorted by channel) or through the command wave of a persistent workgroup; all must hand the proxy the same
+    multiset of commands, with rings of 8 and of 4096 slots."""
     monkeypatch.setenv("EP_PER_TOKEN_WAVES", str(waves))
+    monkeypatch.setenv("EP_DISPATCH_PIPELINE", pipeline)
     for cid, T, entries in ((4, 70, 4096), (4, 70, 8), (2, None, 64), (1, 33, 8)):
         cfg = g.config(cid)
         out = _dispatch_case(epmod, oracle, cfg, T, 0.05, epmod.EP_CMD_PER_TOKEN, ring_entries=entries)
