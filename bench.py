@@ -495,8 +495,8 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also launch N plain device copies of 1 GiB (counter calibration for rocprofv3 --pmc)")
     ap.add_argument("--suite", action="store_true", help="per-call timings of all five workloads instead")
-    ap.add_argument("--suite-out", default=os.path.join(ROOT, "gpurun_out", "per_call_timings_all_workloads.txt"),
-                    help="where --suite writes its formatted table (copy it to profiles/ to commit it)")
+    ap.add_argument("--suite-out", default=os.path.join(ROOT, "profiles", "per_call_timings_all_workloads.txt"),
+                    help="where --suite writes its formatted table")
     args = ap.parse_args()
     if args.suite and args.gpus == 1:
         return run_suite(args)
