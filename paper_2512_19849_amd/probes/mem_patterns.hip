@@ -56,6 +56,20 @@ __global__ __launch_bounds__(256) void write_interleaved_sequential_streams(u32x
   const unsigned i = blockIdx.x, blk = (i % G) * (unsigned)(kBlocks / G) + i / G;
   store_wt(p + (size_t)blk * 256 + threadIdx.x, u32x4{1u, 2u, 3u, blk});
 }
+// the launch-ordered stream (all 448 MiB) cut into chunks of CHUNK_KIB that sit at bit-reversed positions
+// (inside each seventh of the buffer): inside a chunk the stores arrive in address order as in the plain
+// stream, the chunks themselves are scattered; the position is computed, so no wave waits for a load before
+// it stores
+template <int CHUNK_KIB>
+__global__ __launch_bounds__(256) void write_stream_in_scattered_chunks(u32x4 *p) {
+  constexpr unsigned per = CHUNK_KIB / 4;     // 4 KiB blocks per chunk
+  constexpr unsigned m = 16384u / per;        // chunks per seventh of the buffer (a power of two)
+  const unsigned i = blockIdx.x, c = i / per, j = i % per;
+  const unsigned q = c / m, r = c % m;
+  const unsigned rr = m > 1 ? __brev(r) >> (32 - __builtin_ctz(m)) : 0u;
+  const size_t blk = ((size_t)q * m + rr) * per + j;
+  store_wt(p + blk * 256 + threadIdx.x, u32x4{1u, 2u, 3u, i});
+}
 // ---- rows
 // one workgroup (14 waves) per row, rows in sequential order: globally the same sequential stream as above,
 // but a wave first has to fetch its row number
@@ -67,6 +81,7 @@ __global__ __launch_bounds__(896) void write_rows_in_order_one_row_per_workgroup
 // SRC 0: a constant; 1: the slice is loaded (streaming) from the token's own row of x; 2: loaded with cached
 // loads from one of 1024 token rows (16 MiB: stays in the memory-side cache)
 // ZIPF only names the instance: destination rows in sequential order, or those of a Zipf routing
+// (SRC 0 with the rows of a uniform routing over 8, 32 or 64 experts is launched under its own name below)
 template <int SRC, bool ZIPF>
 __global__ __launch_bounds__(256) void scatter_rows_dispatch_shape(const u32x4 *x, u32x4 *recv, const int *rowmap) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, t = blockIdx.x;
@@ -87,6 +102,22 @@ __global__ __launch_bounds__(256) void scatter_rows_dispatch_shape(const u32x4 *
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (v0 + i * 64 < NV) store_wt(dst + v0 + i * 64, v[i]);
+  }
+}
+// the same stores (constant data) when the tokens' 8 rows go to 8 distinct of E expert regions drawn uniformly:
+// E sequential streams are being written at any time
+template <int E>
+__global__ __launch_bounds__(256) void scatter_rows_into_E_expert_regions(u32x4 *recv, const int *rowmap) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, t = blockIdx.x;
+  const int row = lane < K ? rowmap[t * K + lane] : -1;
+  const int v0 = wave * 256 + lane;
+  const u32x4 v = {1u, 2u, 3u, (unsigned)t};
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    u32x4 *dst = recv + (size_t)__builtin_amdgcn_readlane(row, k) * NV;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (v0 + i * 64 < NV) store_wt(dst + v0 + i * 64, v);
   }
 }
 // ---- reads
@@ -163,6 +194,26 @@ int main(int argc, char **argv) {
     for (long long i = 0; i < kRows; ++i) rm[i] = off[idx[i]] + fill[idx[i]]++;
   }
   CK(hipMemcpy(zipf, rm.data(), kRows * 4, hipMemcpyHostToDevice));
+  // ... and of uniform routings (8 distinct experts per token) over 8, 32, 64 and 256 experts
+  int *uni[4];
+  const int uniE[4] = {8, 32, 64, 256};
+  for (int u = 0; u < 4; ++u) {
+    const int E = uniE[u];
+    std::mt19937 g(11 + u);
+    std::vector<int> idx(kRows), cnt(E, 0), off(E + 1, 0), fill(E, 0), perm(E);
+    for (int t = 0; t < T; ++t) {
+      std::iota(perm.begin(), perm.end(), 0);
+      for (int k = 0; k < K; ++k) {  // partial Fisher-Yates
+        std::swap(perm[k], perm[k + (int)(g() % (unsigned)(E - k))]);
+        idx[t * K + k] = perm[k];
+        cnt[perm[k]]++;
+      }
+    }
+    for (int e = 0; e < E; ++e) off[e + 1] = off[e] + cnt[e];
+    for (long long i = 0; i < kRows; ++i) rm[i] = off[idx[i]] + fill[idx[i]]++;
+    CK(hipMalloc(&uni[u], kRows * 4));
+    CK(hipMemcpy(uni[u], rm.data(), kRows * 4, hipMemcpyHostToDevice));
+  }
 
   auto run = [&](auto launch) {
     for (int i = 0; i < 3 + reps; ++i) launch();
@@ -175,9 +226,19 @@ int main(int argc, char **argv) {
   run([&] { hipLaunchKernelGGL(write_interleaved_sequential_streams<8>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
   run([&] { hipLaunchKernelGGL(write_interleaved_sequential_streams<64>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
   run([&] { hipLaunchKernelGGL(write_interleaved_sequential_streams<256>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
+  run([&] { hipLaunchKernelGGL(write_stream_in_scattered_chunks<4>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
+  run([&] { hipLaunchKernelGGL(write_stream_in_scattered_chunks<16>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
+  run([&] { hipLaunchKernelGGL(write_stream_in_scattered_chunks<64>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
+  run([&] { hipLaunchKernelGGL(write_stream_in_scattered_chunks<256>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
+  run([&] { hipLaunchKernelGGL(write_stream_in_scattered_chunks<1024>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
+  run([&] { hipLaunchKernelGGL(write_stream_in_scattered_chunks<16384>, dim3((unsigned)kBlocks), blk, 0, 0, recv); });
   run([&] { hipLaunchKernelGGL(write_rows_in_order_one_row_per_workgroup, dim3((unsigned)kRows), dim3(896), 0, 0, recv, seq); });
   run([&] { hipLaunchKernelGGL((scatter_rows_dispatch_shape<0, false>), dim3(T), blk, 0, 0, x, recv, seq); });
   run([&] { hipLaunchKernelGGL((scatter_rows_dispatch_shape<0, true>), dim3(T), blk, 0, 0, x, recv, zipf); });
+  run([&] { hipLaunchKernelGGL(scatter_rows_into_E_expert_regions<8>, dim3(T), blk, 0, 0, recv, uni[0]); });
+  run([&] { hipLaunchKernelGGL(scatter_rows_into_E_expert_regions<32>, dim3(T), blk, 0, 0, recv, uni[1]); });
+  run([&] { hipLaunchKernelGGL(scatter_rows_into_E_expert_regions<64>, dim3(T), blk, 0, 0, recv, uni[2]); });
+  run([&] { hipLaunchKernelGGL(scatter_rows_into_E_expert_regions<256>, dim3(T), blk, 0, 0, recv, uni[3]); });
   run([&] { hipLaunchKernelGGL((scatter_rows_dispatch_shape<1, true>), dim3(T), blk, 0, 0, x, recv, zipf); });
   run([&] { hipLaunchKernelGGL((scatter_rows_dispatch_shape<2, true>), dim3(T), blk, 0, 0, x, recv, zipf); });
   run([&] { hipLaunchKernelGGL((read_stream<true, false>), dim3((unsigned)kBlocks), blk, 0, 0, y, sink); });
