@@ -121,11 +121,20 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   }
 }
 
-static int tuned_combine_vpl(int forced) {
-  static const int c[] = {1, 2, 4, 7, 14};
+// Column slices (64 lanes x 16 bytes) per wave.  One slice per wave - fewest registers, most waves in
+// flight - is the general choice.  One WAVE PER TOKEN (all slices of the row, its stores together at the
+// end) is faster by 3-5 us per 450 MB for rows of 9 to 15 slices (hidden 4608..7680) once there are about
+// 1500 tokens or more; it is slower for rows whose size is a power of two (hidden 4096, 8192: every wave is
+// then at the same offset of a row that starts a multiple of that size away, i.e. on the same memory
+// channels at the same time) and for fewer tokens (too few waves).  Measured for hidden 4096..8192 and
+// 1024..8192 tokens, Zipf, softmax and uniform routing.
+static int tuned_combine_vpl(int forced, int H, int T) {
+  static const int c[] = {1, 2, 4, 7, 9, 10, 11, 12, 13, 14, 15};
   for (int v : c)
     if (v == forced) return v;
-  return 1;  // one 16-byte column slice per lane: fewest registers, most waves in flight (measured best)
+  const int slices = (H / 8 + 63) / 64;
+  if (slices >= 9 && slices <= 15 && T >= 1536) return slices;
+  return 1;
 }
 
 template <int VPL>
@@ -149,11 +158,17 @@ int launch_combine(const CombineArgs &a, const Tunables &tune, void *stream, con
   hipStream_t st = (hipStream_t)stream;
   if (a.T <= 0) return 0;
   if ((a.H / 8 + 63) / 64 > 65535) return (int)hipErrorInvalidValue;
-  switch (tuned_combine_vpl(tune.combine_vpl)) {
+  switch (tuned_combine_vpl(tune.combine_vpl, a.H, a.T)) {
     case 2: launch_combine_t<2>(a, st, timing); break;
     case 4: launch_combine_t<4>(a, st, timing); break;
     case 7: launch_combine_t<7>(a, st, timing); break;
+    case 9: launch_combine_t<9>(a, st, timing); break;
+    case 10: launch_combine_t<10>(a, st, timing); break;
+    case 11: launch_combine_t<11>(a, st, timing); break;
+    case 12: launch_combine_t<12>(a, st, timing); break;
+    case 13: launch_combine_t<13>(a, st, timing); break;
     case 14: launch_combine_t<14>(a, st, timing); break;
+    case 15: launch_combine_t<15>(a, st, timing); break;
     default: launch_combine_t<1>(a, st, timing); break;
   }
   return (int)hipGetLastError();

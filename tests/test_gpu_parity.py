@@ -682,7 +682,8 @@ def test_combine_directly_after_dispatch_reads_the_fresh_rows_first(epmod, oracl
         assert r.stats()["device_error"] == 0
 
 
-@pytest.mark.parametrize("K,vpl", [(1, 1), (3, 2), (5, 4), (6, 1), (8, 4), (2, 2), (4, 1)])
+@pytest.mark.parametrize("K,vpl", [(1, 1), (3, 2), (5, 4), (6, 1), (8, 4), (2, 2), (4, 1), (8, 7), (3, 9), (8, 10),
+                                   (2, 11), (4, 12), (5, 13), (8, 14), (6, 15)])
 def test_combine_generic_k_and_splits(epmod, oracle, K, vpl, monkeypatch):
     monkeypatch.setenv("EP_COMBINE_VPL", str(vpl))
     cfg = g.EPConfig("ck", T=90, H=1536, E=24, K=K, R=3, seed=99)
@@ -700,6 +701,25 @@ def test_combine_generic_k_and_splits(epmod, oracle, K, vpl, monkeypatch):
         ob = bf16_to_bits(out)
         assert _combine_check(oracle, ob, y, w[0], lay["dst_row"][0], K) == 0
         assert (ob[5] == 0).all()
+
+
+@pytest.mark.parametrize("H", [4608, 4736, 5120, 5632, 6144, 6656, 7168, 7680, 8192])
+def test_combine_one_wave_per_token_for_mid_sized_rows(epmod, oracle, H):
+    """Rows of 9 to 15 column slices and 1536 tokens or more: the library itself lets one wave reduce a whole
+    token (hidden 4736: a ragged last slice; 8192: 16 slices, the one-slice form stays)."""
+    from paper_2512_19849_amd.runner import bits_to_bf16, bf16_to_bits
+    cfg = g.EPConfig("cw", T=1600, H=H, E=32, K=8, R=4, routing="zipf", seed=1234 + H)
+    idx, w = g.routing_all(cfg)
+    idx = g.mask_random(idx, 0.05, seed=H)
+    lay = oracle.layout(idx, cfg.E, cfg.R)
+    rows = int((idx >= 0).sum())
+    y = g.activations(cfg, 0, tid=g.TID_Y, T=rows)
+    with _runner(epmod, cfg) as r:
+        out = torch.full((cfg.T, cfg.H), 7.0, dtype=torch.bfloat16, device="cuda")
+        r.combine(bits_to_bf16(y), _dev(w[0]), _dev(lay["dst_row"][0]), out)
+        torch.cuda.synchronize()
+        assert _combine_check(oracle, bf16_to_bits(out), y, w[0], lay["dst_row"][0], cfg.K) == 0
+        assert r.stats()["device_error"] == 0
 
 
 def test_round_trip_identity_expert(epmod, oracle):
