@@ -565,6 +565,7 @@ int ep_dispatch(ep_handle *h, const void *d_x, const int32_t *d_topk_idx, const 
     if (mode == EP_CMD_NONE) return EP_OK;
     a.T = 0;
   }
+  a.cache_hinted = h->cache_hints ? 1 : 0;
   if (h->cache_hints && T > 0 && !(cmd_mode & EP_CMD_NO_PLACEMENT)) {
     a.reverse = h->last_recv.load(std::memory_order_relaxed) == d_recv
                     ? !h->last_reverse.load(std::memory_order_relaxed)

@@ -540,6 +540,17 @@ int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, vo
   if (a.T <= 0 && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_NONE) return 0;
   if (payload == EP_BF16) {
     int vpl = tuned_dispatch_vpl(a.H, a.T, tune.dispatch_vpl);
+    // Rows that exceed the memory-side cache (256 MB) by half or more have to stream to HBM while the kernel
+    // runs; then ONE slice per wave (many small waves, eight 1 KiB stores each) is faster by 5-10 us per
+    // 450-900 MB than four slices per wave, which wins below that size by as much (measured for 224 to 896
+    // MiB of rows, hidden 4096..8192) - and also where the caller has said that the rows are consumed in
+    // place, out of that cache.  Per-token commands keep their shape: their pushes are made per workgroup of
+    // several tokens.
+    const long long row_bytes_all = (long long)a.T * a.K * a.H * 2;
+    if (!tune.dispatch_vpl && !tune.dispatch_pipeline && !a.cache_hinted &&
+        (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_PER_TOKEN &&
+        row_bytes_all >= 384000000ll && (a.H / 8 + 63) / 64 <= 16)
+      vpl = 1;
     // (7 and 8 vectors per lane make the compiler spill in the form with a command wave: rows that wide take 14 / 16)
     if ((a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE && tune.dispatch_pipeline && (vpl == 7 || vpl == 8)) vpl *= 2;
     if ((a.H / 8 + vpl * 64 - 1) / (vpl * 64) > 16) return (int)hipErrorInvalidValue;

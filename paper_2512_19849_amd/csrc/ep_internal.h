@@ -71,6 +71,7 @@ struct DispatchArgs {
   int32_t tokens_per_block;
   int32_t block_cmds;      // the workgroup's first wave pushes the commands of all its tokens
   int32_t reverse;         // workgroups take the tokens from the last one down (see ep_dispatch)
+  int32_t cache_hinted;    // the caller promised (EP_FLAG_CACHE_HINTS) that the rows are consumed out of the caches
   int32_t msg_rows;        // FP8 only: 0 = codes and scales go to the two receive arrays; 1 = every row is one message
                            // (codes, scales, padding: row_bytes) at its destination row of `recv`; 2 = one message
                            // per token at row t of `recv` (the proxy forwards it to every destination)
