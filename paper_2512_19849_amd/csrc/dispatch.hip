@@ -544,11 +544,13 @@ int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, vo
     // runs; then ONE slice per wave (many small waves, eight 1 KiB stores each) is faster by 5-10 us per
     // 450-900 MB than four slices per wave, which wins below that size by as much (measured for 224 to 896
     // MiB of rows, hidden 4096..8192) - and also where the caller has said that the rows are consumed in
-    // place, out of that cache.  Per-token commands keep their shape: their pushes are made per workgroup of
-    // several tokens.
+    // place, out of that cache.  Per-token commands keep their shape (their pushes are made per workgroup of
+    // several tokens), and so does the sequenced chunk mode (bound by its hottest channel's FIFO; measured
+    // slower with the small waves on the skewed workload).
     const long long row_bytes_all = (long long)a.T * a.K * a.H * 2;
+    const int cmds = a.cmd_mode & EP_CMD_MODE_MASK;
     if (!tune.dispatch_vpl && !tune.dispatch_pipeline && !a.cache_hinted &&
-        (a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_PER_TOKEN &&
+        (cmds == EP_CMD_NONE || cmds == EP_CMD_CHUNK32) &&
         row_bytes_all >= 384000000ll && (a.H / 8 + 63) / 64 <= 16)
       vpl = 1;
     // (7 and 8 vectors per lane make the compiler spill in the form with a command wave: rows that wide take 14 / 16)
