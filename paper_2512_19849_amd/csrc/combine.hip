@@ -123,17 +123,19 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
 
 // Column slices (64 lanes x 16 bytes) per wave.  One slice per wave - fewest registers, most waves in
 // flight - is the general choice.  One WAVE PER TOKEN (all slices of the row, its stores together at the
-// end) is faster by 3-5 us per 450 MB for rows of 9 to 15 slices (hidden 4608..7680) once there are about
-// 1500 tokens or more; it is slower for rows whose size is a power of two (hidden 4096, 8192: every wave is
-// then at the same offset of a row that starts a multiple of that size away, i.e. on the same memory
-// channels at the same time) and for fewer tokens (too few waves).  Measured for hidden 4096..8192 and
-// 1024..8192 tokens, Zipf, softmax and uniform routing.
-static int tuned_combine_vpl(int forced, int H, int T) {
+// end) is faster by 3-5 us per 450 MB for rows of 9 to 15 slices (hidden 4608..7680) when the rows to read
+// exceed the memory-side cache (256 MB) by half or more; it is slower for rows whose size is a power of two
+// (hidden 4096, 8192: every wave is then at the same offset of a row that starts a multiple of that size
+// away, i.e. on the same memory channels at the same time), and mixed below that amount of rows (few tokens:
+// too few waves; a sparse table such as the second level of the hierarchical reduce: slower).  Measured for
+// hidden 4096..8192, 1024..8192 tokens, Zipf, softmax and uniform routing.
+static int tuned_combine_vpl(int forced, const CombineArgs &a) {
   static const int c[] = {1, 2, 4, 7, 9, 10, 11, 12, 13, 14, 15};
   for (int v : c)
     if (v == forced) return v;
-  const int slices = (H / 8 + 63) / 64;
-  if (slices >= 9 && slices <= 15 && T >= 1536) return slices;
+  const int slices = (a.H / 8 + 63) / 64;
+  const long long rows = (long long)a.T * a.K < a.y_rows ? (long long)a.T * a.K : a.y_rows;
+  if (slices >= 9 && slices <= 15 && rows * a.H * 2 >= 384000000ll) return slices;
   return 1;
 }
 
@@ -158,7 +160,7 @@ int launch_combine(const CombineArgs &a, const Tunables &tune, void *stream, con
   hipStream_t st = (hipStream_t)stream;
   if (a.T <= 0) return 0;
   if ((a.H / 8 + 63) / 64 > 65535) return (int)hipErrorInvalidValue;
-  switch (tuned_combine_vpl(tune.combine_vpl, a.H, a.T)) {
+  switch (tuned_combine_vpl(tune.combine_vpl, a)) {
     case 2: launch_combine_t<2>(a, st, timing); break;
     case 4: launch_combine_t<4>(a, st, timing); break;
     case 7: launch_combine_t<7>(a, st, timing); break;

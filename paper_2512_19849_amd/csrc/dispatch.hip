@@ -547,7 +547,8 @@ int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, vo
     // place, out of that cache.  Per-token commands keep their shape (their pushes are made per workgroup of
     // several tokens), and so does the sequenced chunk mode (bound by its hottest channel's FIFO; measured
     // slower with the small waves on the skewed workload).
-    const long long row_bytes_all = (long long)a.T * a.K * a.H * 2;
+    const long long rows_at_most = (long long)a.T * a.K < a.recv_rows ? (long long)a.T * a.K : a.recv_rows;
+    const long long row_bytes_all = rows_at_most * a.H * 2;
     const int cmds = a.cmd_mode & EP_CMD_MODE_MASK;
     if (!tune.dispatch_vpl && !tune.dispatch_pipeline && !a.cache_hinted &&
         (cmds == EP_CMD_NONE || cmds == EP_CMD_CHUNK32) &&
