@@ -97,7 +97,8 @@ enum ep_flags {
                               the 256 MB memory-side cache: ep_combine then reads those rows first and with
                               cached loads (EP_COMBINE_FRESH_MB MiB worth at ep_proxy_start, default 224), and a
                               dispatch into the buffer of the previous dispatch hands the tokens to its
-                              workgroups from the other end of the token range.  Without the flag every
+                              workgroups from the other end of the token range (and keeps the launch shape that
+                              suits rows consumed out of that cache, whatever their volume).  Without the flag every
                               dispatch walks the tokens in ascending order and every combine reads all rows
                               with streaming loads, whatever ran before it. */
 };
