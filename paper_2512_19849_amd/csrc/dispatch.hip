@@ -547,6 +547,12 @@ int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, vo
     // place, out of that cache.  Per-token commands keep their shape (their pushes are made per workgroup of
     // several tokens), and so does the sequenced chunk mode (bound by its hottest channel's FIFO; measured
     // slower with the small waves on the skewed workload).
+    // One command per row: two 1 KiB slices per wave (rows of up to 8192 channels then still put two tokens
+    // into a workgroup, whose first wave pushes for both) beat four by 3-9 us per dispatch, measured for
+    // hidden 5120..8192 and 2048..8192 tokens.
+    if (!tune.dispatch_vpl && !tune.dispatch_pipeline && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_PER_TOKEN &&
+        !(a.cmd_mode & EP_CMD_NO_PLACEMENT) && vpl > 2 && (a.H / 8 + 127) / 128 <= 8)
+      vpl = 2;
     const long long rows_at_most = (long long)a.T * a.K < a.recv_rows ? (long long)a.T * a.K : a.recv_rows;
     const long long row_bytes_all = rows_at_most * a.H * 2;
     const int cmds = a.cmd_mode & EP_CMD_MODE_MASK;
