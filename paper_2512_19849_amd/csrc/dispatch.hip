@@ -540,25 +540,24 @@ int launch_dispatch(const DispatchArgs &a, int payload, const Tunables &tune, vo
   if (a.T <= 0 && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_NONE) return 0;
   if (payload == EP_BF16) {
     int vpl = tuned_dispatch_vpl(a.H, a.T, tune.dispatch_vpl);
-    // Rows that exceed the memory-side cache (256 MB) by half or more have to stream to HBM while the kernel
-    // runs; then ONE slice per wave (many small waves, eight 1 KiB stores each) is faster by 5-10 us per
-    // 450-900 MB than four slices per wave, which wins below that size by as much (measured for 224 to 896
-    // MiB of rows, hidden 4096..8192) - and also where the caller has said that the rows are consumed in
-    // place, out of that cache.  Per-token commands keep their shape (their pushes are made per workgroup of
-    // several tokens), and so does the sequenced chunk mode (bound by its hottest channel's FIFO; measured
-    // slower with the small waves on the skewed workload).
+    const int cmds = a.cmd_mode & EP_CMD_MODE_MASK;
+    const bool free_choice = !tune.dispatch_vpl && !tune.dispatch_pipeline;
     // One command per row: two 1 KiB slices per wave (rows of up to 8192 channels then still put two tokens
     // into a workgroup, whose first wave pushes for both) beat four by 3-9 us per dispatch, measured for
-    // hidden 5120..8192 and 2048..8192 tokens.
-    if (!tune.dispatch_vpl && !tune.dispatch_pipeline && (a.cmd_mode & EP_CMD_MODE_MASK) == EP_CMD_PER_TOKEN &&
+    // hidden 5120..8192 and 2048..8192 tokens.  The sequenced chunk mode gains 2-6 us from the same shape at
+    // 4096 tokens (hidden 5120..8192) and nothing at 8192.
+    if (free_choice && (cmds == EP_CMD_PER_TOKEN || cmds == EP_CMD_CHUNK32_ORDERED) &&
         !(a.cmd_mode & EP_CMD_NO_PLACEMENT) && vpl > 2 && (a.H / 8 + 127) / 128 <= 8)
       vpl = 2;
+    // Ring off or plain chunk commands: rows that exceed the memory-side cache (256 MB) by half or more have to
+    // stream to HBM while the kernel runs; then ONE slice per wave (many small waves, eight 1 KiB stores each)
+    // is faster by 5-10 us per 450-900 MB than four slices per wave, which wins below that size by as much
+    // (measured for 224 to 896 MiB of rows, hidden 4096..8192) - and also where the caller has said that the
+    // rows are consumed in place, out of that cache.  (The sequenced chunk mode, bound by its hottest channel's
+    // FIFO, was measured slower with one slice per wave on the skewed workload.)
     const long long rows_at_most = (long long)a.T * a.K < a.recv_rows ? (long long)a.T * a.K : a.recv_rows;
-    const long long row_bytes_all = rows_at_most * a.H * 2;
-    const int cmds = a.cmd_mode & EP_CMD_MODE_MASK;
-    if (!tune.dispatch_vpl && !tune.dispatch_pipeline && !a.cache_hinted &&
-        (cmds == EP_CMD_NONE || cmds == EP_CMD_CHUNK32) &&
-        row_bytes_all >= 384000000ll && (a.H / 8 + 63) / 64 <= 16)
+    if (free_choice && !a.cache_hinted && (cmds == EP_CMD_NONE || cmds == EP_CMD_CHUNK32) &&
+        rows_at_most * a.H * 2 >= 384000000ll && (a.H / 8 + 63) / 64 <= 16)
       vpl = 1;
     // (7 and 8 vectors per lane make the compiler spill in the form with a command wave: rows that wide take 14 / 16)
     if ((a.cmd_mode & EP_CMD_MODE_MASK) != EP_CMD_NONE && tune.dispatch_pipeline && (vpl == 7 || vpl == 8)) vpl *= 2;
