@@ -95,6 +95,9 @@ wait for the posted counters, combine), host clock over 30 steps queued back to 
 (four launches per step through Python) and replayed from a HIP graph (ep_captured / ep_expect).
 "proxy_writes_*": heaps registered (ep_register_heaps), the proxy threads move the rows with batched copy
 kernels on the proxy's stream and release arrival notices when a batch has completed; same host clock.
+"*_rings_sized_for_the_dispatch": the same per-token dispatches on a handle whose rings hold all commands of one
+dispatch (ring_entries as listed; every other section uses the default of 4096 slots per channel, which the two
+large workloads overrun, so that producers wait for the proxy there).
 "inbound_share_*" (the 32-source decode workload): the rows the other 31 source ranks send into this rank's
 partition, 31 ep_dispatch calls with a rank filter queued back to back, event to event; "send_share" is this
 rank's own dispatch to all 32 ranks.
@@ -332,6 +335,28 @@ def run_suite(args) -> int:
                     del send
                 res[key] = rr
         if cid in (4, 5):
+            # per-token commands again, with rings that hold a whole dispatch's commands (twice a channel's fair
+            # share of them), so that no producer has to wait for the proxy to make room
+            big = 1 << max(12, int(np.ceil(np.log2(2.0 * rows / 8))))
+            with EPRunner(R, E, K, H, T, S=S, num_channels=8, num_proxy_threads=4, ring_entries=big,
+                          spin_timeout_ms=10000) as rb:
+                layb = rb.layout(d_idx)
+                rr = {"ring_entries_per_channel": big}
+                for label, src_heap, flag in (("per_token", None, 0), ("proxy_writes_per_token", d_x, ep.EP_CMD_NO_PLACEMENT)):
+                    if src_heap is not None:
+                        rb.register_heaps(src_heap, recv)
+                    e2e = []
+                    for _ in range(13):
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        rb.dispatch(d_x, d_idx[0], layb, recv, cmd_mode=ep.EP_CMD_PER_TOKEN | flag)
+                        rb.wait()
+                        e2e.append((time.perf_counter() - t0) * 1e6)
+                    e2e = sorted(e2e[3:])
+                    rr[f"{label}_launch_to_last_counter_us"] = round(e2e[len(e2e) // 2], 1)
+                rr["gpu_ring_full"] = rb.stats()["gpu_ring_full"]
+                rb.register_heaps(None, None)
+                res["threads4_channels8_rings_sized_for_the_dispatch"] = rr
             # high-throughput mode: one copy per (token, group), partial reduce per group, final reduce
             for G in ((1, 8) if cid == 4 else (1,)):
                 NG = R // G
