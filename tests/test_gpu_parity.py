@@ -994,7 +994,10 @@ def test_device_side_bounds_check_reports_instead_of_faulting(epmod, oracle):
 @pytest.mark.parametrize("cid,payload,mode,threads", [(4, "bf16", "chunk32", 4), (4, "bf16", "per_token", 4),
                                                       (5, "bf16", "chunk32", 4), (5, "fp8", "chunk32", 1),
                                                       (5, "fp8", "per_token", 4), (4, "fp8", "chunk32", 4),
-                                                      (4, "bf16", "chunk32_ordered", 4)])
+                                                      (4, "bf16", "chunk32_ordered", 4), (5, "bf16", "per_token", 4),
+                                                      (5, "bf16", "chunk32_ordered", 4), (4, "fp8", "per_token", 4),
+                                                      (4, "fp8", "chunk32_ordered", 4), (5, "fp8", "chunk32_ordered", 4),
+                                                      (4, "bf16", "per_token", 1)])
 def test_full_size_round_trip(epmod, oracle, cid, payload, mode, threads):
     """The whole path at the workload's full size, element by element, with the
     launch configuration bench.py times (8 channels x 4096 slots)."""
@@ -1047,6 +1050,41 @@ def test_full_size_round_trip(epmod, oracle, cid, payload, mode, threads):
             else:
                 assert st["atomics_applied"] == cfg.E
                 assert np.array_equal(r.counters()[0], want["count"][0])
+    finally:
+        oracle.set_threads(1)
+
+
+@pytest.mark.parametrize("cid,payload", [(4, "bf16"), (5, "bf16"), (4, "fp8"), (5, "fp8")])
+def test_full_size_ring_off_dispatch(epmod, oracle, cid, payload):
+    """The ring-off dispatch at the workload's full size (the shape the timing suite launches: no proxy threads
+    needed, no commands), element by element."""
+    from paper_2512_19849_amd.runner import EPRunner, bits_to_bf16, bf16_to_bits
+    cfg = g.config(cid, S=1)
+    idx, _ = g.routing_all(cfg)
+    x = g.activations(cfg)
+    rows = idx.size
+    oracle.set_threads(min(16, oracle.max_threads()))
+    try:
+        want = oracle.layout(idx, cfg.E, cfg.R)
+        with EPRunner(cfg.R, cfg.E, cfg.K, cfg.H, cfg.T, num_proxy_threads=4, spin_timeout_ms=10000) as r:
+            d_idx, d_x = _dev(idx), bits_to_bf16(x)
+            lay = r.layout(d_idx)
+            if payload == "bf16":
+                recv = torch.full((rows, cfg.H), -1.5, dtype=torch.bfloat16, device="cuda")
+                r.dispatch(d_x, d_idx[0], lay, recv, cmd_mode=epmod.EP_CMD_NONE)
+                torch.cuda.synchronize()
+                wrecv, _ = oracle.dispatch_bf16(x, idx[0], want["dst_row"][0], cfg.E_loc, rows)
+                assert np.array_equal(bf16_to_bits(recv), wrecv)
+            else:
+                rq = torch.full((rows, cfg.H), 0x55, dtype=torch.uint8, device="cuda")
+                rs = torch.full((rows, cfg.H // 128), -1.0, dtype=torch.float32, device="cuda")
+                r.dispatch(d_x, d_idx[0], lay, rq, rs, payload=epmod.EP_FP8_E4M3, cmd_mode=epmod.EP_CMD_NONE)
+                torch.cuda.synchronize()
+                wq, ws, _ = oracle.dispatch_fp8(x, idx[0], want["dst_row"][0], cfg.E_loc, rows)
+                assert np.array_equal(rq.cpu().numpy(), wq)
+                assert np.array_equal(rs.cpu().numpy().view(np.uint32), ws.view(np.uint32))
+            st = r.stats()
+            assert st["device_error"] == 0 and st["cmds"] == 0
     finally:
         oracle.set_threads(1)
 
