@@ -1255,7 +1255,8 @@ def test_ht_dedup_parity(epmod, oracle, cid, G, T, mask):
                                                (4, 1, 600, 0.0, "chunk32"), (4, 8, 600, 0.1, "chunk32"),
                                                (5, 4, 500, 0.0, "per_token"), (4, 1, 4096, 0.0, "chunk32"),
                                                (4, 8, 600, 0.1, "ring"), (4, 1, 4096, 0.0, "ring"),
-                                               (1, 2, None, 0.25, "ring")])
+                                               (1, 2, None, 0.25, "ring"), (4, 8, 4096, 0.0, "chunk32"),
+                                               (5, 1, 8192, 0.0, "chunk32")])
 def test_ht_round_trip(epmod, oracle, cid, G, T, mask, mode):
     """dedup -> group-level layout and dispatch (second handle) -> per-expert index
     list -> expert outputs -> partial reduce per group -> final reduce."""
@@ -1592,7 +1593,8 @@ def test_ht_ring_dispatch_of_several_sources(epmod, oracle):
             assert np.array_equal(tail[s], per + np.zeros_like(tail[s])) and np.array_equal(head[s], tail[s])
 
 
-@pytest.mark.parametrize("cid,slices,W", [(4, 128, 2), (5, 64, 4), (4, 1024, 1)])
+@pytest.mark.parametrize("cid,slices,W", [(4, 128, 2), (5, 64, 4), (4, 1024, 1), (4, 128, 4), (4, 256, 2), (5, 128, 2),
+                                          (5, 128, 4), (5, 256, 2)])
 def test_ht_ring_dispatch_full_size(epmod, oracle, cid, slices, W):
     """The full prefill-sized workloads through the rings, in the shape the timing suite launches; the last case
     has four times more workgroups than the chip holds at once (a workgroup depends on no other workgroup)."""
