@@ -1089,7 +1089,8 @@ def test_full_size_ring_off_dispatch(epmod, oracle, cid, payload):
         oracle.set_threads(1)
 
 
-@pytest.mark.parametrize("cid,mode", [(4, "per_token"), (4, "chunk32"), (4, "chunk32_ordered"), (5, "per_token")])
+@pytest.mark.parametrize("cid,mode", [(4, "per_token"), (4, "chunk32"), (4, "chunk32_ordered"), (5, "per_token"),
+                                      (5, "chunk32"), (5, "chunk32_ordered")])
 def test_full_size_proxy_performed_writes(epmod, oracle, cid, mode):
     """Registered heaps at the workload's full size, in the shape the timing suite launches (4 proxy threads,
     8 channels x 4096 slots, no logs): the kernel only pushes commands (per token, straight out of x) or packs a
