@@ -86,6 +86,10 @@ its rows, whatever ran before it.
 "warm": calls queued back to back.  Small workloads are launch-latency bound there (the host cannot
 queue them faster than ~15 us apart); "cold": a 512 MiB fill runs before every call, which also keeps the
 queue busy, so those figures are the kernel itself with cold caches.
+Ring-on dispatches ("dispatch_*_per_token_us", "_chunk32_us", "_chunk32_ordered_us") are each followed by ep_wait
+before the next call, so the GPU idles for some tens of microseconds between them: these figures read about
+10 us higher than the same kernel inside a step (the headline's dispatch with chunk commands: 105 us, see
+kernel_stats_cfg4_prefill_bf16_chunk32.txt).
 "*_kernel_us": the kernels' own duration from their begin / end timestamps (ep_profile), mean of 16 warm launches.
 "launch->last counter": host clock from the ep_dispatch call to ep_wait returning (all completion counters
 posted by the proxy).  "proxy rate": commands / (last atomic applied - first command polled), proxy-side clocks.
